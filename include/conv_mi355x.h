@@ -1,0 +1,134 @@
+/*
+ * conv_mi355x.h -- C ABI of the MI355X (gfx950) direct-convolution library.
+ *
+ * The three training passes of a 2-D convolution layer, after "Anatomy Of
+ * High-Performance Deep Learning Convolutions On SIMD Architectures"
+ * (Section II): forward (Algorithm 1), backward by data (Algorithm 6) and
+ * weight-gradient update (Algorithm 8), computed directly (no im2col buffer)
+ * over channel-blocked tensors (Section II-B, Algorithm 2), with padding added:
+ *
+ *   input position of output (oj,oi), tap (r,s):  ij = stride*oj - pad + r,
+ *                                                 ii = stride*oi - pad + s,
+ *   terms whose (ij,ii) lies outside the image are zero;
+ *   P = floor((H + 2 pad - R)/stride) + 1,  Q likewise.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers, 16-byte aligned, allocated and
+ *     owned by the caller.  The library never allocates or frees device
+ *     memory and keeps no pointer after a call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise.  Errors raised by the
+ *     device asynchronously surface at the caller's next synchronisation.
+ *   - Outputs are overwritten (the "+=" of the printed loops starts from 0).
+ *   - A handle owns only a host-side plan.  One handle may be used from one
+ *     host thread at a time.
+ *   - Every function returns a conv_status_t; nothing is ever computed by
+ *     another library or on the host as a fallback.
+ *
+ * Blocked layouts (v = 16 bytes / element size: 4 for fp32, 8 for bf16; the
+ * role the paper's VLEN plays for a 512-bit SIMD register is played here by
+ * the 128-bit per-lane vector that feeds one MFMA operand):
+ *   activations   X[N][Cb][H][W][v]        Cb = ceil(C / v), channel c lives in
+ *                                          block c / v at slot c % v; slots
+ *                                          beyond C hold zeros
+ *   weights       Wb[Cb][R][S][Kp][v]      Kp = K rounded up to v; element
+ *                                          (k, c, r, s) at [c/v][r][s][k][c%v]
+ *   weight grads  same index structure as Wb, element type always fp32
+ * Callers should not hard-code these; conv_query reports sizes, and the pack /
+ * unpack entry points convert from and to the logical layouts I[N][C][H][W],
+ * W[K][C][R][S], O[N][K][P][Q] of Section II.
+ */
+#ifndef CONV_MI355X_H
+#define CONV_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CONV_F32 = 0,  /* fp32 tensors, fp32 MFMA accumulation                      */
+    CONV_BF16 = 1  /* bf16 activations/weights/gradients, fp32 accumulation,
+                      bf16 outputs for fwd/bwd_data, fp32 weight gradients      */
+} conv_dtype_t;
+
+typedef enum {
+    CONV_OK = 0,
+    CONV_EINVAL = 1,       /* NULL pointer, non-positive extent, negative pad,
+                              empty output, unknown dtype, misaligned pointer  */
+    CONV_EUNSUPPORTED = 2, /* valid problem the kernels cannot run             */
+    CONV_EWORKSPACE = 3,   /* workspace required but ws == NULL                */
+    CONV_ELAUNCH = 4       /* the HIP runtime refused a launch                 */
+} conv_status_t;
+
+/* Problem statement (Section II notation).  One stride and one pad for both
+ * spatial axes; no dilation, groups or bias (the paper has none). */
+typedef struct {
+    int32_t N, C, K, H, W, R, S, stride, pad;
+    int32_t dtype; /* conv_dtype_t */
+} conv_desc_t;
+
+typedef struct {
+    int32_t P, Q;           /* output extent                                  */
+    int32_t vlen;           /* v above                                         */
+    int32_t Cb, Kb;         /* channel blocks of the input / output tensors    */
+    int32_t Cp, Kp;         /* C, K rounded up to vlen                         */
+    size_t in_bytes;        /* blocked I / dI                                  */
+    size_t out_bytes;       /* blocked O / dO                                  */
+    size_t wt_bytes;        /* blocked W                                       */
+    size_t dwt_bytes;       /* blocked dW (fp32)                               */
+    size_t workspace_bytes; /* max over the three passes; may be 0             */
+    int32_t upd_splits;     /* partial dW copies summed by conv_upd            */
+    int32_t reserved;
+} conv_info_t;
+
+typedef struct conv_plan *conv_handle_t;
+
+/* Host only: validate the descriptor and plan tile shapes, grids and the
+ * weight-update split (everything the paper does once per layer at set-up). */
+conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
+conv_status_t conv_destroy(conv_handle_t h);
+conv_status_t conv_query(conv_handle_t h, conv_info_t *info);
+const char *conv_status_str(conv_status_t s);
+
+/* Algorithm 1 with padding:  out[n,k,oj,oi] = sum_{c,r,s} in[n,c,ij,ii] * wt[k,c,r,s].
+ * in: blocked I; wt: blocked W; out: blocked O (fully overwritten, padded
+ * channel slots written as zero).  ws unused (may be NULL). */
+conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out,
+                       void *ws, void *stream);
+
+/* Algorithm 6 with padding:  din[n,c,ij,ii] = sum_{k,r,s} dout[n,k,oj,oi] * wt[k,c,r,s]
+ * over all (oj,r), (oi,s) that map to (ij,ii); positions no term maps to are 0.
+ * dout: blocked dO; wt: blocked W (the same buffer conv_fwd takes); din: blocked
+ * dI, fully overwritten.  ws: workspace_bytes of scratch (holds the transposed,
+ * tap-flipped weights of the duality of Section II-H). */
+conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, void *din,
+                            void *ws, void *stream);
+
+/* Algorithm 8 with padding:  dwt[k,c,r,s] = sum_{n,oj,oi} in[n,c,ij,ii] * dout[n,k,oj,oi].
+ * in: blocked I; dout: blocked dO; dwt: blocked dW, fp32, fully overwritten.
+ * ws: workspace_bytes of scratch (partial dW copies over slices of the
+ * minibatch/pixel range, summed in a fixed order: results are deterministic). */
+conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *dwt,
+                       void *ws, void *stream);
+
+/* Layout conversion, pure permutations in the tensor's own element type
+ * (dW: fp32).  "nchw"/"kcrs" are the logical layouts, "blk" the blocked ones. */
+conv_status_t conv_pack_in(conv_handle_t h, const void *nchw, void *blk, void *stream);
+conv_status_t conv_pack_out(conv_handle_t h, const void *nkpq, void *blk, void *stream);
+conv_status_t conv_pack_wt(conv_handle_t h, const void *kcrs, void *blk, void *stream);
+conv_status_t conv_unpack_in(conv_handle_t h, const void *blk, void *nchw, void *stream);
+conv_status_t conv_unpack_out(conv_handle_t h, const void *blk, void *nkpq, void *stream);
+conv_status_t conv_unpack_wt(conv_handle_t h, const void *blk, void *kcrs, void *stream);
+conv_status_t conv_unpack_dwt(conv_handle_t h, const void *blk_f32, void *kcrs_f32, void *stream);
+
+/* Name, launch geometry and dynamic LDS bytes of the kernel a pass would
+ * launch (pass: 0 fwd, 1 bwd_data, 2 upd); for benchmarks and profiles. */
+conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buflen);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV_MI355X_H */

@@ -1,0 +1,257 @@
+"""Thin ctypes binding over libconv_mi355x.so (the C ABI of include/conv_mi355x.h).
+
+Argument marshalling only: every step of the convolution runs in the HIP
+kernels of the library.  torch is used for device memory and streams.  If the
+library is not built this module raises; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconv_mi355x.so")
+
+CONV_F32 = 0
+CONV_BF16 = 1
+PASS_FWD, PASS_BWD_DATA, PASS_UPD = 0, 1, 2
+
+CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5)
+
+EXPORTS = (
+    "conv_create", "conv_destroy", "conv_query", "conv_status_str",
+    "conv_fwd", "conv_bwd_data", "conv_upd",
+    "conv_pack_in", "conv_pack_out", "conv_pack_wt",
+    "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
+    "conv_describe",
+)
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C", "K", "H", "W", "R", "S", "stride", "pad", "dtype")]
+
+
+class ConvInfo(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("vlen", ctypes.c_int32),
+                ("Cb", ctypes.c_int32), ("Kb", ctypes.c_int32),
+                ("Cp", ctypes.c_int32), ("Kp", ctypes.c_int32),
+                ("in_bytes", ctypes.c_size_t), ("out_bytes", ctypes.c_size_t),
+                ("wt_bytes", ctypes.c_size_t), ("dwt_bytes", ctypes.c_size_t),
+                ("workspace_bytes", ctypes.c_size_t),
+                ("upd_splits", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s" % (what, status_str(status)))
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library (after torch, so both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libconv_mi355x.so is not built; run `python -m paper_1808_05567_amd.build` "
+            "(there is no fallback implementation)")
+    try:
+        import torch  # noqa: F401  (loads libamdhip64 first)
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.conv_create.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(vp)]
+    lib.conv_destroy.argtypes = [vp]
+    lib.conv_query.argtypes = [vp, ctypes.POINTER(ConvInfo)]
+    lib.conv_status_str.argtypes = [ctypes.c_int]
+    lib.conv_status_str.restype = ctypes.c_char_p
+    for name in ("conv_fwd", "conv_bwd_data", "conv_upd"):
+        getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp]
+    for name in ("conv_pack_in", "conv_pack_out", "conv_pack_wt", "conv_unpack_in",
+                 "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt"):
+        getattr(lib, name).argtypes = [vp, vp, vp, vp]
+    lib.conv_describe.argtypes = [vp, ctypes.c_int32, ctypes.c_char_p, ctypes.c_size_t]
+    for name in EXPORTS:
+        if name != "conv_status_str":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_str(status: int) -> str:
+    return load().conv_status_str(int(status)).decode()
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, or an int/None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status, what):
+    if status != CONV_OK:
+        raise ConvError(status, what)
+
+
+def conv_create(N, C, K, H, W, R, S, stride, pad, dtype=CONV_F32):
+    d = ConvDesc(N, C, K, H, W, R, S, stride, pad, dtype)
+    h = ctypes.c_void_p()
+    _check(load().conv_create(ctypes.byref(d), ctypes.byref(h)), "conv_create")
+    return h
+
+
+def conv_destroy(h):
+    _check(load().conv_destroy(h), "conv_destroy")
+
+
+def conv_query(h) -> ConvInfo:
+    info = ConvInfo()
+    _check(load().conv_query(h, ctypes.byref(info)), "conv_query")
+    return info
+
+
+def conv_describe(h, which: int) -> str:
+    buf = ctypes.create_string_buffer(512)
+    _check(load().conv_describe(h, which, buf, 512), "conv_describe")
+    return buf.value.decode()
+
+
+def conv_fwd(h, inp, wt, out, ws=None, stream=None):
+    _check(load().conv_fwd(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(ws), _stream(stream)), "conv_fwd")
+
+
+def conv_bwd_data(h, dout, wt, din, ws, stream=None):
+    _check(load().conv_bwd_data(h, _ptr(dout), _ptr(wt), _ptr(din), _ptr(ws), _stream(stream)),
+           "conv_bwd_data")
+
+
+def conv_upd(h, inp, dout, dwt, ws, stream=None):
+    _check(load().conv_upd(h, _ptr(inp), _ptr(dout), _ptr(dwt), _ptr(ws), _stream(stream)),
+           "conv_upd")
+
+
+def _perm(name):
+    def f(h, src, dst, stream=None):
+        _check(getattr(load(), name)(h, _ptr(src), _ptr(dst), _stream(stream)), name)
+    f.__name__ = name
+    return f
+
+
+conv_pack_in = _perm("conv_pack_in")
+conv_pack_out = _perm("conv_pack_out")
+conv_pack_wt = _perm("conv_pack_wt")
+conv_unpack_in = _perm("conv_unpack_in")
+conv_unpack_out = _perm("conv_unpack_out")
+conv_unpack_wt = _perm("conv_unpack_wt")
+conv_unpack_dwt = _perm("conv_unpack_dwt")
+
+
+class ConvLayer:
+    """Convenience holder: a handle plus torch device buffers of the sizes
+    conv_query reports.  Logical tensors go in and come out as torch tensors in
+    NCHW / KCRS; all computation and all layout conversion is done by the
+    library's kernels."""
+
+    def __init__(self, N, C, K, H, W, R, S, stride, pad, dtype=CONV_F32, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.shape = (N, C, K, H, W, R, S, stride, pad)
+        self.dtype = dtype
+        self.tdtype = torch.bfloat16 if dtype == CONV_BF16 else torch.float32
+        self.device = torch.device(device)
+        self.h = conv_create(N, C, K, H, W, R, S, stride, pad, dtype)
+        self.info = conv_query(self.h)
+        es = 2 if dtype == CONV_BF16 else 4
+        i = self.info
+        self.in_blk = torch.empty(i.in_bytes // es, dtype=self.tdtype, device=self.device)
+        self.out_blk = torch.empty(i.out_bytes // es, dtype=self.tdtype, device=self.device)
+        self.wt_blk = torch.empty(i.wt_bytes // es, dtype=self.tdtype, device=self.device)
+        self.dwt_blk = torch.empty(i.dwt_bytes // 4, dtype=torch.float32, device=self.device)
+        self.ws = torch.empty(max(16, i.workspace_bytes), dtype=torch.uint8, device=self.device)
+
+    def close(self):
+        if self.h is not None:
+            conv_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _dev(self, a, dtype):
+        t = a if isinstance(a, self.torch.Tensor) else self.torch.from_numpy(a)
+        return t.to(device=self.device, dtype=dtype).contiguous()
+
+    # -- logical -> blocked
+    def set_input(self, I):
+        N, C, K, H, W = self.shape[:5]
+        t = self._dev(I, self.tdtype)
+        assert tuple(t.shape) == (N, C, H, W)
+        conv_pack_in(self.h, t, self.in_blk)
+
+    def set_weights(self, Wt):
+        N, C, K, H, W, R, S = self.shape[:7]
+        t = self._dev(Wt, self.tdtype)
+        assert tuple(t.shape) == (K, C, R, S)
+        conv_pack_wt(self.h, t, self.wt_blk)
+
+    def set_outgrad(self, dO):
+        N, C, K = self.shape[:3]
+        t = self._dev(dO, self.tdtype)
+        assert tuple(t.shape) == (N, K, self.info.P, self.info.Q)
+        conv_pack_out(self.h, t, self.out_blk)
+
+    # -- passes on the blocked buffers
+    def fwd(self):
+        conv_fwd(self.h, self.in_blk, self.wt_blk, self.out_blk, self.ws)
+
+    def bwd_data(self):
+        conv_bwd_data(self.h, self.out_blk, self.wt_blk, self.in_blk, self.ws)
+
+    def upd(self):
+        conv_upd(self.h, self.in_blk, self.out_blk, self.dwt_blk, self.ws)
+
+    # -- blocked -> logical
+    def get_output(self):
+        N, C, K = self.shape[:3]
+        t = self.torch.empty((N, K, self.info.P, self.info.Q), dtype=self.tdtype, device=self.device)
+        conv_unpack_out(self.h, self.out_blk, t)
+        return t
+
+    def get_input(self):
+        N, C, K, H, W = self.shape[:5]
+        t = self.torch.empty((N, C, H, W), dtype=self.tdtype, device=self.device)
+        conv_unpack_in(self.h, self.in_blk, t)
+        return t
+
+    def get_weights(self):
+        N, C, K, H, W, R, S = self.shape[:7]
+        t = self.torch.empty((K, C, R, S), dtype=self.tdtype, device=self.device)
+        conv_unpack_wt(self.h, self.wt_blk, t)
+        return t
+
+    def get_dweights(self):
+        N, C, K, H, W, R, S = self.shape[:7]
+        t = self.torch.empty((K, C, R, S), dtype=self.torch.float32, device=self.device)
+        conv_unpack_dwt(self.h, self.dwt_blk, t)
+        return t

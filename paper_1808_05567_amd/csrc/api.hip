@@ -1,0 +1,488 @@
+// C ABI of libconv_mi355x: descriptor validation and per-layer planning (done
+// once at conv_create, the analogue of the paper's set-up phase, Section II-G),
+// and the entry points that only enqueue kernels.
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "conv_internal.h"
+
+using namespace convmi;
+
+namespace {
+
+struct IgemmPlan {
+    bool ok = false;
+    IgemmVariant v{};
+    IgemmArgs a{};
+    size_t lds = 0;
+    int grid = 0;
+};
+
+struct BwdClass {  // one stride-parity class of the generic backward pass
+    IgemmPlan p;
+    WtXformArgs x{};
+    size_t ws_off = 0;
+};
+
+}  // namespace
+
+struct conv_plan {
+    conv_desc_t d;
+    conv_info_t info;
+    IgemmPlan fwd;
+    // backward by data
+    int bwd_mode = 0;  // 0 unsupported, 1 one launch (duality), 2 parity classes
+    int n_bwd = 0;
+    BwdClass bwd[16];
+    size_t bwd_ws = 0;
+    // weight update
+    bool upd_ok = false;
+    UpdVariant uv{};
+    UpdArgs ua{};
+    size_t upd_lds = 0;
+    int upd_grid = 0;
+    size_t upd_ws = 0;
+};
+
+namespace {
+
+const int kMaxLds = 160 * 1024;
+
+// Largest number of rows of the padded row space (image n occupies rows
+// [n*Hs, (n+1)*Hs), output row oj of image n starts at n*Hs + oj*stride) that a
+// band of TR consecutive linear output rows touches with an R-tall filter.
+int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
+{
+    const int NP = N * P;
+    int best = 0;
+    for (int rho0 = 0; rho0 < NP; rho0 += TR) {
+        const int rho1 = std::min(NP, rho0 + TR) - 1;
+        const int lam0 = (rho0 / P) * Hs + (rho0 % P) * stride;
+        const int lam1 = (rho1 / P) * Hs + (rho1 % P) * stride + R - 1;
+        best = std::max(best, lam1 - lam0 + 1);
+    }
+    return best;
+}
+
+// Plan one launch of the implicit-GEMM kernel.
+//   input tensor:  N x Cb blocks x H x W;  result extent P x Q;  A rows Kp.
+IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
+                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
+                     int zero_fill)
+{
+    IgemmPlan pl;
+    const int V = vlen_of(dtype);
+    const bool sampled = (R == 1 && S == 1 && pad_h == 0 && pad_w == 0);
+
+    int npl;
+    if (R == 1 && S == 1)
+        npl = (Cb % 4 == 0) ? 4 : 1;
+    else if (R == 3 && S == 3)
+        npl = (Cb % 2 == 0) ? 2 : 1;
+    else
+        npl = 1;
+
+    const int wk = (Kp > 64 && npl != 1) ? 4 : 2;
+    const int wm = 4 / wk;
+    const int fk = 1, fm = 7;
+    const int TK = wk * fk * 32, TM = wm * fm * 32, NT = 256;
+
+    // candidate staged-pixels-per-thread values instantiated for this shape
+    int ppt = -1;
+    int TQ = std::min(Q, TM);
+    int TR = std::max(1, TM / TQ);
+    TR = std::min(TR, N * P);
+    int Hs = 0, LW = 0, LR = 0;
+    for (;; --TR) {
+        if (TR < 1) return pl;
+        if (sampled) {
+            Hs = P;
+            LW = TQ;
+            LR = TR;
+        } else {
+            Hs = (P - 1) * stride + R;
+            LW = (TQ - 1) * stride + S;
+            LR = max_band_rows(N, P, TR, Hs, stride, R);
+        }
+        const int need = ceil_div(LR * LW, NT);
+        ppt = -1;
+        for (int cand = need; cand <= 16; ++cand) {
+            IgemmVariant v{dtype, wk, wm, fk, fm, npl, R, S, cand};
+            if (igemm_variant_exists(v)) {
+                ppt = cand;
+                break;
+            }
+        }
+        const int nent = ((R * S * npl + 1) / 2) * 2;
+        const size_t lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * LR * LW * 16);
+        if (ppt > 0 && lds <= (size_t)kMaxLds) break;
+        if (TR == 1) return pl;
+    }
+
+    IgemmArgs &a = pl.a;
+    memset(&a, 0, sizeof(a));
+    a.N = N; a.Cb = Cb; a.H = H; a.W = W; a.Kp = Kp; a.P = P; a.Q = Q;
+    a.stride = stride; a.pad_h = pad_h; a.pad_w = pad_w;
+    a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
+    a.TR = TR; a.TQ = TQ;
+    a.n_qt = ceil_div(Q, TQ);
+    a.n_mt = ceil_div(N * P, TR);
+    a.n_kt = ceil_div(Kp, TK);
+    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW; a.PLS = LR * LW;
+    a.sampled = sampled ? 1 : 0;
+    a.total = a.n_mt * a.n_qt * a.n_kt;
+    a.per_xcd = ceil_div(a.total, 8);
+    a.n_stage = ceil_div(Cb, npl);
+    pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt};
+    const int nent = ((R * S * npl + 1) / 2) * 2;
+    pl.lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
+    pl.grid = a.per_xcd * 8;
+    // 32-bit index guards (offsets are kept in 16-byte units / elements)
+    const double in_units = (double)N * Cb * H * W, out_units = (double)N * (Kp / V) * OH * OW;
+    if (in_units > 2.0e9 || out_units > 2.0e9) return pl;
+    pl.ok = true;
+    return pl;
+}
+
+void plan_bwd(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int es = esize_of(d.dtype);
+    p->bwd_mode = 0;
+    p->n_bwd = 0;
+    p->bwd_ws = 0;
+    if (d.stride == 1 && d.pad <= d.R - 1 && d.pad <= d.S - 1) {
+        BwdClass &b = p->bwd[0];
+        b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, d.H, d.W, d.R, d.S, 1, d.R - 1 - d.pad,
+                         d.S - 1 - d.pad, d.H, d.W, 1, 0, 0, 0);
+        b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, d.R, d.S, d.R, d.S,
+                          1, 0, 0, d.R, d.S};
+        b.ws_off = 0;
+        if (b.p.ok) {
+            p->bwd_mode = 1;
+            p->n_bwd = 1;
+            p->bwd_ws = (size_t)f.Kb * d.R * d.S * f.Cp * f.vlen * es;
+        }
+        return;
+    }
+    if (d.R == 1 && d.S == 1 && d.pad == 0) {
+        BwdClass &b = p->bwd[0];
+        b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, f.P, f.Q, 1, 1, 1, 0, 0, d.H, d.W,
+                         d.stride, 0, 0, 1);
+        b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, 1, 1, 1, 1, 1, 0, 0, 1, 1};
+        b.ws_off = 0;
+        if (b.p.ok) {
+            p->bwd_mode = 1;
+            p->n_bwd = 1;
+            p->bwd_ws = (size_t)f.Kb * f.Cp * f.vlen * es;
+        }
+        return;
+    }
+    // Generic case: one stride-1 sub-convolution per residue class (py, px) of
+    // the dI position modulo the stride, over the taps congruent to it.
+    const int st = d.stride;
+    if (st * st > 16) return;
+    const int R2 = ceil_div(d.R, st), S2 = ceil_div(d.S, st);
+    size_t off = 0;
+    int n = 0;
+    for (int py = 0; py < st; ++py)
+        for (int px = 0; px < st; ++px) {
+            const int ry = (py + d.pad) % st, rx = (px + d.pad) % st;
+            const int Rsub = ry < d.R ? ceil_div(d.R - ry, st) : 0;
+            const int Ssub = rx < d.S ? ceil_div(d.S - rx, st) : 0;
+            const int dy0 = (py + d.pad) / st, dx0 = (px + d.pad) / st;
+            const int Hsub = py < d.H ? ceil_div(d.H - py, st) : 0;
+            const int Wsub = px < d.W ? ceil_div(d.W - px, st) : 0;
+            if (Hsub == 0 || Wsub == 0) continue;
+            BwdClass &b = p->bwd[n];
+            // With no tap in the class the sub-filter is all zero and the
+            // launch writes zeros, which is what Algorithm 6 leaves there.
+            const int Re = std::max(Rsub, 1), Se = std::max(Ssub, 1);
+            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, Hsub, Wsub, R2, S2, 1,
+                             Re - 1 - dy0, Se - 1 - dx0, d.H, d.W, st, py, px, 0);
+            if (!b.p.ok) return;
+            b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, d.R, d.S, R2, S2,
+                              st, ry, rx, Rsub, Ssub};
+            if (Rsub == 0 || Ssub == 0) { b.x.Rsub = 0; b.x.Ssub = 0; }
+            b.ws_off = off;
+            off += (size_t)f.Kb * R2 * S2 * f.Cp * f.vlen * es;
+            ++n;
+        }
+    p->bwd_mode = 2;
+    p->n_bwd = n;
+    p->bwd_ws = off;
+}
+
+void plan_upd(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    p->upd_ok = false;
+    p->upd_ws = 0;
+    if (d.dtype != CONV_F32) return;
+    const bool sampled = (d.R == 1 && d.S == 1 && d.pad == 0);
+    int ppt_in, ppt_out;
+    if (d.R == 3 && d.S == 3) { ppt_in = 16; ppt_out = 8; }
+    else if (d.R == 1 && d.S == 1) { ppt_in = 8; ppt_out = 8; }
+    else return;
+    UpdVariant v{d.dtype, d.R, d.S, ppt_in, ppt_out};
+    if (!upd_variant_exists(v)) return;
+    const int V = f.vlen;
+    const int TC = 64, TK = 64, NPI = TC / V, NPO = TK / V, NT = 256;
+    const int Qp = (f.Q + 1) & ~1;
+    const int NP = d.N * f.P;
+    int TR = std::min(NP, std::max(1, (ppt_out * NT / NPO) / Qp));
+    int Hs = 0, LW = 0, LR = 0;
+    for (;; --TR) {
+        if (TR < 1) return;
+        if (sampled) { Hs = f.P; LW = Qp; LR = TR; }
+        else {
+            Hs = (f.P - 1) * d.stride + d.R;
+            LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * d.pad);
+            LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, d.R);
+        }
+        if (NPI * LR * LW <= ppt_in * NT && NPO * TR * Qp <= ppt_out * NT) break;
+    }
+    UpdArgs &a = p->ua;
+    memset(&a, 0, sizeof(a));
+    a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+    a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+    a.TR = TR;
+    a.n_ct = ceil_div(f.Cb, NPI);
+    a.n_kt = ceil_div(f.Kb, NPO);
+    const int tiles = a.n_ct * a.n_kt;
+    int splits = std::max(1, (1024 + tiles / 2) / tiles);
+    int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+    splits = ceil_div(NP, rps);
+    a.rows_per_split = rps;
+    a.splits = splits;
+    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW;
+    // plane pitch = 1 (mod 8) pixels: the 8 channel blocks a 32-lane group
+    // reads land in different LDS banks
+    a.PLS_in = ((a.LRW + 7) / 8) * 8 + 1;
+    a.PLS_out = ((TR * Qp + 7) / 8) * 8 + 1;
+    a.sampled = sampled ? 1 : 0;
+    a.total = tiles * splits;
+    a.per_xcd = ceil_div(a.total, 8);
+    p->uv = v;
+    p->upd_lds = ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+    if (p->upd_lds > (size_t)kMaxLds) return;
+    p->upd_grid = a.per_xcd * 8;
+    p->upd_ws = (size_t)splits * f.dwt_bytes;
+    p->upd_ok = true;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *conv_status_str(conv_status_t s)
+{
+    switch (s) {
+        case CONV_OK: return "ok";
+        case CONV_EINVAL: return "invalid argument";
+        case CONV_EUNSUPPORTED: return "unsupported problem";
+        case CONV_EWORKSPACE: return "workspace missing";
+        case CONV_ELAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
+{
+    if (!desc || !out) return CONV_EINVAL;
+    *out = nullptr;
+    const conv_desc_t &d = *desc;
+    if (d.N < 1 || d.C < 1 || d.K < 1 || d.H < 1 || d.W < 1 || d.R < 1 || d.S < 1 || d.stride < 1 ||
+        d.pad < 0)
+        return CONV_EINVAL;
+    if (d.dtype != CONV_F32 && d.dtype != CONV_BF16) return CONV_EINVAL;
+    if (d.H + 2 * d.pad < d.R || d.W + 2 * d.pad < d.S) return CONV_EINVAL;
+
+    conv_plan *p = new (std::nothrow) conv_plan();
+    if (!p) return CONV_EINVAL;
+    p->d = d;
+    conv_info_t &f = p->info;
+    memset(&f, 0, sizeof(f));
+    f.P = (d.H + 2 * d.pad - d.R) / d.stride + 1;
+    f.Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
+    f.vlen = vlen_of(d.dtype);
+    f.Cb = ceil_div(d.C, f.vlen);
+    f.Kb = ceil_div(d.K, f.vlen);
+    f.Cp = f.Cb * f.vlen;
+    f.Kp = f.Kb * f.vlen;
+    const size_t es = esize_of(d.dtype);
+    f.in_bytes = (size_t)d.N * f.Cp * d.H * d.W * es;
+    f.out_bytes = (size_t)d.N * f.Kp * f.P * f.Q * es;
+    f.wt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * es;
+    f.dwt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * sizeof(float);
+
+    p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, d.pad,
+                        d.pad, f.P, f.Q, 1, 0, 0, 0);
+    plan_bwd(p);
+    plan_upd(p);
+    f.upd_splits = p->upd_ok ? p->ua.splits : 0;
+    f.workspace_bytes = std::max(p->bwd_ws, p->upd_ws);
+    *out = p;
+    return CONV_OK;
+}
+
+conv_status_t conv_destroy(conv_handle_t h)
+{
+    if (!h) return CONV_EINVAL;
+    delete h;
+    return CONV_OK;
+}
+
+conv_status_t conv_query(conv_handle_t h, conv_info_t *info)
+{
+    if (!h || !info) return CONV_EINVAL;
+    *info = h->info;
+    return CONV_OK;
+}
+
+conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
+                       void *stream)
+{
+    (void)ws;
+    if (!h || !in || !wt || !out) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(wt) || !aligned16(out)) return CONV_EINVAL;
+    if (!h->fwd.ok) return CONV_EUNSUPPORTED;
+    IgemmArgs a = h->fwd.a;
+    a.in = in;
+    a.wt = wt;
+    a.out = out;
+    hipError_t e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
+    return e == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, void *din, void *ws,
+                            void *stream)
+{
+    if (!h || !dout || !wt || !din) return CONV_EINVAL;
+    if (!aligned16(dout) || !aligned16(wt) || !aligned16(din) || !aligned16(ws)) return CONV_EINVAL;
+    if (h->bwd_mode == 0) return CONV_EUNSUPPORTED;
+    if (!ws) return CONV_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < h->n_bwd; ++i) {
+        const BwdClass &b = h->bwd[i];
+        WtXformArgs x = b.x;
+        x.src = wt;
+        x.dst = static_cast<char *>(ws) + b.ws_off;
+        if (launch_wt_xform(h->d.dtype, x, s) != hipSuccess) return CONV_ELAUNCH;
+        IgemmArgs a = b.p.a;
+        a.in = dout;
+        a.wt = x.dst;
+        a.out = din;
+        if (launch_igemm(b.p.v, a, b.p.lds, b.p.grid, s) != hipSuccess) return CONV_ELAUNCH;
+    }
+    return CONV_OK;
+}
+
+conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *dwt, void *ws,
+                       void *stream)
+{
+    if (!h || !in || !dout || !dwt) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(dout) || !aligned16(dwt) || !aligned16(ws)) return CONV_EINVAL;
+    if (!h->upd_ok) return CONV_EUNSUPPORTED;
+    if (!ws) return CONV_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    UpdArgs a = h->ua;
+    a.in = in;
+    a.dout = dout;
+    a.partial = static_cast<float *>(ws);
+    if (launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s) != hipSuccess) return CONV_ELAUNCH;
+    if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
+                          a.splits, s) != hipSuccess)
+        return CONV_ELAUNCH;
+    return CONV_OK;
+}
+
+#define CHECK_PACK_ARGS(h, a, b)                                  \
+    if (!(h) || !(a) || !(b)) return CONV_EINVAL;                 \
+    if (!aligned16(a) || !aligned16(b)) return CONV_EINVAL;
+
+conv_status_t conv_pack_in(conv_handle_t h, const void *nchw, void *blk, void *stream)
+{
+    CHECK_PACK_ARGS(h, nchw, blk);
+    const conv_desc_t &d = h->d;
+    return launch_pack_act(d.dtype, nchw, blk, d.N, d.C, d.H, d.W, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_pack_out(conv_handle_t h, const void *nkpq, void *blk, void *stream)
+{
+    CHECK_PACK_ARGS(h, nkpq, blk);
+    const conv_desc_t &d = h->d;
+    return launch_pack_act(d.dtype, nkpq, blk, d.N, d.K, h->info.P, h->info.Q,
+                           (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_pack_wt(conv_handle_t h, const void *kcrs, void *blk, void *stream)
+{
+    CHECK_PACK_ARGS(h, kcrs, blk);
+    const conv_desc_t &d = h->d;
+    return launch_pack_wt(d.dtype, kcrs, blk, d.K, d.C, d.R, d.S, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_unpack_in(conv_handle_t h, const void *blk, void *nchw, void *stream)
+{
+    CHECK_PACK_ARGS(h, blk, nchw);
+    const conv_desc_t &d = h->d;
+    return launch_unpack_act(d.dtype, blk, nchw, d.N, d.C, d.H, d.W, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_unpack_out(conv_handle_t h, const void *blk, void *nkpq, void *stream)
+{
+    CHECK_PACK_ARGS(h, blk, nkpq);
+    const conv_desc_t &d = h->d;
+    return launch_unpack_act(d.dtype, blk, nkpq, d.N, d.K, h->info.P, h->info.Q,
+                             (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_unpack_wt(conv_handle_t h, const void *blk, void *kcrs, void *stream)
+{
+    CHECK_PACK_ARGS(h, blk, kcrs);
+    const conv_desc_t &d = h->d;
+    return launch_unpack_wt(d.dtype, blk, kcrs, d.K, d.C, d.R, d.S, h->info.vlen,
+                            (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+conv_status_t conv_unpack_dwt(conv_handle_t h, const void *blk_f32, void *kcrs_f32, void *stream)
+{
+    CHECK_PACK_ARGS(h, blk_f32, kcrs_f32);
+    const conv_desc_t &d = h->d;
+    return launch_unpack_wt(CONV_F32, blk_f32, kcrs_f32, d.K, d.C, d.R, d.S, h->info.vlen,
+                            (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buflen)
+{
+    if (!h || !buf || buflen == 0) return CONV_EINVAL;
+    buf[0] = 0;
+    if (pass == 0 || pass == 1) {
+        const IgemmPlan *p = pass == 0 ? &h->fwd : &h->bwd[0].p;
+        if (pass == 1 && h->bwd_mode == 0) return CONV_EUNSUPPORTED;
+        if (!p->ok) return CONV_EUNSUPPORTED;
+        snprintf(buf, buflen,
+                 "igemm dt=%d waves=%dx%d frags=%dx%d npl=%d RS=%dx%d ppt=%d TR=%d TQ=%d tiles=%d "
+                 "(m=%d q=%d k=%d) grid=%d lds=%zu stages=%d launches=%d",
+                 p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.r, p->v.s, p->v.ppt,
+                 p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->grid, p->lds,
+                 p->a.n_stage, pass == 0 ? 1 : h->n_bwd);
+        return CONV_OK;
+    }
+    if (pass == 2) {
+        if (!h->upd_ok) return CONV_EUNSUPPORTED;
+        snprintf(buf, buflen,
+                 "upd dt=%d RS=%dx%d TR=%d splits=%d rows/split=%d tiles=%dx%d grid=%d lds=%zu",
+                 h->uv.dtype, h->uv.r, h->uv.s, h->ua.TR, h->ua.splits, h->ua.rows_per_split,
+                 h->ua.n_ct, h->ua.n_kt, h->upd_grid, h->upd_lds);
+        return CONV_OK;
+    }
+    return CONV_EINVAL;
+}
+
+}  // extern "C"

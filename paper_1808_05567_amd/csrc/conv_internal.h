@@ -1,0 +1,118 @@
+// Internal declarations shared by the translation units of libconv_mi355x.
+// Not part of the public ABI (that is include/conv_mi355x.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "conv_mi355x.h"
+
+namespace convmi {
+
+// ---------------------------------------------------------------------------
+// Arguments of the implicit-GEMM kernel that serves the forward pass and, via
+// the two duality scenarios of Section II-H, the backward-by-data pass.
+//
+//   out[n][kb][oy][ox][:] = sum_{cb,r,s,c} in[n][cb][oy*stride-pad_h+r][ox*stride-pad_w+s][c]
+//                                          * wt[cb][r][s][k][c]
+//
+// M = output channels (weights are the MFMA A operand), N = output pixels
+// (the staged input tile is the B operand), reduction = (channel block, r, s):
+// the paper's M^=k, N^=pixels, K^=c small-GEMM chain (Section II-D) at
+// workgroup scale.
+// ---------------------------------------------------------------------------
+struct IgemmArgs {
+    const void *in;
+    const void *wt;
+    void *out;
+    int N;
+    int Cb;        // input channel blocks (reduction planes)
+    int H, W;      // input extent
+    int Kp;        // output channels rounded up to vlen (rows of A)
+    int P, Q;      // extent of the convolution result
+    int stride, pad_h, pad_w;
+    int OH, OW;    // extent of the output tensor (== P,Q unless scattering)
+    int ostr;      // result pixel (oj,oi) is written at (oj*ostr+oy0, oi*ostr+ox0)
+    int oy0, ox0;
+    int zero_fill; // ostr>1: also write zeros to the other positions of each ostr x ostr cell
+    int TR, TQ;    // tile = TR linear output rows (n*P+oj) x TQ columns
+    int n_qt;      // column tiles
+    int n_mt;      // row tiles
+    int n_kt;      // output-channel tiles
+    int Hs;        // rows per image in the padded row space of the staged tile
+    int LW;        // staged tile width  (pixels)
+    int LRW;       // staged tile size   (pixels) = rows * LW
+    int PLS;       // LDS plane pitch    (16-byte units)
+    int sampled;   // R=S=1, pad=0: stage only the pixels that are read
+    int total;     // workgroups doing work
+    int per_xcd;   // ceil(total / 8)
+    int n_stage;   // ceil(Cb / planes per stage)
+};
+
+// Key of a kernel instantiation; the host picks one per pass at plan time.
+struct IgemmVariant {
+    int dtype;   // conv_dtype_t
+    int wk, wm;  // waves along channels / pixels
+    int fk, fm;  // 32x32 MFMA fragments per wave along channels / pixels
+    int npl;     // reduction planes (channel blocks) staged per step
+    int r, s;    // filter extent
+    int ppt;     // staged input pixels per thread
+};
+
+hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes,
+                        int grid, hipStream_t stream);
+bool igemm_variant_exists(const IgemmVariant &v);
+
+// Weight transform for backward by data:  dst[kb][r'][s'][c][k%v] (tap-flipped,
+// channel roles swapped, optionally a stride-decimated sub-filter).
+struct WtXformArgs {
+    const void *src;   // Wb[Cb][R][S][Kp][v]
+    void *dst;         // [Kb][R2][S2][Cp][v]
+    int Cb, Kb, Cp, Kp, R, S, R2, S2;
+    int tap_stride;    // source tap r = tap_stride*(Rsub-1-r') + r_off, valid if r' < Rsub
+    int r_off, s_off, Rsub, Ssub;
+};
+hipError_t launch_wt_xform(int dtype, const WtXformArgs &a, hipStream_t stream);
+
+// Weight update (Algorithm 8): partial sums over slices of the pixel range,
+// then a fixed-order reduction.
+struct UpdArgs {
+    const void *in;
+    const void *dout;
+    float *partial;  // [splits][Cb][R][S][Kp][v] fp32
+    int N, Cb, H, W, Kb, Kp, P, Q, R, S, stride, pad;
+    int TR;          // linear output rows per staged step
+    int rows_per_split;
+    int splits;
+    int n_ct, n_kt;  // tiles over input / output channels
+    int Hs, LW, LRW, PLS_in, PLS_out;
+    int sampled;
+    int total, per_xcd;
+};
+struct UpdVariant {
+    int dtype;
+    int r, s;
+    int ppt_in, ppt_out;
+};
+hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
+                      hipStream_t stream);
+bool upd_variant_exists(const UpdVariant &v);
+hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
+                             hipStream_t stream);
+
+// Layout conversion (pure permutations).
+hipError_t launch_pack_act(int dtype, const void *nchw, void *blk, int N, int C, int H, int W,
+                           hipStream_t stream);
+hipError_t launch_unpack_act(int dtype, const void *blk, void *nchw, int N, int C, int H, int W,
+                             hipStream_t stream);
+hipError_t launch_pack_wt(int dtype, const void *kcrs, void *blk, int K, int C, int R, int S,
+                          hipStream_t stream);
+hipError_t launch_unpack_wt(int dtype, const void *blk, void *kcrs, int K, int C, int R, int S,
+                            int vlen, hipStream_t stream);
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int vlen_of(int dtype) { return dtype == CONV_BF16 ? 8 : 4; }
+static inline int esize_of(int dtype) { return dtype == CONV_BF16 ? 2 : 4; }
+
+}  // namespace convmi

@@ -1,0 +1,386 @@
+// Implicit-GEMM direct convolution on MFMA for gfx950: the kernel behind the
+// forward pass (Algorithm 1 of the paper, with padding) and, through the two
+// duality scenarios of Section II-H, the backward-by-data pass (Algorithm 6).
+//
+// Mapping of the paper's ingredients:
+//   * Section II-B blocked layouts: channels are blocked by v = 16 bytes/element
+//     size, the 128-bit vector a lane feeds into one MFMA operand (the role a
+//     512-bit register's VLEN plays on AVX-512).
+//   * Section II-D microkernel (chain of small GEMMs M^=k, N^=pixels, K^=c into
+//     one output tile, stores hoisted out of the r,s loops): a workgroup owns a
+//     tile of TK output channels x TM output pixels, each wave keeps FK x FM
+//     32x32 accumulator tiles in registers for the whole (c_b, r, s) reduction
+//     and writes them once.
+//   * Section II-C: the input-channel loop is innermost around a resident
+//     output tile for every filter size.
+//   * Section II-E prefetching: the next channel step is fetched from HBM into
+//     registers while the current one is consumed from LDS (double buffer).
+//   * "Direct": the input halo tile is staged once per channel step and reused
+//     by all R*S taps out of LDS; no im2col copy exists anywhere.
+//   * Section II-F work split (N, then K_b, then P_b/Q_b): the grid enumerates
+//     (row tile, column tile, channel tile) with the channel tile fastest and
+//     consecutive tiles kept on one XCD so that they share its L2.
+#include "conv_internal.h"
+
+namespace convmi {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int DT>
+struct Elem;
+
+template <>
+struct Elem<CONV_F32> {
+    static constexpr int V = 4;
+    // One 16-byte operand per lane carries 4 reduction indices; lanes 0-31 and
+    // 32-63 hold different channel blocks, so four 32x32x2 MFMAs consume it.
+    static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
+    {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[t]), __uint_as_float(b[t]),
+                                                     c, 0, 0, 0);
+    }
+    // Store 4 consecutive channels of one pixel.
+    static __device__ __forceinline__ void store4(void *base, size_t elem_off, float x0, float x1,
+                                                  float x2, float x3)
+    {
+        u32x4 v = {__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2),
+                   __float_as_uint(x3)};
+        *reinterpret_cast<u32x4 *>(static_cast<float *>(base) + elem_off) = v;
+    }
+};
+
+static __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 p = {(__bf16)lo, (__bf16)hi};  // round to nearest even
+    return __builtin_bit_cast(unsigned, p);
+}
+
+template <>
+struct Elem<CONV_BF16> {
+    static constexpr int V = 8;
+    static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void store4(void *base, size_t elem_off, float x0, float x1,
+                                                  float x2, float x3)
+    {
+        u32x2 v = {pack_bf16x2(x0, x1), pack_bf16x2(x2, x3)};
+        *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(base) + elem_off) = v;
+    }
+};
+
+template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT>
+__global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
+{
+    using E_ = Elem<DT>;
+    constexpr int V = E_::V;
+    constexpr int NT = WK * WM * 64;
+    constexpr int TK = WK * FK * 32;
+    constexpr int NTAPS = R * S;
+    constexpr int NENT = ((NTAPS * NPL + 1) / 2) * 2;  // reduction entries per step, even
+    constexpr int WCH = NENT * TK;                     // 16-byte weight chunks per step
+    constexpr int WPT = (WCH + NT - 1) / NT;
+    constexpr int WBYTES = WCH * 16;
+    static_assert(NPL == 1 || NPL % 2 == 0, "planes per step: 1 or even");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int ibytes = NPL * a.PLS * 16;
+    const int bufbytes = WBYTES + ibytes;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int wave_k = wave % WK;
+    const int wave_m = wave / WK;
+
+    // Workgroup -> tile.  Hardware deals consecutive workgroup ids round-robin
+    // over the 8 XCDs; give every XCD a contiguous run of tiles.
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int rest = lin / a.n_kt;
+    const int qt = rest % a.n_qt;
+    const int mt = rest / a.n_qt;
+    const int k0 = kt * TK;
+    const int q0 = qt * a.TQ;
+    const int rho0 = mt * a.TR;
+    const int NP = a.N * a.P;
+    const int n0 = rho0 / a.P;
+    const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+    const int HW = a.H * a.W;
+
+    // ---- per-thread source offsets of the staged input pixels (16-byte units)
+    int g_off[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+        const int p = tid + i * NT;
+        int off = -1;
+        if (p < a.LRW) {
+            const int row = p / a.LW;
+            const int col = p - row * a.LW;
+            int n, ih, iw;
+            bool ok;
+            if (a.sampled) {
+                const int rho = rho0 + row;
+                n = rho / a.P;
+                ih = (rho - n * a.P) * a.stride;
+                iw = (q0 + col) * a.stride;
+                ok = rho < NP && (q0 + col) < a.Q;
+            } else {
+                const int lam = lam0 + row;
+                n = lam / a.Hs;
+                ih = lam - n * a.Hs - a.pad_h;
+                iw = q0 * a.stride - a.pad_w + col;
+                ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            }
+            if (ok) off = (n * a.Cb * a.H + ih) * a.W + iw;
+        }
+        g_off[i] = off;
+    }
+    // ---- per-thread source offsets of the staged weights
+    int w_off[WPT];
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        const int w = tid + i * NT;
+        int off = -1;
+        if (w < WCH) {
+            const int e = w / TK;
+            const int k = w - e * TK;
+            const int tap = e / NPL;
+            const int pl = e - tap * NPL;
+            if (tap < NTAPS && k0 + k < a.Kp) off = (pl * NTAPS + tap) * a.Kp + k0 + k;
+        }
+        w_off[i] = off;
+    }
+
+    u32x4 ireg[PPT][NPL];
+    u32x4 wreg[WPT];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    auto fetch = [&](int st) {
+        const int cb0 = st * NPL;
+        const u32x4 *ip = static_cast<const u32x4 *>(a.in) + (size_t)cb0 * HW;
+        const u32x4 *wp = static_cast<const u32x4 *>(a.wt) + (size_t)cb0 * NTAPS * a.Kp;
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+#pragma unroll
+            for (int pl = 0; pl < NPL; ++pl)
+                ireg[i][pl] = g_off[i] >= 0 ? ip[g_off[i] + pl * HW] : zero4;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) wreg[i] = w_off[i] >= 0 ? wp[w_off[i]] : zero4;
+    };
+    auto commit = [&](int buf) {
+        unsigned char *wb = lds + buf * bufbytes;
+        unsigned char *ib = wb + WBYTES;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            const int w = tid + i * NT;
+            if (w < WCH) *reinterpret_cast<u32x4 *>(wb + w * 16) = wreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int p = tid + i * NT;
+            if (p < a.LRW) {
+#pragma unroll
+                for (int pl = 0; pl < NPL; ++pl)
+                    *reinterpret_cast<u32x4 *>(ib + (pl * a.PLS + p) * 16) = ireg[i][pl];
+            }
+        }
+    };
+
+    // ---- per-lane pixel bookkeeping for the B fragments and the epilogue
+    int bpos[FM];
+    int opix[FM];
+    const int Kb_out = a.Kp / V;
+#pragma unroll
+    for (int j = 0; j < FM; ++j) {
+        const int m = (wave_m * FM + j) * 32 + l32;
+        const int trow = m / a.TQ;
+        const int tcol = m - trow * a.TQ;
+        const int rho = rho0 + trow;
+        const bool ok = trow < a.TR && rho < NP && (q0 + tcol) < a.Q;
+        const int n = rho / a.P;
+        const int oj = rho - n * a.P;
+        int pos = a.sampled ? m : (n * a.Hs + oj * a.stride - lam0) * a.LW + tcol * a.stride;
+        if (!ok) pos = 0;
+        // lane halves read two channel planes, or (one plane per step) two taps
+        bpos[j] = ((NPL == 1 ? 0 : h) * a.PLS + pos) * 16;
+        opix[j] = ok ? (n * Kb_out * a.OH + oj * a.ostr + a.oy0) * a.OW + (q0 + tcol) * a.ostr + a.ox0
+                     : -1;
+    }
+    const int a_base = (h * TK + wave_k * FK * 32 + l32) * 16;
+
+    f32x16 acc[FK][FM];
+#pragma unroll
+    for (int i = 0; i < FK; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+            for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
+
+    fetch(0);
+    commit(0);
+    __syncthreads();
+
+    for (int st = 0; st < a.n_stage; ++st) {
+        const bool more = st + 1 < a.n_stage;
+        if (more) fetch(st + 1);
+        const unsigned char *wb = lds + (st & 1) * bufbytes;
+        const unsigned char *ib = wb + WBYTES;
+
+        if constexpr (NPL == 1) {
+            // One channel block per step: the two lane halves take two taps.
+#pragma unroll 1
+            for (int q = 0; q < NENT / 2; ++q) {
+                const int t0 = 2 * q;
+                const int t1 = (2 * q + 1 < NTAPS) ? 2 * q + 1 : NTAPS - 1;
+                const int off0 = ((t0 / S) * a.LW + (t0 % S)) * 16;
+                const int off1 = ((t1 / S) * a.LW + (t1 % S)) * 16;
+                const int toff = h ? off1 : off0;
+                u32x4 af[FK], bf[FM];
+#pragma unroll
+                for (int i = 0; i < FK; ++i)
+                    af[i] = *reinterpret_cast<const u32x4 *>(wb + a_base + (2 * q * TK + 32 * i) * 16);
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+                    bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff);
+#pragma unroll
+                for (int i = 0; i < FK; ++i)
+#pragma unroll
+                    for (int j = 0; j < FM; ++j) E_::mma(af[i], bf[j], acc[i][j]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const int toff = (r * a.LW + s) * 16;
+#pragma unroll
+                    for (int pp = 0; pp < NPL / 2; ++pp) {
+                        const int q = (r * S + s) * (NPL / 2) + pp;
+                        u32x4 af[FK], bf[FM];
+#pragma unroll
+                        for (int i = 0; i < FK; ++i)
+                            af[i] = *reinterpret_cast<const u32x4 *>(wb + a_base +
+                                                                     (2 * q * TK + 32 * i) * 16);
+#pragma unroll
+                        for (int j = 0; j < FM; ++j)
+                            bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff +
+                                                                     2 * pp * a.PLS * 16);
+#pragma unroll
+                        for (int i = 0; i < FK; ++i)
+#pragma unroll
+                            for (int j = 0; j < FM; ++j) E_::mma(af[i], bf[j], acc[i][j]);
+                    }
+                }
+            }
+        }
+        if (more) commit((st + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels
+    const size_t oplane = (size_t)a.OH * a.OW;
+#pragma unroll
+    for (int i = 0; i < FK; ++i) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const int krow = k0 + (wave_k * FK + i) * 32 + vq * 8 + h * 4;
+            if (krow >= a.Kp) continue;
+            const int kblk = krow / V;
+            const int sub = krow - kblk * V;
+#pragma unroll
+            for (int j = 0; j < FM; ++j) {
+                if (opix[j] < 0) continue;
+                const size_t off = ((size_t)opix[j] + (size_t)kblk * oplane) * V + sub;
+                E_::store4(a.out, off, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
+                           acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
+                if (a.zero_fill) {
+                    const int ox = opix[j] % a.OW;
+                    const int oy = (opix[j] / a.OW) % a.OH;
+                    for (int dy = 0; dy < a.ostr; ++dy)
+                        for (int dx = 0; dx < a.ostr; ++dx) {
+                            if ((dy | dx) == 0 || oy + dy >= a.OH || ox + dx >= a.OW) continue;
+                            E_::store4(a.out, off + (size_t)(dy * a.OW + dx) * V, 0.f, 0.f, 0.f, 0.f);
+                        }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Instantiations and dispatch
+// ---------------------------------------------------------------------------
+typedef void (*igemm_fn_t)(const IgemmArgs);
+struct IgemmEntry {
+    IgemmVariant v;
+    igemm_fn_t fn;
+    size_t lds_attr;
+};
+
+#define IGEMM_ENTRY(DT, WK, WM, FK, FM, NPL, R, S, PPT)                         \
+    {                                                                            \
+        {DT, WK, WM, FK, FM, NPL, R, S, PPT},                                    \
+            igemm_kernel<DT, WK, WM, FK, FM, NPL, R, S, PPT>, 0                  \
+    }
+
+static IgemmEntry g_igemm[] = {
+    // fp32
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 3, 3, 2),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 3, 3, 3),
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 4, 1, 1, 1),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 4, 1, 1, 2),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 1, 1, 2),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 3, 3, 3),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 7, 7, 12),
+    // bf16
+    IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 2),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 3, 3, 3),
+    IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 1, 1, 2),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 3, 3, 3),
+};
+
+static IgemmEntry *find_igemm(const IgemmVariant &v)
+{
+    for (auto &e : g_igemm) {
+        const IgemmVariant &w = e.v;
+        if (w.dtype == v.dtype && w.wk == v.wk && w.wm == v.wm && w.fk == v.fk && w.fm == v.fm &&
+            w.npl == v.npl && w.r == v.r && w.s == v.s && w.ppt == v.ppt)
+            return &e;
+    }
+    return nullptr;
+}
+
+bool igemm_variant_exists(const IgemmVariant &v) { return find_igemm(v) != nullptr; }
+
+hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes, int grid,
+                        hipStream_t stream)
+{
+    IgemmEntry *e = find_igemm(v);
+    if (!e) return hipErrorInvalidDeviceFunction;
+    if (lds_bytes > e->lds_attr) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        e->lds_attr = lds_bytes;
+    }
+    hipLaunchKernelGGL(e->fn, dim3(grid), dim3(v.wk * v.wm * 64), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convmi

@@ -1,0 +1,307 @@
+// Weight-gradient update (Algorithm 8 of the paper, with padding) on MFMA.
+//
+//   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
+//
+// Mapping of the paper's ingredients (Section II-I, Algorithm 9):
+//   * the VLEN x VLEN dW block kept in registers across the spatial loops becomes
+//     a (32*FC) x (32*FK) MFMA accumulator tile per filter tap, all R*S taps
+//     of the tile resident in one wave (M = input channels, N = output
+//     channels, reduction = pixels);
+//   * the spatial blocking B_P x B_Q becomes the band of TR linear output rows
+//     (n*P+oj) staged in LDS per step: the dO band and the input halo band it
+//     touches, the latter reused by all R*S taps;
+//   * the parallelisation trade-off (one dW vs T private copies + reduction):
+//     the grid is (split of the pixel range) x (channel tiles); each split
+//     writes a private partial dW and a second kernel sums the copies in a
+//     fixed order, so results are bitwise reproducible.  The split also keeps
+//     every fp32 accumulation chain short.
+#include "conv_internal.h"
+
+namespace convmi {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// fp32 activations and gradients (vlen 4).  256 threads = 2 x 2 waves over
+// (input channels, output channels); a wave owns FC x FK fragments per tap.
+template <int R, int S, int FC, int FK, int PPTI, int PPTO>
+__global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
+{
+    constexpr int V = 4;
+    constexpr int NT = 256;
+    constexpr int NTAPS = R * S;
+    constexpr int TC = 2 * FC * 32;
+    constexpr int TK = 2 * FK * 32;
+    constexpr int NPI = TC / V;  // staged input planes
+    constexpr int NPO = TK / V;  // staged dO planes
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    float *ldsI = reinterpret_cast<float *>(lds);
+    float *ldsO = ldsI + (size_t)NPI * a.PLS_in * V;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int wave_c = wave & 1;
+    const int wave_k = wave >> 1;
+
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int rest = lin / a.n_kt;
+    const int ct = rest % a.n_ct;
+    const int split = rest / a.n_ct;
+    const int cb0 = ct * NPI;  // first input channel block of the tile
+    const int kb0 = kt * NPO;  // first output channel block of the tile
+
+    const int NP = a.N * a.P;
+    const int rho_begin = split * a.rows_per_split;
+    const int rho_end = min(NP, rho_begin + a.rows_per_split);
+    const int Qp = (a.Q + 1) & ~1;
+    const int npxO = a.TR * Qp;
+    const int HW = a.H * a.W;
+    const int PQ = a.P * a.Q;
+    const int ls = a.sampled ? 1 : a.stride;
+
+    u32x4 ireg[PPTI];
+    u32x4 oreg[PPTO];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    auto fetch = [&](int rho0) {
+        const int n0 = rho0 / a.P;
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const u32x4 *ip = static_cast<const u32x4 *>(a.in);
+        const u32x4 *op = static_cast<const u32x4 *>(a.dout);
+#pragma unroll
+        for (int i = 0; i < PPTI; ++i) {
+            const int ci = tid + i * NT;
+            u32x4 v = zero4;
+            if (ci < NPI * a.LRW) {
+                const int pl = ci / a.LRW;
+                const int p = ci - pl * a.LRW;
+                const int row = p / a.LW;
+                const int col = p - row * a.LW;
+                int n, ih, iw;
+                bool ok;
+                if (a.sampled) {
+                    const int rho = rho0 + row;
+                    n = rho / a.P;
+                    ih = (rho - n * a.P) * a.stride;
+                    iw = col * a.stride;
+                    ok = rho < rho_end && col < a.Q;
+                } else {
+                    const int lam = lam0 + row;
+                    n = lam / a.Hs;
+                    ih = lam - n * a.Hs - a.pad;
+                    iw = col - a.pad;
+                    ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+                }
+                ok = ok && (cb0 + pl) < a.Cb;
+                if (ok) v = ip[((size_t)(n * a.Cb + cb0 + pl) * a.H + ih) * a.W + iw];
+            }
+            ireg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < PPTO; ++i) {
+            const int ci = tid + i * NT;
+            u32x4 v = zero4;
+            if (ci < NPO * npxO) {
+                const int pl = ci / npxO;
+                const int p = ci - pl * npxO;
+                const int trow = p / Qp;
+                const int col = p - trow * Qp;
+                const int rho = rho0 + trow;
+                if (rho < rho_end && col < a.Q && (kb0 + pl) < a.Kb) {
+                    const int n = rho / a.P;
+                    const int oj = rho - n * a.P;
+                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Q + col];
+                }
+            }
+            oreg[i] = v;
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < PPTI; ++i) {
+            const int ci = tid + i * NT;
+            if (ci < NPI * a.LRW) {
+                const int pl = ci / a.LRW;
+                const int p = ci - pl * a.LRW;
+                *reinterpret_cast<u32x4 *>(ldsI + ((size_t)pl * a.PLS_in + p) * V) = ireg[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PPTO; ++i) {
+            const int ci = tid + i * NT;
+            if (ci < NPO * npxO) {
+                const int pl = ci / npxO;
+                const int p = ci - pl * npxO;
+                *reinterpret_cast<u32x4 *>(ldsO + ((size_t)pl * a.PLS_out + p) * V) = oreg[i];
+            }
+        }
+    };
+
+    f32x16 acc[NTAPS][FC][FK];
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.0f;
+
+    // LDS element offsets of this lane's channel within a staged pixel
+    int a_lane[FC], b_lane[FK];
+#pragma unroll
+    for (int i = 0; i < FC; ++i) {
+        const int c = (wave_c * FC + i) * 32 + l32;
+        a_lane[i] = (c / V) * a.PLS_in * V + (c % V);
+    }
+#pragma unroll
+    for (int j = 0; j < FK; ++j) {
+        const int k = (wave_k * FK + j) * 32 + l32;
+        b_lane[j] = (k / V) * a.PLS_out * V + (k % V);
+    }
+
+    if (rho_begin < rho_end) fetch(rho_begin);
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR) {
+        __syncthreads();  // everyone is done reading the previous band
+        commit();
+        __syncthreads();
+        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR);
+
+        const int n0 = rho0 / a.P;
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int rows = min(a.TR, rho_end - rho0);
+        for (int trow = 0; trow < rows; ++trow) {
+            const int rho = rho0 + trow;
+            const int n = rho / a.P;
+            const int oj = rho - n * a.P;
+            const int lrow = a.sampled ? trow : (n * a.Hs + oj * a.stride - lam0);
+            const int irow = lrow * a.LW;
+            const int orow = trow * Qp;
+#pragma unroll 2
+            for (int col = h; col < Qp; col += 2) {
+                float bv[FK];
+#pragma unroll
+                for (int j = 0; j < FK; ++j) bv[j] = ldsO[b_lane[j] + (orow + col) * V];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int s = 0; s < S; ++s) {
+#pragma unroll
+                        for (int i = 0; i < FC; ++i) {
+                            const float av =
+                                ldsI[a_lane[i] + (irow + r * a.LW + col * ls + s) * V];
+#pragma unroll
+                            for (int j = 0; j < FK; ++j)
+                                acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                    av, bv[j], acc[r * S + s][i][j], 0, 0, 0);
+                        }
+                    }
+            }
+        }
+    }
+
+    // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
+    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    float *dst = a.partial + (size_t)split * copy;
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j) {
+                const int k = kb0 * V + (wave_k * FK + j) * 32 + l32;
+                if (k >= a.Kp) continue;
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int c = cb0 * V + (wave_c * FC + i) * 32 + vq * 8 + h * 4;
+                    const int cb = c / V;
+                    if (cb >= a.Cb) continue;
+                    f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
+                               acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V) = v;
+                }
+            }
+}
+
+// dW[e] = sum_j partial[j][e], j ascending: deterministic.
+__global__ __launch_bounds__(256) void upd_reduce_kernel(const f32x4 *__restrict__ partial,
+                                                         f32x4 *__restrict__ dwt, size_t n4,
+                                                         int splits)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n4) return;
+    f32x4 s = partial[idx];
+    for (int j = 1; j < splits; ++j) {
+        const f32x4 v = partial[(size_t)j * n4 + idx];
+        s[0] += v[0];
+        s[1] += v[1];
+        s[2] += v[2];
+        s[3] += v[3];
+    }
+    dwt[idx] = s;
+}
+
+typedef void (*upd_fn_t)(const UpdArgs);
+struct UpdEntry {
+    UpdVariant v;
+    int fc, fk;
+    upd_fn_t fn;
+    size_t lds_attr;
+};
+
+#define UPD_F32_ENTRY(R, S, FC, FK, PI, PO)                                              \
+    {                                                                                    \
+        {CONV_F32, R, S, PI, PO}, FC, FK, upd_f32_kernel<R, S, FC, FK, PI, PO>, 0         \
+    }
+
+static UpdEntry g_upd[] = {
+    UPD_F32_ENTRY(3, 3, 1, 1, 16, 8),
+    UPD_F32_ENTRY(1, 1, 1, 1, 8, 8),
+};
+
+static UpdEntry *find_upd(const UpdVariant &v)
+{
+    for (auto &e : g_upd)
+        if (e.v.dtype == v.dtype && e.v.r == v.r && e.v.s == v.s && e.v.ppt_in == v.ppt_in &&
+            e.v.ppt_out == v.ppt_out)
+            return &e;
+    return nullptr;
+}
+
+bool upd_variant_exists(const UpdVariant &v) { return find_upd(v) != nullptr; }
+
+hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
+                      hipStream_t stream)
+{
+    UpdEntry *e = find_upd(v);
+    if (!e) return hipErrorInvalidDeviceFunction;
+    if (lds_bytes > e->lds_attr) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        e->lds_attr = lds_bytes;
+    }
+    hipLaunchKernelGGL(e->fn, dim3(grid), dim3(256), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
+                             hipStream_t stream)
+{
+    const size_t n4 = n_elems / 4;
+    hipLaunchKernelGGL(upd_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
+                       reinterpret_cast<const f32x4 *>(partial), reinterpret_cast<f32x4 *>(dwt), n4,
+                       splits);
+    return hipGetLastError();
+}
+
+}  // namespace convmi
