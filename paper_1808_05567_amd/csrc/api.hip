@@ -223,20 +223,24 @@ void plan_upd(conv_plan *p)
     const conv_info_t &f = p->info;
     p->upd_ok = false;
     p->upd_ws = 0;
-    if (d.dtype != CONV_F32) return;
     const bool sampled = (d.R == 1 && d.S == 1 && d.pad == 0);
-    int ppt_in, ppt_out;
-    if (d.R == 3 && d.S == 3) { ppt_in = 16; ppt_out = 8; }
-    else if (d.R == 1 && d.S == 1) { ppt_in = 8; ppt_out = 8; }
-    else return;
-    UpdVariant v{d.dtype, d.R, d.S, ppt_in, ppt_out};
+    const bool bf16 = d.dtype == CONV_BF16;
+    UpdVariant v{};
+    if (d.R == 3 && d.S == 3)
+        v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 16, 8};
+    else if (d.R == 1 && d.S == 1)
+        v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8} : UpdVariant{CONV_F32, 1, 1, 2, 2, 1, 1, 8, 8};
+    else
+        return;
     if (!upd_variant_exists(v)) return;
     const int V = f.vlen;
-    const int TC = 64, TK = 64, NPI = TC / V, NPO = TK / V, NT = 256;
-    const int Qp = (f.Q + 1) & ~1;
+    const int TC = v.wc * v.fc * 32, TK = v.wk * v.fk * 32, NPI = TC / V, NPO = TK / V, NT = 256;
+    // fp32 pairs pixels along a row (row pitch rounded up to even, zero padded);
+    // bf16 walks the band's pixels linearly in steps of 16.
+    const int Qp = bf16 ? f.Q : ((f.Q + 1) & ~1);
     const int NP = d.N * f.P;
-    int TR = std::min(NP, std::max(1, (ppt_out * NT / NPO) / Qp));
-    int Hs = 0, LW = 0, LR = 0;
+    int TR = std::min(NP, std::max(1, (v.ppt_out * NT / NPO) / Qp));
+    int Hs = 0, LW = 0, LR = 0, npxO = 0;
     for (;; --TR) {
         if (TR < 1) return;
         if (sampled) { Hs = f.P; LW = Qp; LR = TR; }
@@ -245,7 +249,8 @@ void plan_upd(conv_plan *p)
             LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * d.pad);
             LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, d.R);
         }
-        if (NPI * LR * LW <= ppt_in * NT && NPO * TR * Qp <= ppt_out * NT) break;
+        npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
+        if (NPI * LR * LW <= v.ppt_in * NT && NPO * npxO <= v.ppt_out * NT) break;
     }
     UpdArgs &a = p->ua;
     memset(&a, 0, sizeof(a));
@@ -261,10 +266,17 @@ void plan_upd(conv_plan *p)
     a.rows_per_split = rps;
     a.splits = splits;
     a.Hs = Hs; a.LW = LW; a.LRW = LR * LW;
-    // plane pitch = 1 (mod 8) pixels: the 8 channel blocks a 32-lane group
-    // reads land in different LDS banks
-    a.PLS_in = ((a.LRW + 7) / 8) * 8 + 1;
-    a.PLS_out = ((TR * Qp + 7) / 8) * 8 + 1;
+    if (bf16) {
+        // plane pitch = 8 (mod 16) pixels: the two channel planes a 16-lane
+        // transposing read touches sit half an LDS row apart
+        a.PLS_in = ((a.LRW + 15) / 16) * 16 + 8;
+        a.PLS_out = ((npxO + 15) / 16) * 16 + 8;
+    } else {
+        // plane pitch = 1 (mod 8) pixels: the 8 channel blocks a 32-lane group
+        // reads land in different LDS banks
+        a.PLS_in = ((a.LRW + 7) / 8) * 8 + 1;
+        a.PLS_out = ((npxO + 7) / 8) * 8 + 1;
+    }
     a.sampled = sampled ? 1 : 0;
     a.total = tiles * splits;
     a.per_xcd = ceil_div(a.total, 8);
@@ -477,9 +489,11 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
     if (pass == 2) {
         if (!h->upd_ok) return CONV_EUNSUPPORTED;
         snprintf(buf, buflen,
-                 "upd dt=%d RS=%dx%d TR=%d splits=%d rows/split=%d tiles=%dx%d grid=%d lds=%zu",
-                 h->uv.dtype, h->uv.r, h->uv.s, h->ua.TR, h->ua.splits, h->ua.rows_per_split,
-                 h->ua.n_ct, h->ua.n_kt, h->upd_grid, h->upd_lds);
+                 "upd dt=%d RS=%dx%d waves=%dx%d frags=%dx%d TR=%d splits=%d rows/split=%d "
+                 "tiles=%dx%d grid=%d lds=%zu",
+                 h->uv.dtype, h->uv.r, h->uv.s, h->uv.wc, h->uv.wk, h->uv.fc, h->uv.fk, h->ua.TR,
+                 h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt, h->upd_grid,
+                 h->upd_lds);
         return CONV_OK;
     }
     return CONV_EINVAL;

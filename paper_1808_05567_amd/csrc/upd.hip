@@ -231,6 +231,267 @@ __global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
             }
 }
 
+
+// bf16 activations and gradients (vlen 8), fp32 accumulation and output.
+//
+// The MFMA wants 8 consecutive reduction indices (pixels) per lane, while the
+// blocked layout keeps 8 channels of one pixel together -- the transpose the
+// paper pays for up front on Knights Mill (Section III-B).  Here the tiles stay
+// in LDS exactly as they sit in HBM ([plane][pixel][8 channels]) and the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b16) delivers, to the lane that
+// owns channel m, four consecutive pixels of that channel: within a group of 16
+// lanes, lane i slot j receives element (i % 4) of the 8 bytes addressed by lane
+// 4*j + i/4.  Lane s of a group therefore addresses [pixel s/4][channels 4*(s%4)..].
+// 256 threads = WC x WK waves; a wave owns FC x FK fragments per tap.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+static __device__ __forceinline__ u32x2 lds_read_tr16(const unsigned char *p)
+{
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    return __builtin_bit_cast(u32x2, v);
+}
+
+template <int R, int S, int WC, int WK, int FC, int FK, int PPTI, int PPTO>
+__global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
+{
+    constexpr int V = 8;
+    constexpr int NT = 256;
+    constexpr int NTAPS = R * S;
+    constexpr int TC = WC * FC * 32;
+    constexpr int TK = WK * FK * 32;
+    constexpr int NPI = TC / V;
+    constexpr int NPO = TK / V;
+    static_assert(WC * WK == 4, "four waves");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    unsigned char *ldsI = lds;
+    unsigned char *ldsO = lds + (size_t)NPI * a.PLS_in * 16;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int grp = (lane >> 4) & 1;  // which 16 rows of the 32-row fragment
+    const int i16 = lane & 15;
+    const int wave_c = wave % WC;
+    const int wave_k = wave / WC;
+
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int rest = lin / a.n_kt;
+    const int ct = rest % a.n_ct;
+    const int split = rest / a.n_ct;
+    const int cb0 = ct * NPI;
+    const int kb0 = kt * NPO;
+
+    const int NP = a.N * a.P;
+    const int rho_begin = split * a.rows_per_split;
+    const int rho_end = min(NP, rho_begin + a.rows_per_split);
+    const int npxO = ((a.TR * a.Q + 15) / 16) * 16;  // staged dO pixels, zero padded
+    const int ls = a.sampled ? 1 : a.stride;
+    const int gap = a.sampled ? 0 : a.Hs - a.P * a.stride;  // extra staged rows between images
+
+    u32x4 ireg[PPTI];
+    u32x4 oreg[PPTO];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    auto fetch = [&](int rho0) {
+        const int n0 = rho0 / a.P;
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const u32x4 *ip = static_cast<const u32x4 *>(a.in);
+        const u32x4 *op = static_cast<const u32x4 *>(a.dout);
+#pragma unroll
+        for (int i = 0; i < PPTI; ++i) {
+            const int ci = tid + i * NT;
+            u32x4 v = zero4;
+            if (ci < NPI * a.LRW) {
+                const int pl = ci / a.LRW;
+                const int p = ci - pl * a.LRW;
+                const int row = p / a.LW;
+                const int col = p - row * a.LW;
+                int n, ih, iw;
+                bool ok;
+                if (a.sampled) {
+                    const int rho = rho0 + row;
+                    n = rho / a.P;
+                    ih = (rho - n * a.P) * a.stride;
+                    iw = col * a.stride;
+                    ok = rho < rho_end && col < a.Q;
+                } else {
+                    const int lam = lam0 + row;
+                    n = lam / a.Hs;
+                    ih = lam - n * a.Hs - a.pad;
+                    iw = col - a.pad;
+                    ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+                }
+                ok = ok && (cb0 + pl) < a.Cb;
+                if (ok) v = ip[((size_t)(n * a.Cb + cb0 + pl) * a.H + ih) * a.W + iw];
+            }
+            ireg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < PPTO; ++i) {
+            const int ci = tid + i * NT;
+            u32x4 v = zero4;
+            if (ci < NPO * npxO) {
+                const int pl = ci / npxO;
+                const int p = ci - pl * npxO;
+                const int trow = p / a.Q;
+                const int col = p - trow * a.Q;
+                const int rho = rho0 + trow;
+                if (trow < a.TR && rho < rho_end && (kb0 + pl) < a.Kb) {
+                    const int n = rho / a.P;
+                    const int oj = rho - n * a.P;
+                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Q + col];
+                }
+            }
+            oreg[i] = v;
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < PPTI; ++i) {
+            const int ci = tid + i * NT;
+            if (ci < NPI * a.LRW) {
+                const int pl = ci / a.LRW;
+                const int p = ci - pl * a.LRW;
+                *reinterpret_cast<u32x4 *>(ldsI + ((size_t)pl * a.PLS_in + p) * 16) = ireg[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PPTO; ++i) {
+            const int ci = tid + i * NT;
+            if (ci < NPO * npxO) {
+                const int pl = ci / npxO;
+                const int p = ci - pl * npxO;
+                *reinterpret_cast<u32x4 *>(ldsO + ((size_t)pl * a.PLS_out + p) * 16) = oreg[i];
+            }
+        }
+    };
+
+    f32x16 acc[NTAPS][FC][FK];
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.0f;
+
+    // Byte offsets, within a staged tile, of the 4-channel group this lane
+    // addresses in a transposing read: channels 16*grp + 4*(i16 % 4) of a fragment.
+    int a_lane[FC], b_lane[FK];
+#pragma unroll
+    for (int i = 0; i < FC; ++i) {
+        const int c = (wave_c * FC + i) * 32 + grp * 16 + (i16 & 3) * 4;
+        a_lane[i] = (c / V) * a.PLS_in * 16 + (c % V) * 2;
+    }
+#pragma unroll
+    for (int j = 0; j < FK; ++j) {
+        const int k = (wave_k * FK + j) * 32 + grp * 16 + (i16 & 3) * 4;
+        b_lane[j] = (k / V) * a.PLS_out * 16 + (k % V) * 2;
+    }
+    // pixel (within a 16-pixel reduction step) this lane addresses, per half-read
+    const int pix_lane = 8 * h + (i16 >> 2);
+    // 16 = qa * Q + qb
+    const int qa = 16 / a.Q, qb = 16 - qa * a.Q;
+
+    if (rho_begin < rho_end) fetch(rho_begin);
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR) {
+        __syncthreads();
+        commit();
+        __syncthreads();
+        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR);
+
+        const int rows = min(a.TR, rho_end - rho0);
+        const int valid = rows * a.Q;
+        const int n0 = rho0 / a.P;
+        const int oj0 = rho0 - n0 * a.P;
+        // per-lane walk over the band's pixels m = 16*ks + pix_lane + 4*t
+        int col[2], oj[2], lrow[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int m = pix_lane + 4 * t;
+            const int trow = m / a.Q;
+            col[t] = m - trow * a.Q;
+            int o = oj0 + trow, lr = a.sampled ? trow : trow * a.stride;
+            while (o >= a.P) { o -= a.P; lr += gap; }
+            oj[t] = o;
+            lrow[t] = lr;
+        }
+        for (int m0 = 0; m0 < valid; m0 += 16) {
+            int ipix[2], opix[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int m = m0 + pix_lane + 4 * t;
+                const bool ok = m < valid;
+                ipix[t] = ok ? (lrow[t] * a.LW + col[t] * ls) * 16 : 0;
+                opix[t] = m * 16;  // zero padded beyond the valid pixels
+                // advance by 16 pixels
+                col[t] += qb;
+                int adv = qa;
+                if (col[t] >= a.Q) { col[t] -= a.Q; ++adv; }
+                oj[t] += adv;
+                lrow[t] += a.sampled ? adv : adv * a.stride;
+                while (oj[t] >= a.P) { oj[t] -= a.P; lrow[t] += gap; }
+            }
+            u32x4 bf[FK];
+#pragma unroll
+            for (int j = 0; j < FK; ++j) {
+                const u32x2 lo = lds_read_tr16(ldsO + b_lane[j] + opix[0]);
+                const u32x2 hi = lds_read_tr16(ldsO + b_lane[j] + opix[1]);
+                bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const int toff = (r * a.LW + s) * 16;
+#pragma unroll
+                    for (int i = 0; i < FC; ++i) {
+                        const u32x2 lo = lds_read_tr16(ldsI + a_lane[i] + ipix[0] + toff);
+                        const u32x2 hi = lds_read_tr16(ldsI + a_lane[i] + ipix[1] + toff);
+                        const u32x4 af = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+                        for (int j = 0; j < FK; ++j)
+                            acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf[j]),
+                                acc[r * S + s][i][j], 0, 0, 0);
+                    }
+                }
+        }
+    }
+
+    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    float *dst = a.partial + (size_t)split * copy;
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j) {
+                const int k = kb0 * V + (wave_k * FK + j) * 32 + l32;
+                if (k >= a.Kp) continue;
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int c = cb0 * V + (wave_c * FC + i) * 32 + vq * 8;
+                    const int cb = c / V;
+                    if (cb >= a.Cb) continue;
+                    f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
+                               acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V +
+                                               4 * h) = v;
+                }
+            }
+}
+
 // dW[e] = sum_j partial[j][e], j ascending: deterministic.
 __global__ __launch_bounds__(256) void upd_reduce_kernel(const f32x4 *__restrict__ partial,
                                                          f32x4 *__restrict__ dwt, size_t n4,
@@ -252,25 +513,32 @@ __global__ __launch_bounds__(256) void upd_reduce_kernel(const f32x4 *__restrict
 typedef void (*upd_fn_t)(const UpdArgs);
 struct UpdEntry {
     UpdVariant v;
-    int fc, fk;
     upd_fn_t fn;
     size_t lds_attr;
 };
 
 #define UPD_F32_ENTRY(R, S, FC, FK, PI, PO)                                              \
     {                                                                                    \
-        {CONV_F32, R, S, PI, PO}, FC, FK, upd_f32_kernel<R, S, FC, FK, PI, PO>, 0         \
+        {CONV_F32, R, S, 2, 2, FC, FK, PI, PO}, upd_f32_kernel<R, S, FC, FK, PI, PO>, 0   \
+    }
+#define UPD_BF16_ENTRY(R, S, WC, WK, FC, FK, PI, PO)                                     \
+    {                                                                                    \
+        {CONV_BF16, R, S, WC, WK, FC, FK, PI, PO},                                       \
+            upd_bf16_kernel<R, S, WC, WK, FC, FK, PI, PO>, 0                             \
     }
 
 static UpdEntry g_upd[] = {
     UPD_F32_ENTRY(3, 3, 1, 1, 16, 8),
     UPD_F32_ENTRY(1, 1, 1, 1, 8, 8),
+    UPD_BF16_ENTRY(3, 3, 2, 2, 1, 2, 8, 8),
+    UPD_BF16_ENTRY(1, 1, 2, 2, 2, 2, 8, 8),
 };
 
 static UpdEntry *find_upd(const UpdVariant &v)
 {
     for (auto &e : g_upd)
-        if (e.v.dtype == v.dtype && e.v.r == v.r && e.v.s == v.s && e.v.ppt_in == v.ppt_in &&
+        if (e.v.dtype == v.dtype && e.v.r == v.r && e.v.s == v.s && e.v.wc == v.wc &&
+            e.v.wk == v.wk && e.v.fc == v.fc && e.v.fk == v.fk && e.v.ppt_in == v.ppt_in &&
             e.v.ppt_out == v.ppt_out)
             return &e;
     return nullptr;

@@ -1,0 +1,62 @@
+"""Parity at the benchmark's full sizes (N = 256, the launch configuration
+bench.py times).  A full fp64 oracle pass is too slow there, so:
+  * forward / backward: images are independent -- the oracle computes every
+    output of a seeded subset of images (always the first and the last);
+  * update: the oracle computes a seeded subset of dW entries, each one a full
+    N*P*Q-long fp64 dot product (always including the corner taps/channels).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1808_05567_amd import conv, inputs
+
+from gpu_util import TOL, rel_l2, run_pass
+
+pytestmark = pytest.mark.gpu
+
+N = 256
+CASES = [(4, conv.CONV_F32), (8, conv.CONV_F32), (13, conv.CONV_F32), (18, conv.CONV_F32),
+         (2, conv.CONV_F32), (6, conv.CONV_F32), (17, conv.CONV_F32), (20, conv.CONV_F32),
+         (4, conv.CONV_BF16), (13, conv.CONV_BF16), (18, conv.CONV_BF16), (7, conv.CONV_BF16),
+         (14, conv.CONV_BF16)]
+
+
+def _entries(rng, K, C, R, S, count):
+    e = np.stack([rng.integers(0, K, count), rng.integers(0, C, count),
+                  rng.integers(0, R, count), rng.integers(0, S, count)], axis=1)
+    corners = [(k, c, r, s) for k in (0, K - 1) for c in (0, C - 1)
+               for r in (0, R - 1) for s in (0, S - 1)]
+    return np.concatenate([np.array(corners), e]).astype(np.int32)
+
+
+@pytest.mark.parametrize("lid,dtype", CASES,
+                         ids=["L%d-%s" % (l, "bf16" if d else "f32") for l, d in CASES])
+def test_table1_layer_at_n256(lid, dtype):
+    l = inputs.layer(lid)
+    print("layer", lid, "dtype", dtype, flush=True)
+    I = inputs.gen_input(N, l.C, l.H, l.W, lid)
+    Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
+    dO = inputs.gen_outgrad(N, l.K, l.P, l.Q, lid)
+    if dtype == conv.CONV_BF16:
+        I, Wt, dO = (inputs.round_to_bf16(x) for x in (I, Wt, dO))
+    rng = np.random.default_rng(1000 + lid)
+    imgs = sorted({0, N - 1, *rng.integers(1, N - 1, 2).tolist()})
+    L = conv.ConvLayer(N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dtype)
+    try:
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+        ref = oracle.fwd(I[imgs], Wt, l.stride, l.pad)
+        assert rel_l2(got[imgs], ref) <= TOL[dtype]
+        assert np.isfinite(got).all()
+        got = run_pass(L, "bwd", dO=dO, Wt=Wt)
+        ref = oracle.bwd_data(dO[imgs], Wt, l.H, l.W, l.stride, l.pad)
+        assert rel_l2(got[imgs], ref) <= TOL[dtype]
+        assert np.isfinite(got).all()
+        got = run_pass(L, "upd", I=I, dO=dO)
+        ent = _entries(rng, l.K, l.C, l.R, l.S, 1024)
+        ref = oracle.upd_entries(I.astype(np.float64), dO.astype(np.float64), l.R, l.S,
+                                 l.stride, l.pad, ent)
+        assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5
+        assert np.isfinite(got).all()
+    finally:
+        L.close()

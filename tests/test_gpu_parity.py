@@ -1,0 +1,117 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU
+oracle on the same seeded inputs.  Bars: rel-L2 <= 1e-5 (fp32), <= 1e-2 (bf16
+inputs, fp32 accumulation); integer-valued inputs must match exactly."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1808_05567_amd import conv, inputs
+
+from gpu_util import TOL, make_inputs, rel_l2, run_pass
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [pytest.param(conv.CONV_F32, id="f32"), pytest.param(conv.CONV_BF16, id="bf16")]
+
+# N, C, K, H, W, R, S, stride, pad -- small enough for a full-tensor oracle run,
+# large enough to span several tiles, ragged tails and every kernel variant.
+SMALL = [
+    (2, 64, 64, 14, 14, 3, 3, 1, 1),      # benchmark config 1
+    (3, 8, 12, 9, 11, 3, 3, 1, 1),        # rectangular image, K below a tile
+    (2, 16, 136, 7, 7, 3, 3, 1, 1),       # ragged channel tile, bands cross images
+    (5, 128, 128, 28, 28, 3, 3, 1, 1),    # several row tiles with a ragged last one
+    (2, 20, 24, 8, 8, 3, 3, 1, 1),        # odd number of channel blocks
+    (2, 24, 40, 12, 10, 3, 3, 1, 0),      # no padding
+    (2, 64, 64, 14, 14, 1, 1, 1, 0),
+    (3, 64, 256, 56, 56, 1, 1, 1, 0),
+    (2, 32, 160, 9, 9, 1, 1, 2, 0),       # stride 2, odd image
+    (3, 256, 128, 16, 16, 1, 1, 2, 0),
+    (2, 4, 8, 8, 8, 1, 1, 1, 0),          # a single channel block
+    (1, 16, 16, 5, 5, 3, 3, 1, 1),        # one tiny image (inference shape)
+]
+
+
+def _layer(shape, dtype):
+    return conv.ConvLayer(*shape, dtype=dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
+def test_three_passes_match_oracle(shape, dtype):
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=len(str(shape)))
+    L = _layer(shape, dtype)
+    try:
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+        assert rel_l2(got, oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        got = run_pass(L, "bwd", dO=dO, Wt=Wt)
+        assert rel_l2(got, oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        got = run_pass(L, "upd", I=I, dO=dO)
+        # weight gradients are fp32 for both dtypes; bf16 products are exact in fp32
+        assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+    finally:
+        L.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(3, 32, 48, 14, 14, 3, 3, 1, 1), (2, 64, 32, 12, 12, 1, 1, 2, 0)],
+                         ids=["3x3", "1x1s2"])
+def test_integer_inputs_are_exact(shape, dtype):
+    """Small integers: every product and partial sum is exact in fp32 (and the
+    values are exact in bf16), so any summation order gives the oracle's bits."""
+    N, C, K, H, W, R, S, stride, pad = shape
+    P, Q = oracle.out_hw(H, W, R, S, stride, pad)
+    I = inputs.gen_small_ints((N, C, H, W), -2, 2, which=3)
+    Wt = inputs.gen_small_ints((K, C, R, S), -2, 2, which=4)
+    dO = inputs.gen_small_ints((N, K, P, Q), -2, 2, which=5)
+    L = _layer(shape, dtype)
+    try:
+        # bf16 outputs hold integers exactly only up to 256: 4*C*R*S must stay below
+        # that for an exact bf16 store, so compare fwd/bwd exactly in fp32 only
+        got = run_pass(L, "upd", I=I, dO=dO)
+        assert np.array_equal(got, oracle.upd(I, dO, R, S, stride, pad))
+        if dtype == conv.CONV_F32:
+            assert np.array_equal(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad))
+            assert np.array_equal(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                                  oracle.bwd_data(dO, Wt, H, W, stride, pad))
+        else:
+            assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= 4e-3
+    finally:
+        L.close()
+
+
+def test_pack_unpack_roundtrip_and_padding():
+    import torch
+    shape = (2, 10, 6, 5, 7, 3, 3, 1, 1)  # C, K not multiples of the block
+    for dtype in (conv.CONV_F32, conv.CONV_BF16):
+        I, Wt, dO = make_inputs(shape, dtype)
+        L = _layer(shape, dtype)
+        try:
+            L.in_blk.fill_(float("nan")); L.wt_blk.fill_(float("nan")); L.out_blk.fill_(float("nan"))
+            L.set_input(I); L.set_weights(Wt); L.set_outgrad(dO)
+            assert np.array_equal(L.get_input().float().cpu().numpy(), I)
+            assert np.array_equal(L.get_weights().float().cpu().numpy(), Wt)
+            assert np.array_equal(L.get_output().float().cpu().numpy(), dO)
+            v = L.info.vlen
+            blk = L.in_blk.float().view(2, L.info.Cb, 5, 7, v).cpu().numpy()
+            assert np.all(blk[:, -1, :, :, 10 % v:] == 0)          # padded channel slots are zero
+            assert np.array_equal(blk[:, 1, :, :, 0], I[:, v])      # channel v sits in block 1, slot 0
+            w = L.wt_blk.float().view(L.info.Cb, 3, 3, L.info.Kp, v).cpu().numpy()
+            assert np.array_equal(w[0, 1, 2, 5, 3], Wt[5, 3, 1, 2])
+            assert np.all(w[:, :, :, 6:, :] == 0)
+        finally:
+            L.close()
+        torch.cuda.synchronize()
+
+
+def test_upd_is_bitwise_deterministic():
+    shape = (4, 64, 64, 28, 28, 3, 3, 1, 1)
+    I, Wt, dO = make_inputs(shape, conv.CONV_F32)
+    L = _layer(shape, conv.CONV_F32)
+    try:
+        a = run_pass(L, "upd", I=I, dO=dO)
+        b = run_pass(L, "upd", I=I, dO=dO)
+        assert np.array_equal(a, b)
+        assert L.info.upd_splits > 1
+    finally:
+        L.close()
