@@ -67,11 +67,11 @@ int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
     return best;
 }
 
-// Plan one launch of the implicit-GEMM kernel.
-//   input tensor:  N x Cb blocks x H x W;  result extent P x Q;  A rows Kp.
-IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
-                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                     int zero_fill)
+// One candidate plan of the implicit-GEMM kernel: `wk` waves along channels,
+// dynamic LDS at most `lds_cap` bytes.  Returns ok=false if nothing fits.
+IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
+                    int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
+                    int zero_fill, int wk, int wm, int fk, size_t lds_cap)
 {
     IgemmPlan pl;
     const int V = vlen_of(dtype);
@@ -85,12 +85,10 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
     else
         npl = 1;
 
-    const int wk = (Kp > 64 && npl != 1) ? 4 : 2;
-    const int wm = 4 / wk;
-    const int fk = 1, fm = 7;
+    const int fm = 7;
     const int TK = wk * fk * 32, TM = wm * fm * 32, NT = 256;
+    const int nent = ((R * S * npl + 1) / 2) * 2;
 
-    // candidate staged-pixels-per-thread values instantiated for this shape
     int ppt = -1;
     int TQ = std::min(Q, TM);
     int TR = std::max(1, TM / TQ);
@@ -116,10 +114,8 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
                 break;
             }
         }
-        const int nent = ((R * S * npl + 1) / 2) * 2;
         const size_t lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * LR * LW * 16);
-        if (ppt > 0 && lds <= (size_t)kMaxLds) break;
-        if (TR == 1) return pl;
+        if (ppt > 0 && lds <= lds_cap) break;
     }
 
     IgemmArgs &a = pl.a;
@@ -137,7 +133,6 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
     a.per_xcd = ceil_div(a.total, 8);
     a.n_stage = ceil_div(Cb, npl);
     pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt};
-    const int nent = ((R * S * npl + 1) / 2) * 2;
     pl.lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
     pl.grid = a.per_xcd * 8;
     // 32-bit index guards (offsets are kept in 16-byte units / elements)
@@ -145,6 +140,51 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
     if (in_units > 2.0e9 || out_units > 2.0e9) return pl;
     pl.ok = true;
     return pl;
+}
+
+// MFMA work a plan issues relative to the useful work: padded pixel slots of
+// the tiles and padded channel rows both cost full MFMA time.
+double igemm_waste(const IgemmPlan &p, int N, int P, int Q, int Kp)
+{
+    const double TM = p.v.wm * p.v.fm * 32.0, TK = p.v.wk * p.v.fk * 32.0;
+    return (p.a.n_mt * p.a.n_qt * TM * p.a.n_kt * TK) / ((double)N * P * Q * Kp);
+}
+
+// Plan one launch of the implicit-GEMM kernel.
+//   input tensor:  N x Cb blocks x H x W;  result extent P x Q;  A rows Kp.
+// Candidates: 4 or 2 waves along channels, tile within half of the LDS (two
+// workgroups per CU overlap each other's barriers and staging) or all of it.
+// Preference: least wasted MFMA work, then two workgroups per CU, then the
+// wider channel tile (fewer re-reads of the input tile).
+IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
+                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
+                     int zero_fill)
+{
+    IgemmPlan best;
+    double best_cost = 0;
+    const size_t caps[2] = {(size_t)kMaxLds / 2, (size_t)kMaxLds};
+    struct Cand { int wk, wm, fk; };
+    // bf16: two channel fragments per wave halve the LDS reads per MFMA (one
+    // fragment per wave cannot keep the bf16 matrix core fed from 128 B/clk of LDS)
+    const Cand cands[4] = {{2, 2, 2}, {1, 4, 2}, {4, 1, 1}, {2, 2, 1}};
+    for (int ci = 0; ci < 2; ++ci)
+        for (const Cand &cd : cands) {
+            if (cd.fk == 2 && dtype != CONV_BF16) continue;
+            const int TK = cd.wk * cd.fk * 32;
+            if (TK > 64 && Kp <= TK / 2) continue;
+            IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
+                                    ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, caps[ci]);
+            if (!c.ok) continue;
+            // one workgroup per CU loses roughly a fifth to exposed barriers/staging
+            double cost = igemm_waste(c, N, P, Q, Kp) * (ci == 0 ? 1.0 : 1.2) *
+                          (1.0 + 0.01 * (128 / TK));
+            if (dtype == CONV_BF16 && cd.fk == 1) cost *= 1.5;
+            if (!best.ok || cost < best_cost) {
+                best = c;
+                best_cost = cost;
+            }
+        }
+    return best;
 }
 
 void plan_bwd(conv_plan *p)
@@ -227,9 +267,10 @@ void plan_upd(conv_plan *p)
     const bool bf16 = d.dtype == CONV_BF16;
     UpdVariant v{};
     if (d.R == 3 && d.S == 3)
-        v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 16, 8};
+        v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
     else if (d.R == 1 && d.S == 1)
-        v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8} : UpdVariant{CONV_F32, 1, 1, 2, 2, 1, 1, 8, 8};
+        v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8}
+                 : UpdVariant{CONV_F32, 1, 1, 2, 2, f.Cp > 64 ? 2 : 1, f.Kp > 64 ? 2 : 1, 4, 4};
     else
         return;
     if (!upd_variant_exists(v)) return;
@@ -239,7 +280,12 @@ void plan_upd(conv_plan *p)
     // bf16 walks the band's pixels linearly in steps of 16.
     const int Qp = bf16 ? f.Q : ((f.Q + 1) & ~1);
     const int NP = d.N * f.P;
-    int TR = std::min(NP, std::max(1, (v.ppt_out * NT / NPO) / Qp));
+    // staged pixels a band may hold (see the staging maps of the two kernels)
+    const int max_px_in = bf16 ? v.ppt_in * NT / NPI : NT / v.ppt_in;
+    const int max_px_out = bf16 ? v.ppt_out * NT / NPO : NT / v.ppt_out;
+    // fp32 tiles are kept below half of the LDS so that two workgroups share a CU
+    const size_t lds_cap = bf16 ? (size_t)kMaxLds : (size_t)kMaxLds / 2;
+    int TR = std::min(NP, std::max(1, max_px_out / Qp));
     int Hs = 0, LW = 0, LR = 0, npxO = 0;
     for (;; --TR) {
         if (TR < 1) return;
@@ -250,7 +296,8 @@ void plan_upd(conv_plan *p)
             LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, d.R);
         }
         npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
-        if (NPI * LR * LW <= v.ppt_in * NT && NPO * npxO <= v.ppt_out * NT) break;
+        const size_t lds_est = ((size_t)NPI * (LR * LW + 16) + (size_t)NPO * (npxO + 16)) * 16;
+        if (LR * LW <= max_px_in && npxO <= max_px_out && lds_est <= lds_cap) break;
     }
     UpdArgs &a = p->ua;
     memset(&a, 0, sizeof(a));

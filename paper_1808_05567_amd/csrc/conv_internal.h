@@ -95,7 +95,8 @@ struct UpdVariant {
     int r, s;
     int wc, wk;            // waves along input / output channels
     int fc, fk;            // 32x32 fragments per wave along input / output channels
-    int ppt_in, ppt_out;   // staged 16-byte chunks per thread (input band, dO band)
+    int ppt_in, ppt_out;   // bf16: staged 16-byte chunks per thread (input band, dO band);
+                           // fp32: plane groups of the staging map (input band, dO band)
 };
 hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
                       hipStream_t stream);

@@ -352,6 +352,12 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 1, 1, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 3, 3, 3),
+    // bf16, two channel fragments per wave: every staged-input fragment read
+    // from LDS feeds two MFMAs (LDS bandwidth is what bounds bf16 otherwise)
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 2, 7, 2, 3, 3, 3),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 7, 2, 3, 3, 5),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 2, 7, 4, 1, 1, 2),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 7, 4, 1, 1, 4),
 };
 
 static IgemmEntry *find_igemm(const IgemmVariant &v)

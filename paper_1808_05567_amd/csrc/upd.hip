@@ -23,18 +23,30 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Exact floor(x / d) for 0 <= x < 2^22 with inv = 1.0f / d: (x + 0.5) / d is
+// never an integer and stays 0.5/d away from one, more than the rounding error.
+static __device__ __forceinline__ int fast_div(int x, float inv)
+{
+    return (int)(((float)x + 0.5f) * inv);
+}
+
 // fp32 activations and gradients (vlen 4).  256 threads = 2 x 2 waves over
 // (input channels, output channels); a wave owns FC x FK fragments per tap.
-template <int R, int S, int FC, int FK, int PPTI, int PPTO>
-__global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
+// Tiles are small enough for two workgroups per CU: one computes while the
+// other stages its next band, so the staging is a plain load -> LDS copy.
+// Staging map: thread -> (pixel p = tid % (256/G), plane group g = tid / (256/G)),
+// planes g, g+G, ...; GI / GO are the group counts for the input / dO band.
+template <int R, int S, int FC, int FK, int GI, int GO, bool PREFETCH>
+__global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
 {
     constexpr int V = 4;
-    constexpr int NT = 256;
     constexpr int NTAPS = R * S;
     constexpr int TC = 2 * FC * 32;
     constexpr int TK = 2 * FK * 32;
     constexpr int NPI = TC / V;  // staged input planes
     constexpr int NPO = TK / V;  // staged dO planes
+    constexpr int PXI = 256 / GI, PXO = 256 / GO;
+    static_assert(NPI % GI == 0 && NPO % GO == 0, "plane groups");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     float *ldsI = reinterpret_cast<float *>(lds);
@@ -66,82 +78,67 @@ __global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
     const int HW = a.H * a.W;
     const int PQ = a.P * a.Q;
     const int ls = a.sampled ? 1 : a.stride;
-
-    u32x4 ireg[PPTI];
-    u32x4 oreg[PPTO];
+    const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
+    const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
+    // Stage the input halo band and the dO band of linear rows [rho0, rho0+TR):
+    // fetch() loads into registers, commit() writes them to LDS.  With PREFETCH
+    // the next band's loads are in flight while the current one is consumed.
+    u32x4 vi[NPI / GI], vo[NPO / GO];
+    const int gi = tid / PXI, pi = tid - gi * PXI;
+    const int go = tid / PXO, po = tid - go * PXO;
     auto fetch = [&](int rho0) {
-        const int n0 = rho0 / a.P;
+        const int n0 = fast_div(rho0, inv_P);
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
-        const u32x4 *ip = static_cast<const u32x4 *>(a.in);
-        const u32x4 *op = static_cast<const u32x4 *>(a.dout);
-#pragma unroll
-        for (int i = 0; i < PPTI; ++i) {
-            const int ci = tid + i * NT;
-            u32x4 v = zero4;
-            if (ci < NPI * a.LRW) {
-                const int pl = ci / a.LRW;
-                const int p = ci - pl * a.LRW;
-                const int row = p / a.LW;
-                const int col = p - row * a.LW;
-                int n, ih, iw;
-                bool ok;
-                if (a.sampled) {
-                    const int rho = rho0 + row;
-                    n = rho / a.P;
-                    ih = (rho - n * a.P) * a.stride;
-                    iw = col * a.stride;
-                    ok = rho < rho_end && col < a.Q;
-                } else {
-                    const int lam = lam0 + row;
-                    n = lam / a.Hs;
-                    ih = lam - n * a.Hs - a.pad;
-                    iw = col - a.pad;
-                    ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-                }
-                ok = ok && (cb0 + pl) < a.Cb;
-                if (ok) v = ip[((size_t)(n * a.Cb + cb0 + pl) * a.H + ih) * a.W + iw];
+        if (pi < a.LRW) {
+            const int row = fast_div(pi, inv_LW);
+            const int col = pi - row * a.LW;
+            int n, ih, iw;
+            bool ok;
+            if (a.sampled) {
+                const int rho = rho0 + row;
+                n = fast_div(rho, inv_P);
+                ih = (rho - n * a.P) * a.stride;
+                iw = col * a.stride;
+                ok = rho < rho_end && col < a.Q;
+            } else {
+                const int lam = lam0 + row;
+                n = fast_div(lam, inv_Hs);
+                ih = lam - n * a.Hs - a.pad;
+                iw = col - a.pad;
+                ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
-            ireg[i] = v;
+            const u32x4 *ip = static_cast<const u32x4 *>(a.in) +
+                              ((size_t)(n * a.Cb + cb0 + gi) * a.H + ih) * a.W + iw;
+#pragma unroll
+            for (int j = 0; j < NPI / GI; ++j)
+                vi[j] = (ok && cb0 + gi + GI * j < a.Cb) ? ip[(size_t)j * GI * HW] : zero4;
         }
+        if (po < npxO) {
+            const int trow = fast_div(po, inv_Qp);
+            const int col = po - trow * Qp;
+            const int rho = rho0 + trow;
+            const int n = fast_div(rho, inv_P);
+            const int oj = rho - n * a.P;
+            const bool ok = rho < rho_end && col < a.Q;
+            const u32x4 *op = static_cast<const u32x4 *>(a.dout) +
+                              ((size_t)(n * a.Kb + kb0 + go) * a.P + oj) * a.Q + col;
 #pragma unroll
-        for (int i = 0; i < PPTO; ++i) {
-            const int ci = tid + i * NT;
-            u32x4 v = zero4;
-            if (ci < NPO * npxO) {
-                const int pl = ci / npxO;
-                const int p = ci - pl * npxO;
-                const int trow = p / Qp;
-                const int col = p - trow * Qp;
-                const int rho = rho0 + trow;
-                if (rho < rho_end && col < a.Q && (kb0 + pl) < a.Kb) {
-                    const int n = rho / a.P;
-                    const int oj = rho - n * a.P;
-                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Q + col];
-                }
-            }
-            oreg[i] = v;
+            for (int j = 0; j < NPO / GO; ++j)
+                vo[j] = (ok && kb0 + go + GO * j < a.Kb) ? op[(size_t)j * GO * PQ] : zero4;
         }
     };
     auto commit = [&]() {
+        if (pi < a.LRW) {
 #pragma unroll
-        for (int i = 0; i < PPTI; ++i) {
-            const int ci = tid + i * NT;
-            if (ci < NPI * a.LRW) {
-                const int pl = ci / a.LRW;
-                const int p = ci - pl * a.LRW;
-                *reinterpret_cast<u32x4 *>(ldsI + ((size_t)pl * a.PLS_in + p) * V) = ireg[i];
-            }
+            for (int j = 0; j < NPI / GI; ++j)
+                *reinterpret_cast<u32x4 *>(ldsI + ((size_t)(gi + GI * j) * a.PLS_in + pi) * V) = vi[j];
         }
+        if (po < npxO) {
 #pragma unroll
-        for (int i = 0; i < PPTO; ++i) {
-            const int ci = tid + i * NT;
-            if (ci < NPO * npxO) {
-                const int pl = ci / npxO;
-                const int p = ci - pl * npxO;
-                *reinterpret_cast<u32x4 *>(ldsO + ((size_t)pl * a.PLS_out + p) * V) = oreg[i];
-            }
+            for (int j = 0; j < NPO / GO; ++j)
+                *reinterpret_cast<u32x4 *>(ldsO + ((size_t)(go + GO * j) * a.PLS_out + po) * V) = vo[j];
         }
     };
 
@@ -168,12 +165,13 @@ __global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
         b_lane[j] = (k / V) * a.PLS_out * V + (k % V);
     }
 
-    if (rho_begin < rho_end) fetch(rho_begin);
+    if (PREFETCH && rho_begin < rho_end) fetch(rho_begin);
     for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR) {
         __syncthreads();  // everyone is done reading the previous band
+        if (!PREFETCH) fetch(rho0);
         commit();
         __syncthreads();
-        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR);
+        if (PREFETCH && rho0 + a.TR < rho_end) fetch(rho0 + a.TR);
 
         const int n0 = rho0 / a.P;
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
@@ -230,7 +228,6 @@ __global__ __launch_bounds__(256) void upd_f32_kernel(const UpdArgs a)
                 }
             }
 }
-
 
 // bf16 activations and gradients (vlen 8), fp32 accumulation and output.
 //
@@ -492,22 +489,39 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
             }
 }
 
-// dW[e] = sum_j partial[j][e], j ascending: deterministic.
+// dW[e] = sum_j partial[j][e] in a fixed order: 8 interleaved chains over j
+// (chain g takes j = g, g+8, ...), each ascending, then chains 0..7 ascending.
 __global__ __launch_bounds__(256) void upd_reduce_kernel(const f32x4 *__restrict__ partial,
                                                          f32x4 *__restrict__ dwt, size_t n4,
                                                          int splits)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n4) return;
-    f32x4 s = partial[idx];
-    for (int j = 1; j < splits; ++j) {
-        const f32x4 v = partial[(size_t)j * n4 + idx];
-        s[0] += v[0];
-        s[1] += v[1];
-        s[2] += v[2];
-        s[3] += v[3];
+    __shared__ f32x4 part[8][32];
+    const int colt = threadIdx.x & 31;
+    const int g = threadIdx.x >> 5;
+    const size_t idx = (size_t)blockIdx.x * 32 + colt;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (idx < n4) {
+        for (int j = g; j < splits; j += 8) {
+            const f32x4 v = partial[(size_t)j * n4 + idx];
+            s[0] += v[0];
+            s[1] += v[1];
+            s[2] += v[2];
+            s[3] += v[3];
+        }
     }
-    dwt[idx] = s;
+    part[g][colt] = s;
+    __syncthreads();
+    if (g == 0 && idx < n4) {
+        f32x4 t = part[0][colt];
+        for (int q = 1; q < 8; ++q) {
+            const f32x4 v = part[q][colt];
+            t[0] += v[0];
+            t[1] += v[1];
+            t[2] += v[2];
+            t[3] += v[3];
+        }
+        dwt[idx] = t;
+    }
 }
 
 typedef void (*upd_fn_t)(const UpdArgs);
@@ -517,9 +531,9 @@ struct UpdEntry {
     size_t lds_attr;
 };
 
-#define UPD_F32_ENTRY(R, S, FC, FK, PI, PO)                                              \
+#define UPD_F32_ENTRY(R, S, FC, FK, GI, GO, PF)                                          \
     {                                                                                    \
-        {CONV_F32, R, S, 2, 2, FC, FK, PI, PO}, upd_f32_kernel<R, S, FC, FK, PI, PO>, 0   \
+        {CONV_F32, R, S, 2, 2, FC, FK, GI, GO}, upd_f32_kernel<R, S, FC, FK, GI, GO, PF>, 0 \
     }
 #define UPD_BF16_ENTRY(R, S, WC, WK, FC, FK, PI, PO)                                     \
     {                                                                                    \
@@ -528,8 +542,11 @@ struct UpdEntry {
     }
 
 static UpdEntry g_upd[] = {
-    UPD_F32_ENTRY(3, 3, 1, 1, 16, 8),
-    UPD_F32_ENTRY(1, 1, 1, 1, 8, 8),
+    UPD_F32_ENTRY(3, 3, 1, 1, 1, 4, false),
+    UPD_F32_ENTRY(1, 1, 1, 1, 4, 4, true),
+    UPD_F32_ENTRY(1, 1, 1, 2, 4, 4, true),
+    UPD_F32_ENTRY(1, 1, 2, 1, 4, 4, true),
+    UPD_F32_ENTRY(1, 1, 2, 2, 4, 4, true),
     UPD_BF16_ENTRY(3, 3, 2, 2, 1, 2, 8, 8),
     UPD_BF16_ENTRY(1, 1, 2, 2, 2, 2, 8, 8),
 };
@@ -566,7 +583,7 @@ hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, i
                              hipStream_t stream)
 {
     const size_t n4 = n_elems / 4;
-    hipLaunchKernelGGL(upd_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(upd_reduce_kernel, dim3((unsigned)((n4 + 31) / 32)), dim3(256), 0, stream,
                        reinterpret_cast<const f32x4 *>(partial), reinterpret_cast<f32x4 *>(dwt), n4,
                        splits);
     return hipGetLastError();
