@@ -114,7 +114,8 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
                 break;
             }
         }
-        const size_t lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * LR * LW * 16);
+        // the plane pitch is a whole number of wave-level (64-lane) loads
+        const size_t lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * ceil_div(LR * LW, 64) * 64 * 16);
         if (ppt > 0 && lds <= lds_cap) break;
     }
 
@@ -127,7 +128,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.n_qt = ceil_div(Q, TQ);
     a.n_mt = ceil_div(N * P, TR);
     a.n_kt = ceil_div(Kp, TK);
-    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW; a.PLS = LR * LW;
+    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW; a.PLS = ceil_div(LR * LW, 64) * 64;
     a.sampled = sampled ? 1 : 0;
     a.total = a.n_mt * a.n_qt * a.n_kt;
     a.per_xcd = ceil_div(a.total, 8);
@@ -136,8 +137,11 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     pl.lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
     pl.grid = a.per_xcd * 8;
     // 32-bit index guards (offsets are kept in 16-byte units / elements)
+    // tensors are addressed with 32-bit byte offsets
     const double in_units = (double)N * Cb * H * W, out_units = (double)N * (Kp / V) * OH * OW;
-    if (in_units > 2.0e9 || out_units > 2.0e9) return pl;
+    if (in_units * 16 > 4.0e9 || out_units * 16 > 4.0e9) return pl;
+    // the kernels divide small indices through a float reciprocal, exact below 2^22
+    if ((double)(N + 1) * std::max(Hs, P) >= 4.0e6 || a.LRW >= (1 << 22)) return pl;
     pl.ok = true;
     return pl;
 }

@@ -114,6 +114,13 @@ hipError_t launch_pack_wt(int dtype, const void *kcrs, void *blk, int K, int C, 
 hipError_t launch_unpack_wt(int dtype, const void *blk, void *kcrs, int K, int C, int R, int S,
                             int vlen, hipStream_t stream);
 
+// Exact floor(x / d) for 0 <= x < 2^22 with inv = 1.0f / d: (x + 0.5) / d is
+// never an integer and stays 0.5/d away from one, more than the rounding error.
+static __device__ __forceinline__ int fast_div(int x, float inv)
+{
+    return (int)(((float)x + 0.5f) * inv);
+}
+
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int vlen_of(int dtype) { return dtype == CONV_BF16 ? 8 : 4; }
 static inline int esize_of(int dtype) { return dtype == CONV_BF16 ? 2 : 4; }

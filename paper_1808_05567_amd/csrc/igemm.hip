@@ -13,8 +13,8 @@
 //     and writes them once.
 //   * Section II-C: the input-channel loop is innermost around a resident
 //     output tile for every filter size.
-//   * Section II-E prefetching: the next channel step is fetched from HBM into
-//     registers while the current one is consumed from LDS (double buffer).
+//   * Section II-E prefetching: the next channel step streams from HBM straight
+//     into the second LDS buffer while the current one is consumed.
 //   * "Direct": the input halo tile is staged once per channel step and reused
 //     by all R*S taps out of LDS; no im2col copy exists anywhere.
 //   * Section II-F work split (N, then K_b, then P_b/Q_b): the grid enumerates
@@ -29,12 +29,37 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// Buffer addressing: a tensor is reached through a buffer resource
+// (base, byte size) plus a 32-bit per-lane byte offset.  Loads whose offset is
+// at or beyond the size return zero and stores there are dropped, so padding
+// and ragged tiles need no branches: such lanes carry the offset kOutOfRange.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOutOfRange = 0xFFFFFFFFu;
+static __device__ __forceinline__ rsrc_t make_rsrc(const void *base, size_t skip, size_t total)
+{
+    // view of [base + skip, base + total); the range check stays exact
+    return __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char *>(static_cast<const char *>(base)) + skip, 0,
+        (int)(unsigned)(total - skip), 0x00020000);
+}
+// 16-byte load from global memory straight into LDS: lane i of the wave writes
+// lds_wave_base + 16*i (the LDS base must be wave-uniform), zero if out of range.
+static __device__ __forceinline__ void load_to_lds_16(rsrc_t r, unsigned byte_off,
+                                                      unsigned char *lds_wave_base)
+{
+    typedef __attribute__((address_space(3))) void *lds_vptr_t;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, 0, 0, 0);
+}
+// Wait until every outstanding memory operation of this wave, staging loads included, is done.
+static __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+
 template <int DT>
 struct Elem;
 
 template <>
 struct Elem<CONV_F32> {
     static constexpr int V = 4;
+    static constexpr int ES = 4;
     // One 16-byte operand per lane carries 4 reduction indices; lanes 0-31 and
     // 32-63 hold different channel blocks, so four 32x32x2 MFMAs consume it.
     static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
@@ -44,13 +69,13 @@ struct Elem<CONV_F32> {
             c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[t]), __uint_as_float(b[t]),
                                                      c, 0, 0, 0);
     }
-    // Store 4 consecutive channels of one pixel.
-    static __device__ __forceinline__ void store4(void *base, size_t elem_off, float x0, float x1,
+    // Store 4 consecutive channels of one pixel (dropped if byte_off is out of range).
+    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, float x0, float x1,
                                                   float x2, float x3)
     {
         u32x4 v = {__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2),
                    __float_as_uint(x3)};
-        *reinterpret_cast<u32x4 *>(static_cast<float *>(base) + elem_off) = v;
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 0);
     }
 };
 
@@ -64,16 +89,17 @@ static __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 template <>
 struct Elem<CONV_BF16> {
     static constexpr int V = 8;
+    static constexpr int ES = 2;
     static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
     {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                     __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ void store4(void *base, size_t elem_off, float x0, float x1,
+    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, float x0, float x1,
                                                   float x2, float x3)
     {
         u32x2 v = {pack_bf16x2(x0, x1), pack_bf16x2(x2, x3)};
-        *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(base) + elem_off) = v;
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, 0, 0);
     }
 };
 
@@ -88,7 +114,7 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
     constexpr int NENT = ((NTAPS * NPL + 1) / 2) * 2;  // reduction entries per step, even
     constexpr int WCH = NENT * TK;                     // 16-byte weight chunks per step
     constexpr int WPT = (WCH + NT - 1) / NT;
-    constexpr int WBYTES = WCH * 16;
+    constexpr int WBYTES = WCH * 16;  // a multiple of 64 chunks: whole wave-level loads
     static_assert(NPL == 1 || NPL % 2 == 0, "planes per step: 1 or even");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -116,108 +142,107 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
     const int q0 = qt * a.TQ;
     const int rho0 = mt * a.TR;
     const int NP = a.N * a.P;
-    const int n0 = rho0 / a.P;
+    const float inv_P = 1.0f / (float)a.P, inv_Hs = 1.0f / (float)a.Hs;
+    const float inv_LW = 1.0f / (float)a.LW, inv_TQ = 1.0f / (float)a.TQ;
+    const int n0 = fast_div(rho0, inv_P);
     const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
     const int HW = a.H * a.W;
 
-    // ---- per-thread source offsets of the staged input pixels (16-byte units)
-    int g_off[PPT];
+    // ---- per-thread source byte offsets of the staged input pixels (plane 0)
+    unsigned g_off[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const int p = tid + i * NT;
-        int off = -1;
+        unsigned off = kOutOfRange;
         if (p < a.LRW) {
-            const int row = p / a.LW;
+            const int row = fast_div(p, inv_LW);
             const int col = p - row * a.LW;
             int n, ih, iw;
             bool ok;
             if (a.sampled) {
                 const int rho = rho0 + row;
-                n = rho / a.P;
+                n = fast_div(rho, inv_P);
                 ih = (rho - n * a.P) * a.stride;
                 iw = (q0 + col) * a.stride;
                 ok = rho < NP && (q0 + col) < a.Q;
             } else {
                 const int lam = lam0 + row;
-                n = lam / a.Hs;
+                n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad_h;
                 iw = q0 * a.stride - a.pad_w + col;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
-            if (ok) off = (n * a.Cb * a.H + ih) * a.W + iw;
+            if (ok) off = (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u;
         }
         g_off[i] = off;
     }
-    // ---- per-thread source offsets of the staged weights
-    int w_off[WPT];
+    // ---- per-thread source byte offsets of the staged weights (channel block 0)
+    unsigned w_off[WPT];
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
         const int w = tid + i * NT;
-        int off = -1;
+        unsigned off = kOutOfRange;
         if (w < WCH) {
             const int e = w / TK;
             const int k = w - e * TK;
             const int tap = e / NPL;
             const int pl = e - tap * NPL;
-            if (tap < NTAPS && k0 + k < a.Kp) off = (pl * NTAPS + tap) * a.Kp + k0 + k;
+            if (tap < NTAPS && k0 + k < a.Kp)
+                off = (unsigned)((pl * NTAPS + tap) * a.Kp + k0 + k) * 16u;
         }
         w_off[i] = off;
     }
 
-    u32x4 ireg[PPT][NPL];
-    u32x4 wreg[WPT];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
+    // Staging: 16-byte buffer loads that write straight into LDS (lane i of a
+    // wave lands at base + 16*i), so no registers, VALU work or LDS-write
+    // instructions are spent on it.  Padding (outside the image, beyond the
+    // channel count, the odd filler entry, the tail of a plane's last
+    // wave-level load) is out of range and arrives as zeros.  Per step only the
+    // scalar base of the resource moves; the per-lane offsets never change.
+    const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
+    const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
+    const int wave_chunk = wave * 64;  // first chunk a wave's load instruction fills
     auto fetch = [&](int st) {
         const int cb0 = st * NPL;
-        const u32x4 *ip = static_cast<const u32x4 *>(a.in) + (size_t)cb0 * HW;
-        const u32x4 *wp = static_cast<const u32x4 *>(a.wt) + (size_t)cb0 * NTAPS * a.Kp;
-#pragma unroll
-        for (int i = 0; i < PPT; ++i)
-#pragma unroll
-            for (int pl = 0; pl < NPL; ++pl)
-                ireg[i][pl] = g_off[i] >= 0 ? ip[g_off[i] + pl * HW] : zero4;
-#pragma unroll
-        for (int i = 0; i < WPT; ++i) wreg[i] = w_off[i] >= 0 ? wp[w_off[i]] : zero4;
-    };
-    auto commit = [&](int buf) {
-        unsigned char *wb = lds + buf * bufbytes;
+        unsigned char *wb = lds + (st & 1) * bufbytes;
         unsigned char *ib = wb + WBYTES;
 #pragma unroll
-        for (int i = 0; i < WPT; ++i) {
-            const int w = tid + i * NT;
-            if (w < WCH) *reinterpret_cast<u32x4 *>(wb + w * 16) = wreg[i];
-        }
+        for (int pl = 0; pl < NPL; ++pl) {
+            const rsrc_t ri = make_rsrc(a.in, (size_t)(cb0 + pl) * HW * 16, in_bytes);
 #pragma unroll
-        for (int i = 0; i < PPT; ++i) {
-            const int p = tid + i * NT;
-            if (p < a.LRW) {
-#pragma unroll
-                for (int pl = 0; pl < NPL; ++pl)
-                    *reinterpret_cast<u32x4 *>(ib + (pl * a.PLS + p) * 16) = ireg[i][pl];
-            }
+            for (int i = 0; i < PPT; ++i)
+                if (i * NT + wave_chunk < a.PLS)  // wave-uniform; PLS is a multiple of 64
+                    load_to_lds_16(ri, g_off[i], ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
         }
+        const rsrc_t rw = make_rsrc(a.wt, (size_t)cb0 * NTAPS * a.Kp * 16, wt_bytes);
+#pragma unroll
+        for (int i = 0; i < WPT; ++i)
+            if (i * NT + wave_chunk < WCH)  // wave-uniform
+                load_to_lds_16(rw, w_off[i], wb + (i * NT + wave_chunk) * 16);
     };
+    // All of this wave's staging loads have landed in LDS (vmcnt = 0).
+    auto staged = [&]() { wait_all_memory(); };
 
     // ---- per-lane pixel bookkeeping for the B fragments and the epilogue
     int bpos[FM];
-    int opix[FM];
+    unsigned obyte[FM];  // byte offset of the lane's pixel in output channel block 0
     const int Kb_out = a.Kp / V;
 #pragma unroll
     for (int j = 0; j < FM; ++j) {
         const int m = (wave_m * FM + j) * 32 + l32;
-        const int trow = m / a.TQ;
+        const int trow = fast_div(m, inv_TQ);
         const int tcol = m - trow * a.TQ;
         const int rho = rho0 + trow;
         const bool ok = trow < a.TR && rho < NP && (q0 + tcol) < a.Q;
-        const int n = rho / a.P;
+        const int n = fast_div(rho, inv_P);
         const int oj = rho - n * a.P;
         int pos = a.sampled ? m : (n * a.Hs + oj * a.stride - lam0) * a.LW + tcol * a.stride;
         if (!ok) pos = 0;
         // lane halves read two channel planes, or (one plane per step) two taps
         bpos[j] = ((NPL == 1 ? 0 : h) * a.PLS + pos) * 16;
-        opix[j] = ok ? (n * Kb_out * a.OH + oj * a.ostr + a.oy0) * a.OW + (q0 + tcol) * a.ostr + a.ox0
-                     : -1;
+        obyte[j] = ok ? (unsigned)((n * Kb_out * a.OH + oj * a.ostr + a.oy0) * a.OW +
+                                   (q0 + tcol) * a.ostr + a.ox0) * 16u
+                      : kOutOfRange;
     }
     const int a_base = (h * TK + wave_k * FK * 32 + l32) * 16;
 
@@ -230,7 +255,7 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
             for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
 
     fetch(0);
-    commit(0);
+    staged();
     __syncthreads();
 
     for (int st = 0; st < a.n_stage; ++st) {
@@ -286,33 +311,42 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
                 }
             }
         }
-        if (more) commit((st + 1) & 1);
+        staged();
         __syncthreads();
     }
 
-    // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels
-    const size_t oplane = (size_t)a.OH * a.OW;
+    // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels.
+    // The channel block of a store is wave-uniform, so it moves the scalar base
+    // of the resource; the per-lane offset is the pixel's.
+    const size_t oplane = (size_t)a.OH * a.OW * 16;
+    const size_t out_bytes = (size_t)a.N * Kb_out * oplane;
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-            const int krow = k0 + (wave_k * FK + i) * 32 + vq * 8 + h * 4;
-            if (krow >= a.Kp) continue;
-            const int kblk = krow / V;
-            const int sub = krow - kblk * V;
+            const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
+            if (krow0 >= a.Kp) continue;                            // wave-uniform
+            // fp32: 8 rows = blocks 2*q (h=0) and 2*q+1 (h=1); bf16: one block, halves by h
+            const size_t skip = (size_t)(krow0 / V) * oplane;
+            const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
+            const rsrc_t ro = make_rsrc(a.out, skip, out_bytes);
 #pragma unroll
             for (int j = 0; j < FM; ++j) {
-                if (opix[j] < 0) continue;
-                const size_t off = ((size_t)opix[j] + (size_t)kblk * oplane) * V + sub;
-                E_::store4(a.out, off, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
+                // (fp32: the upper lane half's block may lie beyond the last channel block)
+                const bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
+                const unsigned off = live ? obyte[j] + lane_off : kOutOfRange;
+                E_::store4(ro, off, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
                            acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
                 if (a.zero_fill) {
-                    const int ox = opix[j] % a.OW;
-                    const int oy = (opix[j] / a.OW) % a.OH;
+                    const int pix = (int)(obyte[j] >> 4);
+                    const int ox = pix % a.OW;
+                    const int oy = (pix / a.OW) % a.OH;
                     for (int dy = 0; dy < a.ostr; ++dy)
                         for (int dx = 0; dx < a.ostr; ++dx) {
-                            if ((dy | dx) == 0 || oy + dy >= a.OH || ox + dx >= a.OW) continue;
-                            E_::store4(a.out, off + (size_t)(dy * a.OW + dx) * V, 0.f, 0.f, 0.f, 0.f);
+                            if ((dy | dx) == 0) continue;
+                            const bool in = live && oy + dy < a.OH && ox + dx < a.OW;
+                            E_::store4(ro, in ? off + (unsigned)(dy * a.OW + dx) * 16u : kOutOfRange,
+                                       0.f, 0.f, 0.f, 0.f);
                         }
                 }
             }

@@ -23,13 +23,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Exact floor(x / d) for 0 <= x < 2^22 with inv = 1.0f / d: (x + 0.5) / d is
-// never an integer and stays 0.5/d away from one, more than the rounding error.
-static __device__ __forceinline__ int fast_div(int x, float inv)
-{
-    return (int)(((float)x + 0.5f) * inv);
-}
-
 // fp32 activations and gradients (vlen 4).  256 threads = 2 x 2 waves over
 // (input channels, output channels); a wave owns FC x FK fragments per tap.
 // Tiles are small enough for two workgroups per CU: one computes while the
