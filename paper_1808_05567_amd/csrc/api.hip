@@ -40,6 +40,8 @@ struct conv_plan {
     size_t bwd_ws = 0;
     // weight update
     bool upd_ok = false;
+    bool upd_c4 = false;   // few-channel formulation (one input channel block)
+    int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
     UpdArgs ua{};
     size_t upd_lds = 0;
@@ -71,7 +73,7 @@ int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
 // dynamic LDS at most `lds_cap` bytes.  Returns ok=false if nothing fits.
 IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                    int zero_fill, int wk, int wm, int fk, size_t lds_cap)
+                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap)
 {
     IgemmPlan pl;
     const int V = vlen_of(dtype);
@@ -80,12 +82,9 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     int npl;
     if (R == 1 && S == 1)
         npl = (Cb % 4 == 0) ? 4 : 1;
-    else if (R == 3 && S == 3)
-        npl = (Cb % 2 == 0) ? 2 : 1;
     else
-        npl = 1;
+        npl = (Cb % 2 == 0) ? 2 : 1;
 
-    const int fm = 7;
     const int TK = wk * fk * 32, TM = wm * fm * 32, NT = 256;
     const int nent = ((R * S * npl + 1) / 2) * 2;
 
@@ -115,7 +114,9 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
             }
         }
         // the plane pitch is a whole number of wave-level (64-lane) loads
-        const size_t lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * ceil_div(LR * LW, 64) * 64 * 16);
+        // (a single-step reduction never touches the second buffer)
+        const size_t nbuf = ceil_div(Cb, npl) > 1 ? 2 : 1;
+        const size_t lds = nbuf * ((size_t)nent * TK * 16 + (size_t)npl * ceil_div(LR * LW, 64) * 64 * 16);
         if (ppt > 0 && lds <= lds_cap) break;
     }
 
@@ -134,7 +135,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.per_xcd = ceil_div(a.total, 8);
     a.n_stage = ceil_div(Cb, npl);
     pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt};
-    pl.lds = 2 * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
+    pl.lds = (a.n_stage > 1 ? 2 : 1) * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
     pl.grid = a.per_xcd * 8;
     // 32-bit index guards (offsets are kept in 16-byte units / elements)
     // tensors are addressed with 32-bit byte offsets
@@ -167,17 +168,17 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
     IgemmPlan best;
     double best_cost = 0;
     const size_t caps[2] = {(size_t)kMaxLds / 2, (size_t)kMaxLds};
-    struct Cand { int wk, wm, fk; };
+    struct Cand { int wk, wm, fk, fm; };
     // bf16: two channel fragments per wave halve the LDS reads per MFMA (one
     // fragment per wave cannot keep the bf16 matrix core fed from 128 B/clk of LDS)
-    const Cand cands[4] = {{2, 2, 2}, {1, 4, 2}, {4, 1, 1}, {2, 2, 1}};
+    const Cand cands[5] = {{1, 4, 2, 4}, {2, 2, 2, 7}, {1, 4, 2, 7}, {4, 1, 1, 7}, {2, 2, 1, 7}};
     for (int ci = 0; ci < 2; ++ci)
         for (const Cand &cd : cands) {
             if (cd.fk == 2 && dtype != CONV_BF16) continue;
             const int TK = cd.wk * cd.fk * 32;
             if (TK > 64 && Kp <= TK / 2) continue;
             IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
-                                    ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, caps[ci]);
+                                    ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, cd.fm, caps[ci]);
             if (!c.ok) continue;
             // one workgroup per CU loses roughly a fifth to exposed barriers/staging
             double cost = igemm_waste(c, N, P, Q, Kp) * (ci == 0 ? 1.0 : 1.2) *
@@ -269,6 +270,49 @@ void plan_upd(conv_plan *p)
     p->upd_ws = 0;
     const bool sampled = (d.R == 1 && d.S == 1 && d.pad == 0);
     const bool bf16 = d.dtype == CONV_BF16;
+    p->upd_c4 = false;
+    if (!bf16 && f.Cb == 1 && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
+        // one input channel block: filter-row formulation
+        const int NT = 256, NPO = 16;
+        const int Qp = (f.Q + 1) & ~1;
+        const int NP = d.N * f.P;
+        UpdArgs &a = p->ua;
+        memset(&a, 0, sizeof(a));
+        a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+        int TR = std::min(NP, std::max(1, 256 / Qp));
+        for (;; --TR) {
+            if (TR < 1) return;
+            a.Hs = (f.P - 1) * d.stride + d.R;
+            // a lane reads up to 8 pixels (32 floats) past the pair's first pixel
+            a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * d.pad);
+            const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
+            a.LRW = LR * a.LW;
+            a.PLS_in = a.LRW + 8;
+            a.PLS_out = ((TR * Qp + 7) / 8) * 8 + 1;
+            p->upd_lds = ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+            if (p->upd_lds <= (size_t)kMaxLds) break;
+        }
+        a.TR = TR;
+        a.n_ct = 1;
+        a.n_kt = ceil_div(f.Kb, NPO);
+        int splits = std::max(1, 512 / a.n_kt);
+        int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+        splits = ceil_div(NP, rps);
+        a.rows_per_split = rps;
+        a.splits = splits;
+        a.sampled = 0;
+        a.total = a.n_kt * splits;
+        a.per_xcd = ceil_div(a.total, 8);
+        if ((double)(d.N + 1) * a.Hs >= 4.0e6 || NPO * TR * Qp >= (1 << 22)) return;
+        p->upd_grid = a.per_xcd * 8;
+        p->upd_copies = splits * 4;
+        p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+        p->upd_c4 = true;
+        p->upd_ok = true;
+        (void)NT;
+        return;
+    }
     UpdVariant v{};
     if (d.R == 3 && d.S == 3)
         v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
@@ -335,6 +379,7 @@ void plan_upd(conv_plan *p)
     p->upd_lds = ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
     if (p->upd_lds > (size_t)kMaxLds) return;
     p->upd_grid = a.per_xcd * 8;
+    p->upd_copies = splits;
     p->upd_ws = (size_t)splits * f.dwt_bytes;
     p->upd_ok = true;
 }
@@ -390,7 +435,7 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
                         d.pad, f.P, f.Q, 1, 0, 0, 0);
     plan_bwd(p);
     plan_upd(p);
-    f.upd_splits = p->upd_ok ? p->ua.splits : 0;
+    f.upd_splits = p->upd_ok ? p->upd_copies : 0;
     f.workspace_bytes = std::max(p->bwd_ws, p->upd_ws);
     *out = p;
     return CONV_OK;
@@ -460,9 +505,11 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.in = in;
     a.dout = dout;
     a.partial = static_cast<float *>(ws);
-    if (launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s) != hipSuccess) return CONV_ELAUNCH;
+    const hipError_t e = h->upd_c4 ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
+                                   : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+    if (e != hipSuccess) return CONV_ELAUNCH;
     if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
-                          a.splits, s) != hipSuccess)
+                          h->upd_copies, s) != hipSuccess)
         return CONV_ELAUNCH;
     return CONV_OK;
 }
@@ -539,6 +586,13 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
     }
     if (pass == 2) {
         if (!h->upd_ok) return CONV_EUNSUPPORTED;
+        if (h->upd_c4) {
+            snprintf(buf, buflen,
+                     "upd_c4 dt=0 RS=%dx%d TR=%d splits=%d x4 copies rows/split=%d ktiles=%d grid=%d lds=%zu",
+                     h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
+                     h->upd_grid, h->upd_lds);
+            return CONV_OK;
+        }
         snprintf(buf, buflen,
                  "upd dt=%d RS=%dx%d waves=%dx%d frags=%dx%d TR=%d splits=%d rows/split=%d "
                  "tiles=%dx%d grid=%d lds=%zu",

@@ -101,6 +101,9 @@ struct UpdVariant {
 hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
                       hipStream_t stream);
 bool upd_variant_exists(const UpdVariant &v);
+// fp32, one input channel block (C <= 4): filter-row formulation, 7x7 and 3x3
+hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+                         hipStream_t stream);
 hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
                              hipStream_t stream);
 

@@ -104,7 +104,7 @@ struct Elem<CONV_BF16> {
 };
 
 template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT>
-__global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
     constexpr int V = E_::V;
@@ -202,23 +202,29 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
     const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
     const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
     const int wave_chunk = wave * 64;  // first chunk a wave's load instruction fills
-    auto fetch = [&](int st) {
+    // Load number l of a step: the input loads (plane-major) come first, then the weights.
+    constexpr int NLOADS = NPL * PPT + WPT;
+    auto fetch_one = [&](int st, int l) {
         const int cb0 = st * NPL;
         unsigned char *wb = lds + (st & 1) * bufbytes;
         unsigned char *ib = wb + WBYTES;
-#pragma unroll
-        for (int pl = 0; pl < NPL; ++pl) {
-            const rsrc_t ri = make_rsrc(a.in, (size_t)(cb0 + pl) * HW * 16, in_bytes);
-#pragma unroll
-            for (int i = 0; i < PPT; ++i)
-                if (i * NT + wave_chunk < a.PLS)  // wave-uniform; PLS is a multiple of 64
-                    load_to_lds_16(ri, g_off[i], ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
-        }
-        const rsrc_t rw = make_rsrc(a.wt, (size_t)cb0 * NTAPS * a.Kp * 16, wt_bytes);
-#pragma unroll
-        for (int i = 0; i < WPT; ++i)
-            if (i * NT + wave_chunk < WCH)  // wave-uniform
+        if (l < NPL * PPT) {
+            const int pl = l / PPT, i = l - pl * PPT;
+            if (i * NT + wave_chunk < a.PLS) {  // wave-uniform; PLS is a multiple of 64
+                const rsrc_t ri = make_rsrc(a.in, (size_t)(cb0 + pl) * HW * 16, in_bytes);
+                load_to_lds_16(ri, g_off[i], ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
+            }
+        } else {
+            const int i = l - NPL * PPT;
+            if (i * NT + wave_chunk < WCH) {  // wave-uniform
+                const rsrc_t rw = make_rsrc(a.wt, (size_t)cb0 * NTAPS * a.Kp * 16, wt_bytes);
                 load_to_lds_16(rw, w_off[i], wb + (i * NT + wave_chunk) * 16);
+            }
+        }
+    };
+    auto fetch = [&](int st) {
+#pragma unroll
+        for (int l = 0; l < NLOADS; ++l) fetch_one(st, l);
     };
     // All of this wave's staging loads have landed in LDS (vmcnt = 0).
     auto staged = [&]() { wait_all_memory(); };
@@ -260,7 +266,7 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
 
     for (int st = 0; st < a.n_stage; ++st) {
         const bool more = st + 1 < a.n_stage;
-        if (more) fetch(st + 1);
+        if (NPL == 1 && more) fetch(st + 1);
         const unsigned char *wb = lds + (st & 1) * bufbytes;
         const unsigned char *ib = wb + WBYTES;
 
@@ -294,6 +300,14 @@ __global__ __launch_bounds__(WK *WM * 64) void igemm_kernel(const IgemmArgs a)
 #pragma unroll
                     for (int pp = 0; pp < NPL / 2; ++pp) {
                         const int q = (r * S + s) * (NPL / 2) + pp;
+                        // The next step's staging loads are spread over this step's
+                        // MFMA stream so that the memory pipeline never backs up.
+                        constexpr int NQ = NTAPS * (NPL / 2);
+                        if (more) {
+#pragma unroll
+                            for (int l = q * NLOADS / NQ; l < (q + 1) * NLOADS / NQ; ++l)
+                                fetch_one(st + 1, l);
+                        }
                         u32x4 af[FK], bf[FM];
 #pragma unroll
                         for (int i = 0; i < FK; ++i)
@@ -379,6 +393,8 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 1, 1, 2),
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 3, 3, 3),
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 7, 7, 12),
+    // 4x4: the stride-2 residue classes of a 7x7 backward pass (conv1)
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 4, 4, 4),
     // bf16
     IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 3, 3, 3),
@@ -392,6 +408,11 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 7, 2, 3, 3, 5),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 2, 7, 4, 1, 1, 2),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 7, 4, 1, 1, 4),
+    // bf16, 128 accumulator registers per wave: two workgroups share a CU, so one
+    // workgroup's prologue and output writes overlap the other's MFMA stream
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 3),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 4),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 4, 1, 1, 2),
 };
 
 static IgemmEntry *find_igemm(const IgemmVariant &v)
