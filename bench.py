@@ -42,7 +42,52 @@ def parse():
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=16)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch a plain 1 GiB device copy (reference for HBM counters)")
+    ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: turn two rocprofv3 --pmc counter_collection CSVs "
+                         "(FETCH_SIZE, WRITE_SIZE) of a --calib-copy run into a traffic summary")
+    ap.add_argument("--out", default=None)
     return ap.parse_args()
+
+
+CALIB_BYTES = 1 << 30
+TRAFFIC_FILE = {"f32": "igemm_f32_resnet50_3x3_n256_hbm_traffic.json",
+                "bf16": "igemm_bf16_resnet50_3x3_n256_hbm_traffic.json"}
+
+
+def summarize_pmc(fetch_csv, write_csv, out):
+    """Average HBM bytes per dispatch of every kernel, from FETCH_SIZE / WRITE_SIZE
+    (KiB per dispatch), each scaled by what the same counter reads for the 1 GiB copy."""
+    import collections
+    import csv
+
+    def load(path, counter):
+        acc = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] == counter:
+                acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return {k: sum(v) / len(v) for k, v in acc.items()}, {k: len(v) for k, v in acc.items()}
+
+    fetch, calls = load(fetch_csv, "FETCH_SIZE")
+    write, _ = load(write_csv, "WRITE_SIZE")
+    copy = [k for k in fetch if "copy" in k.lower() or "elementwise" in k.lower()]
+    copy = max(copy, key=lambda k: fetch[k]) if copy else None
+    f_scale = (CALIB_BYTES / 1024.0) / fetch[copy] if copy else 1.0
+    w_scale = (CALIB_BYTES / 1024.0) / write[copy] if copy and write.get(copy) else 1.0
+    rows = {}
+    for k in fetch:
+        rows[k] = {"calls": calls[k], "fetch_bytes": fetch[k] * 1024 * f_scale,
+                   "write_bytes": write.get(k, 0.0) * 1024 * w_scale}
+    summary = {"copy_kernel": copy, "copy_bytes_each_way": CALIB_BYTES,
+               "fetch_scale": f_scale, "write_scale": w_scale, "kernels": rows}
+    if out:
+        with open(out, "w") as f:
+            json.dump(summary, f, indent=1)
+    for k, r in sorted(rows.items(), key=lambda kv: -kv[1]["fetch_bytes"]):
+        print("%-90s calls %4d  fetch %9.1f MB  write %9.1f MB" % (
+            k[:90], r["calls"], r["fetch_bytes"] / 1e6, r["write_bytes"] / 1e6))
+    print("scales: fetch %.4f write %.4f (copy kernel: %s)" % (f_scale, w_scale, copy))
 
 
 def algorithmic_bytes(l, N, es, which):
@@ -116,6 +161,9 @@ def cpu_baseline(ids, n_cpu):
 
 def main():
     args = parse()
+    if args.summarize_pmc:
+        summarize_pmc(args.summarize_pmc[0], args.summarize_pmc[1], args.out)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -137,6 +185,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.empty(CALIB_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # Per-launch HIP events on the stream the kernels run on (torch's current
     # stream is the one handed to the library), recorded inside the timed region.
@@ -167,8 +222,20 @@ def main():
     fwd_ms = sum(per[(l.id, "fwd")] for l, _ in layers)
     achieved = fwd_flops / (fwd_ms * 1e-3) / 1e12
     peak = MFMA_PEAK[args.dtype]
+    # HBM bytes per igemm launch, from the committed rocprofv3 counter summary of this
+    # same workload (see profiles/); null when the workload differs or none exists.
+    traffic = None
+    tf_path = os.path.join(ROOT, "profiles", TRAFFIC_FILE[args.dtype])
+    if args.layers == "4,8,13,18" and N == N_BATCH and os.path.exists(tf_path):
+        try:
+            ks = json.load(open(tf_path))["kernels"]
+            ig = [(v["calls"], v["fetch_bytes"] + v["write_bytes"]) for k, v in ks.items()
+                  if "igemm_kernel" in k]
+            traffic = round(sum(c * b for c, b in ig) / sum(c for c, _ in ig))
+        except Exception:
+            traffic = None
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": None,
+                "frac": round(achieved / peak, 4), "traffic": traffic,
                 "kernel": "igemm_kernel (forward launches of the workload's layers)",
                 "per_pass_tflops": {
                     w: round(sum(l.flops(N) for l, _ in layers) /

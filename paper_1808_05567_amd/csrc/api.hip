@@ -183,7 +183,10 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
             // one workgroup per CU loses roughly a fifth to exposed barriers/staging
             double cost = igemm_waste(c, N, P, Q, Kp) * (ci == 0 ? 1.0 : 1.2) *
                           (1.0 + 0.01 * (128 / TK));
-            if (dtype == CONV_BF16 && cd.fk == 1) cost *= 1.5;
+            // one fragment per wave starves the bf16 matrix core of LDS bandwidth; it only
+            // matters where the filter gives the layer enough reuse to be MFMA-bound
+            if (dtype == CONV_BF16 && cd.fk == 1 && R * S > 1) cost *= 1.5;
+            if (dtype == CONV_BF16 && cd.fk == 2 && R * S == 1) cost *= 1.5;
             if (!best.ok || cost < best_cost) {
                 best = c;
                 best_cost = cost;
