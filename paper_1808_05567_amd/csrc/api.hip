@@ -41,6 +41,8 @@ struct conv_plan {
     // weight update
     bool upd_ok = false;
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
+    bool upd_rows = false; // bf16 row kernel (stride 1)
+    UpdRowsVariant urv{};
     int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
     UpdArgs ua{};
@@ -316,6 +318,58 @@ void plan_upd(conv_plan *p)
         (void)NT;
         return;
     }
+    p->upd_rows = false;
+    if (bf16 && d.R == 3 && d.S == 3 && d.stride == 1 && f.Cb % 8 == 0) {
+        // bf16 row kernel: 8-pixel runs, filter-column shifts in registers
+        UpdRowsVariant rv = f.Kp <= 64 ? UpdRowsVariant{3, 3, 2, 1, 2, 1, 2}
+                                       : UpdRowsVariant{3, 3, 2, 2, 1, 1, 2};
+        if (upd_rows_variant_exists(rv)) {
+            const int TC = rv.wc * rv.fc * 32, TK = rv.wk * rv.fk * 32, NPI = TC / 8, NPO = TK / 8;
+            const int NP = d.N * f.P;
+            UpdArgs &a = p->ua;
+            memset(&a, 0, sizeof(a));
+            a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+            a.R = d.R; a.S = d.S; a.stride = 1; a.pad = d.pad;
+            a.runs = ceil_div(f.Q, 8);
+            const int RP = a.runs * 8;
+            a.Hs = f.P - 1 + d.R;
+            a.LW = std::max(d.W + 2 * d.pad, RP + 4);
+            int TR = std::min(NP, 64);
+            for (;; --TR) {
+                if (TR < 1) return;
+                const int LR = max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
+                a.LRW = LR * a.LW;
+                a.PLS_in = ceil_div(a.LRW, 64) * 64;
+                a.PLS_out = ceil_div(TR * RP + 8, 64) * 64;
+                p->upd_lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+                if (p->upd_lds <= (size_t)kMaxLds) break;
+            }
+            a.TR = TR;
+            a.n_ct = ceil_div(f.Cb, NPI);
+            a.n_kt = ceil_div(f.Kb, NPO);
+            const int tiles = a.n_ct * a.n_kt;
+            // one workgroup per CU; pixel waves count as splits of their own
+            int splits = std::max(1, (256 + tiles * rv.wp / 2) / (tiles * rv.wp));
+            splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
+            int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+            splits = ceil_div(NP, rps);
+            a.rows_per_split = rps;
+            a.splits = splits;
+            a.sampled = 0;
+            a.total = tiles * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            if ((double)(d.N + 1) * a.Hs < 4.0e6 && (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 &&
+                (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
+                p->urv = rv;
+                p->upd_grid = a.per_xcd * 8;
+                p->upd_copies = splits * rv.wp;
+                p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+                p->upd_rows = true;
+                p->upd_ok = true;
+                return;
+            }
+        }
+    }
     UpdVariant v{};
     if (d.R == 3 && d.S == 3)
         v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
@@ -358,7 +412,12 @@ void plan_upd(conv_plan *p)
     a.n_ct = ceil_div(f.Cb, NPI);
     a.n_kt = ceil_div(f.Kb, NPO);
     const int tiles = a.n_ct * a.n_kt;
-    int splits = std::max(1, (1024 + tiles / 2) / tiles);
+    // two rounds of two workgroups per CU (measured better than one round: the tail is
+    // shorter), and no accumulation
+    // chain longer than about 2^15 pixels
+    const int target = 1024;
+    int splits = std::max(1, (target + tiles / 2) / tiles);
+    splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
     int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
     splits = ceil_div(NP, rps);
     a.rows_per_split = rps;
@@ -508,8 +567,9 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.in = in;
     a.dout = dout;
     a.partial = static_cast<float *>(ws);
-    const hipError_t e = h->upd_c4 ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
-                                   : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+    const hipError_t e = h->upd_c4     ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
+                         : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
+                                       : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
     if (e != hipSuccess) return CONV_ELAUNCH;
     if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
                           h->upd_copies, s) != hipSuccess)
@@ -593,6 +653,15 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
             snprintf(buf, buflen,
                      "upd_c4 dt=0 RS=%dx%d TR=%d splits=%d x4 copies rows/split=%d ktiles=%d grid=%d lds=%zu",
                      h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
+                     h->upd_grid, h->upd_lds);
+            return CONV_OK;
+        }
+        if (h->upd_rows) {
+            snprintf(buf, buflen,
+                     "upd_rows dt=1 RS=%dx%d waves=%dx%dx%d frags=%dx%d TR=%d runs=%d splits=%d "
+                     "rows/split=%d tiles=%dx%d grid=%d lds=%zu",
+                     h->d.R, h->d.S, h->urv.wc, h->urv.wk, h->urv.wp, h->urv.fc, h->urv.fk, h->ua.TR,
+                     h->ua.runs, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt,
                      h->upd_grid, h->upd_lds);
             return CONV_OK;
         }

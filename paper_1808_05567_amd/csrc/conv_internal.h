@@ -89,6 +89,7 @@ struct UpdArgs {
     int Hs, LW, LRW, PLS_in, PLS_out;
     int sampled;
     int total, per_xcd;
+    int runs;        // bf16 row kernel: 8-pixel runs per output row
 };
 struct UpdVariant {
     int dtype;
@@ -101,6 +102,15 @@ struct UpdVariant {
 hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
                       hipStream_t stream);
 bool upd_variant_exists(const UpdVariant &v);
+// bf16, stride 1 (or 1x1 sampled): 8-pixel runs along a row, filter-column shifts in registers
+struct UpdRowsVariant {
+    int r, s;
+    int wc, wk, wp;  // waves along input channels / output channels / pixels
+    int fc, fk;      // 32x32 fragments per wave along input / output channels
+};
+bool upd_rows_variant_exists(const UpdRowsVariant &v);
+hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
+                           hipStream_t stream);
 // fp32, one input channel block (C <= 4): filter-row formulation, 7x7 and 3x3
 hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream);
@@ -123,6 +133,30 @@ static __device__ __forceinline__ int fast_div(int x, float inv)
 {
     return (int)(((float)x + 0.5f) * inv);
 }
+
+// Buffer addressing: a tensor is reached through a buffer resource
+// (base, byte size) plus a 32-bit per-lane byte offset.  Loads whose offset is
+// at or beyond the size return zero and stores there are dropped, so padding
+// and ragged tiles need no branches: such lanes carry the offset kOutOfRange.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOutOfRange = 0xFFFFFFFFu;
+static __device__ __forceinline__ rsrc_t make_rsrc(const void *base, size_t skip, size_t total)
+{
+    // view of [base + skip, base + total); the range check stays exact
+    return __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char *>(static_cast<const char *>(base)) + skip, 0,
+        (int)(unsigned)(total - skip), 0x00020000);
+}
+// 16-byte load from global memory straight into LDS: lane i of the wave writes
+// lds_wave_base + 16*i (the LDS base must be wave-uniform), zero if out of range.
+static __device__ __forceinline__ void load_to_lds_16(rsrc_t r, unsigned byte_off,
+                                                      unsigned char *lds_wave_base)
+{
+    typedef __attribute__((address_space(3))) void *lds_vptr_t;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, 0, 0, 0);
+}
+// Wait until every outstanding memory operation of this wave, staging loads included, is done.
+static __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int vlen_of(int dtype) { return dtype == CONV_BF16 ? 8 : 4; }

@@ -1,0 +1,328 @@
+// Weight-gradient update (Algorithm 8 of the paper, with padding) for bf16
+// tensors on MFMA, fp32 accumulation and output -- the kernel for stride-1
+// layers (and for 1x1 layers of any stride, whose input is staged sampled).
+//
+//   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj-pad+r,oi-pad+s] * dO[n,k,oj,oi]
+//
+// M = input channels, N = output channels, reduction = pixels; one 32x32
+// accumulator tile per filter tap, all taps of the tile resident in the wave
+// (the register-resident dW block of Algorithm 9).
+//
+// The MFMA takes 8 consecutive reduction indices (pixels) per lane while the
+// blocked layout keeps 8 channels of one pixel together: the transpose the paper
+// pays for up front on Knights Mill (Section III-B).  Here the bands stay in LDS
+// exactly as they sit in HBM ([plane][pixel][8 channels]) and gfx950's
+// transposing LDS read hands each lane four consecutive pixels of its channel.
+//
+// The reduction walks 8-pixel runs along output rows; the two lane halves of a
+// step take two different runs.  For one filter row r a lane reads a window of
+// 12 consecutive input pixels of its channel once and forms the operands of the
+// S taps from it in registers (a tap one pixel to the right is the same data
+// shifted by 16 bits): the staged input row is read once per filter row, not
+// once per tap.
+//
+// Staging is by buffer loads straight into a double-buffered LDS band (padding
+// and band tails are out-of-range lanes and arrive as zeros); the next band
+// streams in while the current one is consumed.  Grid = (split of the linear
+// output-row range) x (channel tiles); every split writes a private partial dW
+// and the reduce kernel sums them in a fixed order.  Waves that share a channel
+// tile but take different runs (WP > 1) write private copies as well.
+#include "conv_internal.h"
+
+namespace convmi {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Transposing 64-bit LDS read: within a group of 16 lanes, lane i slot j
+// receives 16-bit element (i % 4) of the 8 bytes addressed by lane 4*j + i/4.
+static __device__ __forceinline__ u32x2 lds_read_tr16_b64(const unsigned char *p)
+{
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    return __builtin_bit_cast(u32x2, v);
+}
+
+template <int R, int S, int WC, int WK, int WP, int FC, int FK>
+__global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
+{
+    constexpr int V = 8;
+    constexpr int NTAPS = R * S;
+    constexpr int TC = WC * FC * 32;
+    constexpr int TK = WK * FK * 32;
+    constexpr int NPI = TC / V;
+    constexpr int NPO = TK / V;
+    constexpr int WIN = (8 + S - 1 + 3) / 4;  // 4-pixel reads covering a run plus S-1 shifts
+    static_assert(WC * WK * WP == 4, "four waves");
+    static_assert(S <= 5, "window of three 4-pixel reads");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int ibytes = NPI * a.PLS_in * 16;
+    const int obytes = NPO * a.PLS_out * 16;
+    const int bufbytes = ibytes + obytes;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int grp = (lane >> 4) & 1;
+    const int i16 = lane & 15;
+    const int wave_c = wave % WC;
+    const int wave_k = (wave / WC) % WK;
+    const int wave_p = wave / (WC * WK);
+
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int rest = lin / a.n_kt;
+    const int ct = rest % a.n_ct;
+    const int split = rest / a.n_ct;
+    const int cb0 = ct * NPI;
+    const int kb0 = kt * NPO;
+
+    const int NP = a.N * a.P;
+    const int rho_begin = split * a.rows_per_split;
+    const int rho_end = min(NP, rho_begin + a.rows_per_split);
+    const int RP = a.runs * 8;              // staged dO row pitch (pixels), zero padded beyond Q
+    const int npxO = a.TR * RP + 8;         // ... plus one all-zero run for idle lane halves
+    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const int gap = a.sampled ? 0 : a.Hs - a.P;  // staged rows between images (stride 1)
+    const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
+    const float inv_RP = 1.0f / (float)RP, inv_P = 1.0f / (float)a.P;
+    const float inv_runs = 1.0f / (float)a.runs;
+    const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
+    const size_t out_bytes = (size_t)a.N * a.Kb * PQ * 16;
+    const int wave_chunk = wave * 64;
+
+    // Stage the bands of linear output rows [rho0, rho0 + TR) into buffer `buf`.
+    auto fetch = [&](int rho0, int buf) {
+        unsigned char *ib = lds + buf * bufbytes;
+        unsigned char *ob = ib + ibytes;
+        const int n0 = fast_div(rho0, inv_P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P);
+        for (int p0 = 0; p0 < a.PLS_in; p0 += 256) {
+            if (p0 + wave_chunk >= a.PLS_in) break;  // wave-uniform; PLS is a multiple of 64
+            const int p = p0 + tid;
+            unsigned off = kOutOfRange;
+            if (p < a.LRW) {
+                const int row = fast_div(p, inv_LW);
+                const int col = p - row * a.LW;
+                int n, ih, iw;
+                bool ok;
+                if (a.sampled) {
+                    const int rho = rho0 + row;
+                    n = fast_div(rho, inv_P);
+                    ih = (rho - n * a.P) * a.stride;
+                    iw = col * a.stride;
+                    ok = rho < rho_end && col < a.Q;
+                } else {
+                    const int lam = lam0 + row;
+                    n = fast_div(lam, inv_Hs);
+                    ih = lam - n * a.Hs - a.pad;
+                    iw = col - a.pad;
+                    ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+                }
+                if (ok) off = (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u;
+            }
+#pragma unroll
+            for (int pl = 0; pl < NPI; ++pl) {
+                // channel blocks beyond the tensor: an empty view, everything reads zero
+                const size_t skip = (size_t)(cb0 + pl) * HW * 16;
+                const rsrc_t ri = make_rsrc(a.in, min(skip, in_bytes), in_bytes);
+                load_to_lds_16(ri, off, ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
+            }
+        }
+        for (int p0 = 0; p0 < a.PLS_out; p0 += 256) {
+            if (p0 + wave_chunk >= a.PLS_out) break;
+            const int p = p0 + tid;
+            unsigned off = kOutOfRange;
+            if (p < a.TR * RP) {
+                const int trow = fast_div(p, inv_RP);
+                const int col = p - trow * RP;
+                const int rho = rho0 + trow;
+                if (rho < rho_end && col < a.Q) {
+                    const int n = fast_div(rho, inv_P);
+                    const int oj = rho - n * a.P;
+                    off = (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
+                }
+            }
+#pragma unroll
+            for (int pl = 0; pl < NPO; ++pl) {
+                const size_t skip = (size_t)(kb0 + pl) * PQ * 16;
+                const rsrc_t ro = make_rsrc(a.dout, min(skip, out_bytes), out_bytes);
+                load_to_lds_16(ro, off, ob + (pl * a.PLS_out + p0 + wave_chunk) * 16);
+            }
+        }
+    };
+
+    f32x16 acc[NTAPS][FC][FK];
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.0f;
+
+    // Byte offset, within a staged band, of what this lane addresses in a
+    // transposing read: pixel (i16 / 4) of the 4-pixel group, channels
+    // 16*grp + 4*(i16 % 4) .. +3 of the fragment.
+    int a_lane[FC], b_lane[FK];
+#pragma unroll
+    for (int i = 0; i < FC; ++i) {
+        const int c = (wave_c * FC + i) * 32 + grp * 16 + (i16 & 3) * 4;
+        a_lane[i] = ((c / V) * a.PLS_in + (i16 >> 2)) * 16 + (c % V) * 2;
+    }
+#pragma unroll
+    for (int j = 0; j < FK; ++j) {
+        const int k = (wave_k * FK + j) * 32 + grp * 16 + (i16 & 3) * 4;
+        b_lane[j] = ((k / V) * a.PLS_out + (i16 >> 2)) * 16 + (k % V) * 2;
+    }
+
+    int nsteps = 0;
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR) ++nsteps;
+    if (nsteps > 0) {
+        fetch(rho_begin, 0);
+        wait_all_memory();
+    }
+    __syncthreads();
+
+    int step = 0;
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, ++step) {
+        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, (step + 1) & 1);
+        const unsigned char *ib = lds + (step & 1) * bufbytes;
+        const unsigned char *ob = ib + ibytes;
+
+        const int rows = min(a.TR, rho_end - rho0);
+        const int nruns = rows * a.runs;
+        const int n0 = fast_div(rho0, inv_P);
+        const int oj0 = rho0 - n0 * a.P;
+        // run pairs: lane half h takes run 2*t + h; waves along pixels interleave t
+        for (int t = wave_p; 2 * t < nruns; t += WP) {
+            const int q = 2 * t + h;
+            const bool live = q < nruns;
+            const int trow = fast_div(q, inv_runs);
+            const int ri = q - trow * a.runs;
+            int lrow = trow;
+            if (!a.sampled) {
+                // staged row of output row (rho0 + trow), tap row 0
+                const int o = oj0 + trow;
+                const int dn = fast_div(o, inv_P);
+                lrow = trow + dn * gap;
+            }
+            const int ipix = live ? (lrow * a.LW + ri * 8) * 16 : 0;
+            const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
+
+            u32x4 bf[FK];
+#pragma unroll
+            for (int j = 0; j < FK; ++j) {
+                const u32x2 lo = lds_read_tr16_b64(ob + b_lane[j] + opix);
+                const u32x2 hi = lds_read_tr16_b64(ob + b_lane[j] + opix + 4 * 16);
+                bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int i = 0; i < FC; ++i) {
+                    // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
+                    unsigned w[2 * WIN];
+#pragma unroll
+                    for (int g = 0; g < WIN; ++g) {
+                        const u32x2 v = lds_read_tr16_b64(ib + a_lane[i] + ipix + (r * a.LW + 4 * g) * 16);
+                        w[2 * g] = v[0];
+                        w[2 * g + 1] = v[1];
+                    }
+#pragma unroll
+                    for (int s = 0; s < S; ++s) {
+                        u32x4 af;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const int lo = d + s / 2;
+                            af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[lo + 1], w[lo], 16) : w[lo];
+                        }
+#pragma unroll
+                        for (int j = 0; j < FK; ++j)
+                            acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf[j]),
+                                acc[r * S + s][i][j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        wait_all_memory();
+        __syncthreads();
+    }
+
+    // ---- this (split, pixel wave)'s partial dW tile: [copy][cb][tap][k][c%8]
+    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    float *dst = a.partial + ((size_t)split * WP + wave_p) * copy;
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int i = 0; i < FC; ++i)
+#pragma unroll
+            for (int j = 0; j < FK; ++j) {
+                const int k = kb0 * V + (wave_k * FK + j) * 32 + l32;
+                if (k >= a.Kp) continue;
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int c = cb0 * V + (wave_c * FC + i) * 32 + vq * 8;
+                    const int cb = c / V;
+                    if (cb >= a.Cb) continue;
+                    f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
+                               acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V +
+                                               4 * h) = v;
+                }
+            }
+}
+
+typedef void (*upd_rows_fn_t)(const UpdArgs);
+struct UpdRowsEntry {
+    UpdRowsVariant v;
+    upd_rows_fn_t fn;
+    size_t lds_attr;
+};
+#define UPD_ROWS_ENTRY(R, S, WC, WK, WP, FC, FK)                                         \
+    {                                                                                    \
+        {R, S, WC, WK, WP, FC, FK}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK>, 0    \
+    }
+static UpdRowsEntry g_rows[] = {
+    UPD_ROWS_ENTRY(3, 3, 2, 2, 1, 1, 2),  // 64 x 128 channels
+    UPD_ROWS_ENTRY(3, 3, 2, 1, 2, 1, 2),  // 64 x 64 channels, two waves along pixels
+};
+
+static UpdRowsEntry *find_rows(const UpdRowsVariant &v)
+{
+    for (auto &e : g_rows)
+        if (e.v.r == v.r && e.v.s == v.s && e.v.wc == v.wc && e.v.wk == v.wk && e.v.wp == v.wp &&
+            e.v.fc == v.fc && e.v.fk == v.fk)
+            return &e;
+    return nullptr;
+}
+bool upd_rows_variant_exists(const UpdRowsVariant &v) { return find_rows(v) != nullptr; }
+
+hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
+                           hipStream_t stream)
+{
+    UpdRowsEntry *e = find_rows(v);
+    if (!e) return hipErrorInvalidDeviceFunction;
+    if (lds_bytes > e->lds_attr) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        e->lds_attr = lds_bytes;
+    }
+    hipLaunchKernelGGL(e->fn, dim3(grid), dim3(256), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convmi
