@@ -321,8 +321,8 @@ void plan_upd(conv_plan *p)
     p->upd_rows = false;
     if (bf16 && d.R == 3 && d.S == 3 && d.stride == 1 && f.Cb % 8 == 0) {
         // bf16 row kernel: 8-pixel runs, filter-column shifts in registers
-        UpdRowsVariant rv = f.Kp <= 64 ? UpdRowsVariant{3, 3, 2, 1, 2, 1, 2}
-                                       : UpdRowsVariant{3, 3, 2, 2, 1, 1, 2};
+        UpdRowsVariant rv = f.Kp <= 64 ? UpdRowsVariant{3, 3, 2, 2, 2, 1, 1}
+                                       : UpdRowsVariant{3, 3, 2, 4, 1, 1, 1};
         if (upd_rows_variant_exists(rv)) {
             const int TC = rv.wc * rv.fc * 32, TK = rv.wk * rv.fk * 32, NPI = TC / 8, NPO = TK / 8;
             const int NP = d.N * f.P;
@@ -348,8 +348,8 @@ void plan_upd(conv_plan *p)
             a.n_ct = ceil_div(f.Cb, NPI);
             a.n_kt = ceil_div(f.Kb, NPO);
             const int tiles = a.n_ct * a.n_kt;
-            // one workgroup per CU; pixel waves count as splits of their own
-            int splits = std::max(1, (256 + tiles * rv.wp / 2) / (tiles * rv.wp));
+            // one workgroup per CU
+            int splits = std::max(1, (256 + tiles / 2) / tiles);
             splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
             int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
             splits = ceil_div(NP, rps);

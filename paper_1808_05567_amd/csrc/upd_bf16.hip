@@ -48,16 +48,20 @@ static __device__ __forceinline__ u32x2 lds_read_tr16_b64(const unsigned char *p
 }
 
 template <int R, int S, int WC, int WK, int WP, int FC, int FK>
-__global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
+__global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const UpdArgs a)
 {
     constexpr int V = 8;
+    constexpr int NT = WC * WK * WP * 64;
     constexpr int NTAPS = R * S;
     constexpr int TC = WC * FC * 32;
     constexpr int TK = WK * FK * 32;
     constexpr int NPI = TC / V;
     constexpr int NPO = TK / V;
     constexpr int WIN = (8 + S - 1 + 3) / 4;  // 4-pixel reads covering a run plus S-1 shifts
-    static_assert(WC * WK * WP == 4, "four waves");
+    static_assert(NT == 256 || NT == 512, "four or eight waves");
+    // Two waves per SIMD need the accumulators to fit the 256 AGPRs outright:
+    // above that the compiler shuttles tiles between register files every step.
+    static_assert(NTAPS * FC * FK * 16 <= 256, "accumulators must fit the AGPRs");
     static_assert(S <= 5, "window of three 4-pixel reads");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
         unsigned char *ob = ib + ibytes;
         const int n0 = fast_div(rho0, inv_P);
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P);
-        for (int p0 = 0; p0 < a.PLS_in; p0 += 256) {
+        for (int p0 = 0; p0 < a.PLS_in; p0 += NT) {
             if (p0 + wave_chunk >= a.PLS_in) break;  // wave-uniform; PLS is a multiple of 64
             const int p = p0 + tid;
             unsigned off = kOutOfRange;
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
                 load_to_lds_16(ri, off, ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
             }
         }
-        for (int p0 = 0; p0 < a.PLS_out; p0 += 256) {
+        for (int p0 = 0; p0 < a.PLS_out; p0 += NT) {
             if (p0 + wave_chunk >= a.PLS_out) break;
             const int p = p0 + tid;
             unsigned off = kOutOfRange;
@@ -204,8 +208,9 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
         const int nruns = rows * a.runs;
         const int n0 = fast_div(rho0, inv_P);
         const int oj0 = rho0 - n0 * a.P;
-        // run pairs: lane half h takes run 2*t + h; waves along pixels interleave t
-        for (int t = wave_p; 2 * t < nruns; t += WP) {
+        // Run pairs: lane half h takes run 2*t + h; waves along pixels interleave t.
+        // (Two waves per SIMD: one wave's LDS latency hides behind the other's MFMAs.)
+        auto load_pair = [&](int t, unsigned (&w)[R][FC][2 * WIN], u32x4 (&bf)[FK]) {
             const int q = 2 * t + h;
             const bool live = q < nruns;
             const int trow = fast_div(q, inv_runs);
@@ -213,14 +218,11 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
             int lrow = trow;
             if (!a.sampled) {
                 // staged row of output row (rho0 + trow), tap row 0
-                const int o = oj0 + trow;
-                const int dn = fast_div(o, inv_P);
+                const int dn = fast_div(oj0 + trow, inv_P);
                 lrow = trow + dn * gap;
             }
             const int ipix = live ? (lrow * a.LW + ri * 8) * 16 : 0;
             const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
-
-            u32x4 bf[FK];
 #pragma unroll
             for (int j = 0; j < FK; ++j) {
                 const u32x2 lo = lds_read_tr16_b64(ob + b_lane[j] + opix);
@@ -228,24 +230,30 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
                 bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < FC; ++i) {
-                    // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
-                    unsigned w[2 * WIN];
+                for (int i = 0; i < FC; ++i)
 #pragma unroll
                     for (int g = 0; g < WIN; ++g) {
+                        // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
                         const u32x2 v = lds_read_tr16_b64(ib + a_lane[i] + ipix + (r * a.LW + 4 * g) * 16);
-                        w[2 * g] = v[0];
-                        w[2 * g + 1] = v[1];
+                        w[r][i][2 * g] = v[0];
+                        w[r][i][2 * g + 1] = v[1];
                     }
+        };
+        auto mma_pair = [&](const unsigned (&w)[R][FC][2 * WIN], const u32x4 (&bf)[FK]) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < FC; ++i)
 #pragma unroll
                     for (int s = 0; s < S; ++s) {
                         u32x4 af;
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
                             const int lo = d + s / 2;
-                            af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[lo + 1], w[lo], 16) : w[lo];
+                            af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][lo + 1], w[r][i][lo], 16)
+                                            : w[r][i][lo];
                         }
 #pragma unroll
                         for (int j = 0; j < FK; ++j)
@@ -253,8 +261,12 @@ __global__ __launch_bounds__(256) void upd_rows_bf16_kernel(const UpdArgs a)
                                 __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf[j]),
                                 acc[r * S + s][i][j], 0, 0, 0);
                     }
-                }
-            }
+        };
+        unsigned w0[R][FC][2 * WIN];
+        u32x4 b0[FK];
+        for (int t = wave_p; 2 * t < nruns; t += WP) {
+            load_pair(t, w0, b0);
+            mma_pair(w0, b0);
         }
         wait_all_memory();
         __syncthreads();
@@ -295,8 +307,8 @@ struct UpdRowsEntry {
         {R, S, WC, WK, WP, FC, FK}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK>, 0    \
     }
 static UpdRowsEntry g_rows[] = {
-    UPD_ROWS_ENTRY(3, 3, 2, 2, 1, 1, 2),  // 64 x 128 channels
-    UPD_ROWS_ENTRY(3, 3, 2, 1, 2, 1, 2),  // 64 x 64 channels, two waves along pixels
+    UPD_ROWS_ENTRY(3, 3, 2, 4, 1, 1, 1),  // 64 x 128 channels, eight waves
+    UPD_ROWS_ENTRY(3, 3, 2, 2, 2, 1, 1),  // 64 x 64 channels, two wave groups along pixels
 };
 
 static UpdRowsEntry *find_rows(const UpdRowsVariant &v)
@@ -321,7 +333,7 @@ hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds
         if (err != hipSuccess) return err;
         e->lds_attr = lds_bytes;
     }
-    hipLaunchKernelGGL(e->fn, dim3(grid), dim3(256), lds_bytes, stream, a);
+    hipLaunchKernelGGL(e->fn, dim3(grid), dim3(v.wc * v.wk * v.wp * 64), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
