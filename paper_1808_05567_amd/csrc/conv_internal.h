@@ -138,6 +138,8 @@ static __device__ __forceinline__ int fast_div(int x, float inv)
 // (base, byte size) plus a 32-bit per-lane byte offset.  Loads whose offset is
 // at or beyond the size return zero and stores there are dropped, so padding
 // and ragged tiles need no branches: such lanes carry the offset kOutOfRange.
+// A wave-uniform byte offset (channel block, reduction step) rides in the
+// scalar offset of the instruction; the range check covers the sum.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 constexpr unsigned kOutOfRange = 0xFFFFFFFFu;
 static __device__ __forceinline__ rsrc_t make_rsrc(const void *base, size_t skip, size_t total)
@@ -150,10 +152,12 @@ static __device__ __forceinline__ rsrc_t make_rsrc(const void *base, size_t skip
 // 16-byte load from global memory straight into LDS: lane i of the wave writes
 // lds_wave_base + 16*i (the LDS base must be wave-uniform), zero if out of range.
 static __device__ __forceinline__ void load_to_lds_16(rsrc_t r, unsigned byte_off,
+                                                      unsigned uniform_off,
                                                       unsigned char *lds_wave_base)
 {
     typedef __attribute__((address_space(3))) void *lds_vptr_t;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, uniform_off,
+                                             0, 0);
 }
 // Wait until every outstanding memory operation of this wave, staging loads included, is done.
 static __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }

@@ -46,12 +46,12 @@ struct Elem<CONV_F32> {
                                                      c, 0, 0, 0);
     }
     // Store 4 consecutive channels of one pixel (dropped if byte_off is out of range).
-    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, float x0, float x1,
-                                                  float x2, float x3)
+    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
+                                                  float x0, float x1, float x2, float x3)
     {
         u32x4 v = {__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2),
                    __float_as_uint(x3)};
-        __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, uniform_off, 0);
     }
 };
 
@@ -71,11 +71,11 @@ struct Elem<CONV_BF16> {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                     __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, float x0, float x1,
-                                                  float x2, float x3)
+    static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
+                                                  float x0, float x1, float x2, float x3)
     {
         u32x2 v = {pack_bf16x2(x0, x1), pack_bf16x2(x2, x3)};
-        __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, uniform_off, 0);
     }
 };
 
@@ -178,6 +178,8 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
     const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
     const int wave_chunk = wave * 64;  // first chunk a wave's load instruction fills
+    const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
+    const rsrc_t rsrc_wt = make_rsrc(a.wt, 0, wt_bytes);
     // Load number l of a step: the input loads (plane-major) come first, then the weights.
     constexpr int NLOADS = NPL * PPT + WPT;
     auto fetch_one = [&](int st, int l) {
@@ -187,14 +189,14 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         if (l < NPL * PPT) {
             const int pl = l / PPT, i = l - pl * PPT;
             if (i * NT + wave_chunk < a.PLS) {  // wave-uniform; PLS is a multiple of 64
-                const rsrc_t ri = make_rsrc(a.in, (size_t)(cb0 + pl) * HW * 16, in_bytes);
-                load_to_lds_16(ri, g_off[i], ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
+                load_to_lds_16(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
+                               ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
             }
         } else {
             const int i = l - NPL * PPT;
             if (i * NT + wave_chunk < WCH) {  // wave-uniform
-                const rsrc_t rw = make_rsrc(a.wt, (size_t)cb0 * NTAPS * a.Kp * 16, wt_bytes);
-                load_to_lds_16(rw, w_off[i], wb + (i * NT + wave_chunk) * 16);
+                load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
+                               wb + (i * NT + wave_chunk) * 16);
             }
         }
     };
@@ -306,10 +308,11 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     }
 
     // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels.
-    // The channel block of a store is wave-uniform, so it moves the scalar base
-    // of the resource; the per-lane offset is the pixel's.
+    // The channel block of a store is wave-uniform, so it rides in the scalar
+    // offset; the per-lane offset is the pixel's.
     const size_t oplane = (size_t)a.OH * a.OW * 16;
     const size_t out_bytes = (size_t)a.N * Kb_out * oplane;
+    const rsrc_t ro = make_rsrc(a.out, 0, out_bytes);
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
 #pragma unroll
@@ -317,15 +320,14 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
             if (krow0 >= a.Kp) continue;                            // wave-uniform
             // fp32: 8 rows = blocks 2*q (h=0) and 2*q+1 (h=1); bf16: one block, halves by h
-            const size_t skip = (size_t)(krow0 / V) * oplane;
+            const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
             const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
-            const rsrc_t ro = make_rsrc(a.out, skip, out_bytes);
 #pragma unroll
             for (int j = 0; j < FM; ++j) {
                 // (fp32: the upper lane half's block may lie beyond the last channel block)
                 const bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
                 const unsigned off = live ? obyte[j] + lane_off : kOutOfRange;
-                E_::store4(ro, off, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
+                E_::store4(ro, off, skip, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
                            acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
                 if (a.zero_fill) {
                     const int pix = (int)(obyte[j] >> 4);
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
                             if ((dy | dx) == 0) continue;
                             const bool in = live && oy + dy < a.OH && ox + dx < a.OW;
                             E_::store4(ro, in ? off + (unsigned)(dy * a.OW + dx) * 16u : kOutOfRange,
-                                       0.f, 0.f, 0.f, 0.f);
+                                       skip, 0.f, 0.f, 0.f, 0.f);
                         }
                 }
             }

@@ -103,6 +103,8 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
     const size_t out_bytes = (size_t)a.N * a.Kb * PQ * 16;
     const int wave_chunk = wave * 64;
+    const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
+    const rsrc_t rsrc_out = make_rsrc(a.dout, 0, out_bytes);
 
     // Stage the bands of linear output rows [rho0, rho0 + TR) into buffer `buf`.
     auto fetch = [&](int rho0, int buf) {
@@ -135,12 +137,11 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 if (ok) off = (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u;
             }
 #pragma unroll
-            for (int pl = 0; pl < NPI; ++pl) {
-                // channel blocks beyond the tensor: an empty view, everything reads zero
-                const size_t skip = (size_t)(cb0 + pl) * HW * 16;
-                const rsrc_t ri = make_rsrc(a.in, min(skip, in_bytes), in_bytes);
-                load_to_lds_16(ri, off, ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
-            }
+            for (int pl = 0; pl < NPI; ++pl)
+                // (channel blocks beyond the tensor are out of range as a whole: zeros)
+                load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+                               (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
+                               ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
         }
         for (int p0 = 0; p0 < a.PLS_out; p0 += NT) {
             if (p0 + wave_chunk >= a.PLS_out) break;
@@ -157,11 +158,10 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 }
             }
 #pragma unroll
-            for (int pl = 0; pl < NPO; ++pl) {
-                const size_t skip = (size_t)(kb0 + pl) * PQ * 16;
-                const rsrc_t ro = make_rsrc(a.dout, min(skip, out_bytes), out_bytes);
-                load_to_lds_16(ro, off, ob + (pl * a.PLS_out + p0 + wave_chunk) * 16);
-            }
+            for (int pl = 0; pl < NPO; ++pl)
+                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                               (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
+                               ob + (pl * a.PLS_out + p0 + wave_chunk) * 16);
         }
     };
 
