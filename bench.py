@@ -265,12 +265,33 @@ def main():
                              "pct_mfma_peak": round(100 * tf / peak, 1),
                              "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
                              "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
+        # layout conversion, timed on its own (the passes work on resident blocked tensors)
+        from paper_1808_05567_amd import conv as _conv
+        for l, L in layers:
+            nchw = torch.empty((N, l.C, l.H, l.W), dtype=L.tdtype, device="cuda")
+            nkpq = torch.empty((N, l.K, l.P, l.Q), dtype=L.tdtype, device="cuda")
+            for name, fn, src, dst, by in (
+                    ("pack_in", _conv.conv_pack_in, nchw, L.x_blk, 2 * nchw.numel() * es),
+                    ("unpack_out", _conv.conv_unpack_out, L.out_blk, nkpq, 2 * nkpq.numel() * es)):
+                fn(L.h, src, dst)
+                a0 = torch.cuda.Event(enable_timing=True)
+                a1 = torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for _ in range(5):
+                    fn(L.h, src, dst)
+                a1.record()
+                torch.cuda.synchronize()
+                ms = a0.elapsed_time(a1) / 5
+                rows.append({"layer": l.id, "pass": name, "ms": round(ms, 4), "tflops": 0.0,
+                             "pct_mfma_peak": 0.0, "ceiling_tflops": 0.0, "pct_ceiling": 0.0,
+                             "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
+            del nchw, nkpq
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         path = os.path.join(ROOT, "gpurun_out", "layers_%s.json" % args.dtype)
         with open(path, "w") as f:
             json.dump(rows, f, indent=1)
         for r in rows:
-            print("# L%-2d %-3s %8.3f ms %8.2f TF/s %5.1f%% peak %5.1f%% of ceiling %7.1f GB/s" % (
+            print("# L%-2d %-10s %8.3f ms %8.2f TF/s %5.1f%% peak %5.1f%% of ceiling %7.1f GB/s" % (
                 r["layer"], r["pass"], r["ms"], r["tflops"], r["pct_mfma_peak"], r["pct_ceiling"],
                 r["alg_GBps"]), file=sys.stderr)
 

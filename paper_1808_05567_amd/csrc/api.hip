@@ -339,8 +339,8 @@ void plan_upd(conv_plan *p)
                 if (TR < 1) return;
                 const int LR = max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
                 a.LRW = LR * a.LW;
-                a.PLS_in = ceil_div(a.LRW, 64) * 64;
-                a.PLS_out = ceil_div(TR * RP + 8, 64) * 64;
+                a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
+                a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
                 p->upd_lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
                 if (p->upd_lds <= (size_t)kMaxLds) break;
             }

@@ -112,8 +112,12 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         unsigned char *ob = ib + ibytes;
         const int n0 = fast_div(rho0, inv_P);
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P);
-        for (int p0 = 0; p0 < a.PLS_in; p0 += NT) {
-            if (p0 + wave_chunk >= a.PLS_in) break;  // wave-uniform; PLS is a multiple of 64
+        // Positions are staged in whole wave-level loads (64 chunks); the plane pitch is
+        // that count plus 4 pixels, so that the two planes a 16-lane transposing read
+        // touches start 64 bytes apart in the 256-byte bank row.
+        const int cov_in = (a.LRW + 63) & ~63, cov_out = (npxO + 63) & ~63;
+        for (int p0 = 0; p0 < cov_in; p0 += NT) {
+            if (p0 + wave_chunk >= cov_in) break;  // wave-uniform
             const int p = p0 + tid;
             unsigned off = kOutOfRange;
             if (p < a.LRW) {
@@ -143,8 +147,8 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                                (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
                                ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
         }
-        for (int p0 = 0; p0 < a.PLS_out; p0 += NT) {
-            if (p0 + wave_chunk >= a.PLS_out) break;
+        for (int p0 = 0; p0 < cov_out; p0 += NT) {
+            if (p0 + wave_chunk >= cov_out) break;
             const int p = p0 + tid;
             unsigned off = kOutOfRange;
             if (p < a.TR * RP) {

@@ -60,3 +60,25 @@ def test_table1_layer_at_n256(lid, dtype):
         assert np.isfinite(got).all()
     finally:
         L.close()
+
+
+# (the 3-channel first layer is an fp32 workload only)
+N1_CASES = [(lid, dt) for lid in (4, 8, 13, 18, 1, 6, 20) for dt in (conv.CONV_F32, conv.CONV_BF16)
+            if not (lid == 1 and dt == conv.CONV_BF16)]
+
+
+@pytest.mark.parametrize("lid,dtype", N1_CASES,
+                         ids=["L%d-%s" % (l, "bf16" if d else "f32") for l, d in N1_CASES])
+def test_single_image_inference_forward(lid, dtype):
+    """N = 1 forward (latency-bound, few tiles): full-tensor oracle comparison."""
+    l = inputs.layer(lid)
+    I = inputs.gen_input(1, l.C, l.H, l.W, lid)
+    Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
+    if dtype == conv.CONV_BF16:
+        I, Wt = inputs.round_to_bf16(I), inputs.round_to_bf16(Wt)
+    L = conv.ConvLayer(1, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dtype)
+    try:
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+        assert rel_l2(got, oracle.fwd(I, Wt, l.stride, l.pad)) <= TOL[dtype]
+    finally:
+        L.close()
