@@ -185,6 +185,9 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
             // one workgroup per CU loses roughly a fifth to exposed barriers/staging
             double cost = igemm_waste(c, N, P, Q, Kp) * (ci == 0 ? 1.0 : 1.2) *
                           (1.0 + 0.01 * (128 / TK));
+            // rounds of workgroups over the 256 CUs: a last, partly filled round costs a full one
+            const int slots = 256 * (ci == 0 ? 2 : 1);
+            cost *= (double)(ceil_div(c.a.total, slots) * slots) / c.a.total;
             // one fragment per wave starves the bf16 matrix core of LDS bandwidth; it only
             // matters where the filter gives the layer enough reuse to be MFMA-bound
             if (dtype == CONV_BF16 && cd.fk == 1 && R * S > 1) cost *= 1.5;
