@@ -322,25 +322,49 @@ void plan_upd(conv_plan *p)
         return;
     }
     p->upd_rows = false;
-    if (bf16 && d.R == 3 && d.S == 3 && d.stride == 1 && f.Cb % 8 == 0) {
-        // bf16 row kernel: 8-pixel runs, filter-column shifts in registers
-        UpdRowsVariant rv = f.Kp <= 64 ? UpdRowsVariant{3, 3, 2, 2, 2, 1, 1}
-                                       : UpdRowsVariant{3, 3, 2, 4, 1, 1, 1};
-        if (upd_rows_variant_exists(rv)) {
+    const bool rows_3x3 = d.R == 3 && d.S == 3 && d.stride == 1;
+    if (bf16 && (rows_3x3 || sampled)) {
+        // bf16 row kernel: 8-pixel runs, filter-column shifts in registers.
+        // 3x3: all nine taps in the wave (144 accumulators).  1x1: the layer is bound by
+        // HBM, so take the channel tile that re-reads the least (input is read once per
+        // output-channel tile, dO once per input-channel tile), then the smaller tile.
+        static const UpdRowsVariant k3x3[2] = {{3, 3, 2, 4, 1, 1, 1}, {3, 3, 2, 2, 2, 1, 1}};
+        static const UpdRowsVariant k1x1[7] = {{1, 1, 2, 2, 2, 1, 1}, {1, 1, 2, 4, 1, 1, 1},
+                                               {1, 1, 4, 2, 1, 1, 1}, {1, 1, 2, 4, 1, 1, 2},
+                                               {1, 1, 4, 2, 1, 2, 1}, {1, 1, 2, 4, 1, 2, 2},
+                                               {1, 1, 4, 2, 1, 2, 2}};
+        UpdRowsVariant rv{};
+        bool have = false;
+        if (rows_3x3) {
+            rv = f.Kp <= 64 ? k3x3[1] : k3x3[0];
+            have = upd_rows_variant_exists(rv);
+        } else {
+            double best = 0;
+            for (const UpdRowsVariant &c : k1x1) {
+                if (!upd_rows_variant_exists(c)) continue;
+                const int TC = c.wc * c.fc * 32, TK = c.wk * c.fk * 32;
+                const double bytes = (double)f.in_bytes * ceil_div(f.Kp, TK) +
+                                     (double)f.out_bytes * ceil_div(f.Cp, TC);
+                const double cost = bytes * (1.0 + 1e-4 * (TC + TK));
+                if (!have || cost < best) { rv = c; best = cost; have = true; }
+            }
+        }
+        if (have) {
             const int TC = rv.wc * rv.fc * 32, TK = rv.wk * rv.fk * 32, NPI = TC / 8, NPO = TK / 8;
             const int NP = d.N * f.P;
             UpdArgs &a = p->ua;
             memset(&a, 0, sizeof(a));
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-            a.R = d.R; a.S = d.S; a.stride = 1; a.pad = d.pad;
+            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
             a.runs = ceil_div(f.Q, 8);
             const int RP = a.runs * 8;
-            a.Hs = f.P - 1 + d.R;
-            a.LW = std::max(d.W + 2 * d.pad, RP + 4);
+            a.sampled = sampled ? 1 : 0;
+            a.Hs = sampled ? f.P : f.P - 1 + d.R;
+            a.LW = sampled ? RP : std::max(d.W + 2 * d.pad, RP + 4);
             int TR = std::min(NP, 64);
             for (;; --TR) {
                 if (TR < 1) return;
-                const int LR = max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
+                const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
                 a.LRW = LR * a.LW;
                 a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
                 a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
@@ -358,10 +382,10 @@ void plan_upd(conv_plan *p)
             splits = ceil_div(NP, rps);
             a.rows_per_split = rps;
             a.splits = splits;
-            a.sampled = 0;
             a.total = tiles * splits;
             a.per_xcd = ceil_div(a.total, 8);
-            if ((double)(d.N + 1) * a.Hs < 4.0e6 && (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 &&
+            if ((double)(d.N + 1) * std::max(a.Hs, f.P) < 4.0e6 &&
+                (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 &&
                 (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
                 p->urv = rv;
                 p->upd_grid = a.per_xcd * 8;

@@ -102,7 +102,6 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     const float inv_runs = 1.0f / (float)a.runs;
     const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
     const size_t out_bytes = (size_t)a.N * a.Kb * PQ * 16;
-    const int wave_chunk = wave * 64;
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
     const rsrc_t rsrc_out = make_rsrc(a.dout, 0, out_bytes);
 
@@ -115,57 +114,71 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         // Positions are staged in whole wave-level loads (64 chunks); the plane pitch is
         // that count plus 4 pixels, so that the two planes a 16-lane transposing read
         // touches start 64 bytes apart in the 256-byte bank row.
+        constexpr int NW = NT / 64;
         const int cov_in = (a.LRW + 63) & ~63, cov_out = (npxO + 63) & ~63;
-        for (int p0 = 0; p0 < cov_in; p0 += NT) {
-            if (p0 + wave_chunk >= cov_in) break;  // wave-uniform
-            const int p = p0 + tid;
-            unsigned off = kOutOfRange;
-            if (p < a.LRW) {
-                const int row = fast_div(p, inv_LW);
-                const int col = p - row * a.LW;
-                int n, ih, iw;
-                bool ok;
-                if (a.sampled) {
-                    const int rho = rho0 + row;
-                    n = fast_div(rho, inv_P);
-                    ih = (rho - n * a.P) * a.stride;
-                    iw = col * a.stride;
-                    ok = rho < rho_end && col < a.Q;
-                } else {
-                    const int lam = lam0 + row;
-                    n = fast_div(lam, inv_Hs);
-                    ih = lam - n * a.Hs - a.pad;
-                    iw = col - a.pad;
-                    ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-                }
-                if (ok) off = (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u;
+        // byte offset of staged input position p / dO position p in channel block 0
+        auto in_off = [&](int p) -> unsigned {
+            if (p >= a.LRW) return kOutOfRange;
+            const int row = fast_div(p, inv_LW);
+            const int col = p - row * a.LW;
+            int n, ih, iw;
+            bool ok;
+            if (a.sampled) {
+                const int rho = rho0 + row;
+                n = fast_div(rho, inv_P);
+                ih = (rho - n * a.P) * a.stride;
+                iw = col * a.stride;
+                ok = rho < rho_end && col < a.Q;
+            } else {
+                const int lam = lam0 + row;
+                n = fast_div(lam, inv_Hs);
+                ih = lam - n * a.Hs - a.pad;
+                iw = col - a.pad;
+                ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
+            return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
+        };
+        auto out_off = [&](int p) -> unsigned {
+            if (p >= a.TR * RP) return kOutOfRange;
+            const int trow = fast_div(p, inv_RP);
+            const int col = p - trow * RP;
+            const int rho = rho0 + trow;
+            if (rho >= rho_end || col >= a.Q) return kOutOfRange;
+            const int n = fast_div(rho, inv_P);
+            const int oj = rho - n * a.P;
+            return (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
+        };
+        // (channel blocks beyond the tensor are out of range as a whole: zeros)
+        auto load_in = [&](int pl, int p0, unsigned off) {
+            load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+                           (unsigned)(cb0 + pl) * (unsigned)HW * 16u, ib + (pl * a.PLS_in + p0) * 16);
+        };
+        auto load_out = [&](int pl, int p0, unsigned off) {
+            load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                           (unsigned)(kb0 + pl) * (unsigned)PQ * 16u, ob + (pl * a.PLS_out + p0) * 16);
+        };
+        if (cov_in >= 3 * 64) {
+            // several position chunks: a wave takes whole chunks, all planes
+            for (int p0 = wave * 64; p0 < cov_in; p0 += NT) {
+                const unsigned off = in_off(p0 + lane);
 #pragma unroll
-            for (int pl = 0; pl < NPI; ++pl)
-                // (channel blocks beyond the tensor are out of range as a whole: zeros)
-                load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
-                               (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
-                               ib + (pl * a.PLS_in + p0 + wave_chunk) * 16);
-        }
-        for (int p0 = 0; p0 < cov_out; p0 += NT) {
-            if (p0 + wave_chunk >= cov_out) break;
-            const int p = p0 + tid;
-            unsigned off = kOutOfRange;
-            if (p < a.TR * RP) {
-                const int trow = fast_div(p, inv_RP);
-                const int col = p - trow * RP;
-                const int rho = rho0 + trow;
-                if (rho < rho_end && col < a.Q) {
-                    const int n = fast_div(rho, inv_P);
-                    const int oj = rho - n * a.P;
-                    off = (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
-                }
+                for (int pl = 0; pl < NPI; ++pl) load_in(pl, p0, off);
             }
+            for (int p0 = wave * 64; p0 < cov_out; p0 += NT) {
+                const unsigned off = out_off(p0 + lane);
 #pragma unroll
-            for (int pl = 0; pl < NPO; ++pl)
-                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
-                               (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
-                               ob + (pl * a.PLS_out + p0 + wave_chunk) * 16);
+                for (int pl = 0; pl < NPO; ++pl) load_out(pl, p0, off);
+            }
+        } else {
+            // few chunks (1x1 layers): the planes of a chunk are dealt round-robin to the waves
+            for (int p0 = 0, c = 0; p0 < cov_in; p0 += 64, ++c) {
+                const unsigned off = in_off(p0 + lane);
+                for (int pl = (wave + c) % NW; pl < NPI; pl += NW) load_in(pl, p0, off);
+            }
+            for (int p0 = 0, c = 0; p0 < cov_out; p0 += 64, ++c) {
+                const unsigned off = out_off(p0 + lane);
+                for (int pl = (wave + c) % NW; pl < NPO; pl += NW) load_out(pl, p0, off);
+            }
         }
     };
 
@@ -313,6 +326,14 @@ struct UpdRowsEntry {
 static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(3, 3, 2, 4, 1, 1, 1),  // 64 x 128 channels, eight waves
     UPD_ROWS_ENTRY(3, 3, 2, 2, 2, 1, 1),  // 64 x 64 channels, two wave groups along pixels
+    // 1x1 (input staged sampled): channel tiles TC x TK
+    UPD_ROWS_ENTRY(1, 1, 2, 2, 2, 1, 1),  //  64 x  64
+    UPD_ROWS_ENTRY(1, 1, 2, 4, 1, 1, 1),  //  64 x 128
+    UPD_ROWS_ENTRY(1, 1, 4, 2, 1, 1, 1),  // 128 x  64
+    UPD_ROWS_ENTRY(1, 1, 2, 4, 1, 1, 2),  //  64 x 256
+    UPD_ROWS_ENTRY(1, 1, 4, 2, 1, 2, 1),  // 256 x  64
+    UPD_ROWS_ENTRY(1, 1, 2, 4, 1, 2, 2),  // 128 x 256
+    UPD_ROWS_ENTRY(1, 1, 4, 2, 1, 2, 2),  // 256 x 128
 };
 
 static UpdRowsEntry *find_rows(const UpdRowsVariant &v)
