@@ -20,6 +20,8 @@
 //   * Section II-F work split (N, then K_b, then P_b/Q_b): the grid enumerates
 //     (row tile, column tile, channel tile) with the channel tile fastest and
 //     consecutive tiles kept on one XCD so that they share its L2.
+#include <type_traits>
+
 #include "conv_internal.h"
 
 namespace convmi {
@@ -124,11 +126,24 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
     const int HW = a.H * a.W;
 
+    // Staging: 16-byte buffer loads that write straight into LDS (lane i of a
+    // wave lands at base + 16*i), so no registers, VALU work or LDS-write
+    // instructions are spent on it.  Padding (outside the image, beyond the
+    // channel count, the odd filler entry, the tail of a plane's last
+    // wave-level load) is out of range and arrives as zeros.  Per step only the
+    // scalar offset moves; the per-lane offsets never change.
+    //
+    // A plane is PLS chunks (a multiple of 64), the weights of a step WCH
+    // chunks (also one).  Load i of a wave covers chunks [c, c + 64) with
+    // c = min(i*NT + 64*wave, size - 64): where the waves' shares are ragged the
+    // surplus loads repeat the last chunk group (same bytes to the same place),
+    // which keeps the staging code free of branches.
+    const int wave_chunk = wave * 64;
     // ---- per-thread source byte offsets of the staged input pixels (plane 0)
     unsigned g_off[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-        const int p = tid + i * NT;
+        const int p = min(i * NT + wave_chunk, a.PLS - 64) + lane;
         unsigned off = kOutOfRange;
         if (p < a.LRW) {
             const int row = fast_div(p, inv_LW);
@@ -156,28 +171,19 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     unsigned w_off[WPT];
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
-        const int w = tid + i * NT;
+        const int w = min(i * NT + wave_chunk, WCH - 64) + lane;
         unsigned off = kOutOfRange;
-        if (w < WCH) {
-            const int e = w / TK;
-            const int k = w - e * TK;
-            const int tap = e / NPL;
-            const int pl = e - tap * NPL;
-            if (tap < NTAPS && k0 + k < a.Kp)
-                off = (unsigned)((pl * NTAPS + tap) * a.Kp + k0 + k) * 16u;
-        }
+        const int e = w / TK;
+        const int k = w - e * TK;
+        const int tap = e / NPL;
+        const int pl = e - tap * NPL;
+        if (tap < NTAPS && k0 + k < a.Kp)
+            off = (unsigned)((pl * NTAPS + tap) * a.Kp + k0 + k) * 16u;
         w_off[i] = off;
     }
 
-    // Staging: 16-byte buffer loads that write straight into LDS (lane i of a
-    // wave lands at base + 16*i), so no registers, VALU work or LDS-write
-    // instructions are spent on it.  Padding (outside the image, beyond the
-    // channel count, the odd filler entry, the tail of a plane's last
-    // wave-level load) is out of range and arrives as zeros.  Per step only the
-    // scalar base of the resource moves; the per-lane offsets never change.
     const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
     const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
-    const int wave_chunk = wave * 64;  // first chunk a wave's load instruction fills
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
     const rsrc_t rsrc_wt = make_rsrc(a.wt, 0, wt_bytes);
     // Load number l of a step: the input loads (plane-major) come first, then the weights.
@@ -188,23 +194,19 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         unsigned char *ib = wb + WBYTES;
         if (l < NPL * PPT) {
             const int pl = l / PPT, i = l - pl * PPT;
-            if (i * NT + wave_chunk < a.PLS) {  // wave-uniform; PLS is a multiple of 64
-                load_to_lds_16(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
-                               ib + (pl * a.PLS + i * NT + wave_chunk) * 16);
-            }
+            load_to_lds_16(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
+                           ib + (pl * a.PLS + min(i * NT + wave_chunk, a.PLS - 64)) * 16);
         } else {
             const int i = l - NPL * PPT;
-            if (i * NT + wave_chunk < WCH) {  // wave-uniform
-                load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
-                               wb + (i * NT + wave_chunk) * 16);
-            }
+            load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
+                           wb + min(i * NT + wave_chunk, WCH - 64) * 16);
         }
     };
     auto fetch = [&](int st) {
 #pragma unroll
         for (int l = 0; l < NLOADS; ++l) fetch_one(st, l);
     };
-    // All of this wave's staging loads have landed in LDS (vmcnt = 0).
+    // All of this wave's staging loads have landed in LDS and all of its LDS reads are done.
     auto staged = [&]() { wait_all_memory(); };
 
     // ---- per-lane pixel bookkeeping for the B fragments and the epilogue
@@ -242,14 +244,12 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     staged();
     __syncthreads();
 
-    for (int st = 0; st < a.n_stage; ++st) {
-        const bool more = st + 1 < a.n_stage;
-        if (NPL == 1 && more) fetch(st + 1);
-        const unsigned char *wb = lds + (st & 1) * bufbytes;
-        const unsigned char *ib = wb + WBYTES;
-
-        if constexpr (NPL == 1) {
-            // One channel block per step: the two lane halves take two taps.
+    if constexpr (NPL == 1) {
+        // One channel block per step: the two lane halves take two taps.
+        for (int st = 0; st < a.n_stage; ++st) {
+            if (st + 1 < a.n_stage) fetch(st + 1);
+            const unsigned char *wb = lds + (st & 1) * bufbytes;
+            const unsigned char *ib = wb + WBYTES;
 #pragma unroll 1
             for (int q = 0; q < NENT / 2; ++q) {
                 const int t0 = 2 * q;
@@ -269,42 +269,71 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
 #pragma unroll
                     for (int j = 0; j < FM; ++j) E_::mma(af[i], bf[j], acc[i][j]);
             }
-        } else {
+            staged();
+            __syncthreads();
+        }
+    } else {
+        // A step is NQ MFMA rounds (tap x plane pair).  The operands of round
+        // q+1 are read from LDS into a second register set while the MFMAs of
+        // round q issue.  The next step's staging loads all issue in round 0
+        // and are awaited before the LAST round, together with this wave's final
+        // reads of the current buffer; after that barrier the last round already
+        // reads the next step's first operands, and the buffer just left is free
+        // for the loads of the step after.
+        constexpr int NQ = NTAPS * (NPL / 2);
+        static_assert(NQ >= 2, "a step needs two MFMA rounds");
+        u32x4 ac[FK], bc[FM];
+        auto read_round = [&](int buf, int q, u32x4(&af)[FK], u32x4(&bf)[FM]) {
+            const unsigned char *wb = lds + buf * bufbytes;
+            const unsigned char *ib = wb + WBYTES;
+            const int tap = q / (NPL / 2), pp = q - tap * (NPL / 2);
+            const int toff = ((tap / S) * a.LW + (tap % S) + 2 * pp * a.PLS) * 16;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int i = 0; i < FK; ++i)
+                af[i] = *reinterpret_cast<const u32x4 *>(wb + a_base + (2 * q * TK + 32 * i) * 16);
 #pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    const int toff = (r * a.LW + s) * 16;
+            for (int j = 0; j < FM; ++j)
+                bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff);
+        };
+        auto step = [&](int st, auto more_tag) {
+            constexpr bool MORE = decltype(more_tag)::value;
 #pragma unroll
-                    for (int pp = 0; pp < NPL / 2; ++pp) {
-                        const int q = (r * S + s) * (NPL / 2) + pp;
-                        // The next step's staging loads are spread over this step's
-                        // MFMA stream so that the memory pipeline never backs up.
-                        constexpr int NQ = NTAPS * (NPL / 2);
-                        if (more) {
+            for (int q = 0; q < NQ; ++q) {
+                u32x4 an[FK], bn[FM];
+                if (q + 1 < NQ)
+                    read_round(st & 1, q + 1, an, bn);
+                else if (MORE)
+                    read_round((st + 1) & 1, 0, an, bn);
+                if (MORE && q == 0) fetch(st + 1);
 #pragma unroll
-                            for (int l = q * NLOADS / NQ; l < (q + 1) * NLOADS / NQ; ++l)
-                                fetch_one(st + 1, l);
-                        }
-                        u32x4 af[FK], bf[FM];
+                for (int i = 0; i < FK; ++i)
 #pragma unroll
-                        for (int i = 0; i < FK; ++i)
-                            af[i] = *reinterpret_cast<const u32x4 *>(wb + a_base +
-                                                                     (2 * q * TK + 32 * i) * 16);
+                    for (int j = 0; j < FM; ++j) E_::mma(ac[i], bc[j], acc[i][j]);
+                // Issue order of the round: one MFMA, then an LDS read or a
+                // staging load, and so on, instead of all reads first.
+                constexpr int NMFMA = FK * FM * (DT == CONV_F32 ? 4 : 1);
 #pragma unroll
-                        for (int j = 0; j < FM; ++j)
-                            bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff +
-                                                                     2 * pp * a.PLS * 16);
+                for (int k = 0; k < NMFMA; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // staging loads
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (MORE && q == NQ - 2) {
+                    staged();
+                    __syncthreads();
+                }
+                if (q + 1 < NQ || MORE) {
 #pragma unroll
-                        for (int i = 0; i < FK; ++i)
+                    for (int i = 0; i < FK; ++i) ac[i] = an[i];
 #pragma unroll
-                            for (int j = 0; j < FM; ++j) E_::mma(af[i], bf[j], acc[i][j]);
-                    }
+                    for (int j = 0; j < FM; ++j) bc[j] = bn[j];
                 }
             }
-        }
-        staged();
-        __syncthreads();
+        };
+        read_round(0, 0, ac, bc);
+        for (int st = 0; st + 1 < a.n_stage; ++st) step(st, std::true_type{});
+        step(a.n_stage - 1, std::false_type{});
     }
 
     // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels.
