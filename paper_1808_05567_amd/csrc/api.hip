@@ -24,6 +24,8 @@ struct IgemmPlan {
 struct BwdClass {  // one stride-parity class of the generic backward pass
     IgemmPlan p;
     WtXformArgs x{};
+    WtMergeArgs m{};      // all classes in one launch (merged == true)
+    bool merged = false;
     size_t ws_off = 0;
 };
 
@@ -127,6 +129,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.N = N; a.Cb = Cb; a.H = H; a.W = W; a.Kp = Kp; a.P = P; a.Q = Q;
     a.stride = stride; a.pad_h = pad_h; a.pad_w = pad_w;
     a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
+    a.shuffle = 0; a.out_kb = Kp / V;
     a.TR = TR; a.TQ = TQ;
     a.n_qt = ceil_div(Q, TQ);
     a.n_mt = ceil_div(N * P, TR);
@@ -173,12 +176,15 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
     struct Cand { int wk, wm, fk, fm; };
     // bf16: two channel fragments per wave halve the LDS reads per MFMA (one
     // fragment per wave cannot keep the bf16 matrix core fed from 128 B/clk of LDS)
-    const Cand cands[5] = {{1, 4, 2, 4}, {2, 2, 2, 7}, {1, 4, 2, 7}, {4, 1, 1, 7}, {2, 2, 1, 7}};
+    // (the last: 32 rows, for results with at most 32 channel rows)
+    const Cand cands[6] = {{1, 4, 2, 4}, {2, 2, 2, 7}, {1, 4, 2, 7}, {4, 1, 1, 7}, {2, 2, 1, 7},
+                           {1, 4, 1, 7}};
     for (int ci = 0; ci < 2; ++ci)
         for (const Cand &cd : cands) {
             if (cd.fk == 2 && dtype != CONV_BF16) continue;
             const int TK = cd.wk * cd.fk * 32;
             if (TK > 64 && Kp <= TK / 2) continue;
+            if (TK == 32 && Kp > 32) continue;
             IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
                                     ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, cd.fm, caps[ci]);
             if (!c.ok) continue;
@@ -239,6 +245,50 @@ void plan_bwd(conv_plan *p)
     // the dI position modulo the stride, over the taps congruent to it.
     const int st = d.stride;
     if (st * st > 16) return;
+    // dI with one channel block (conv1): the classes' sub-filters become the
+    // rows of one filter over their common window, class (py, px) in channel
+    // block py*st+px of the result, and the store interleaves the blocks into
+    // the st x st cells of dI.  One launch, and st*st*vlen live rows per MFMA
+    // instead of vlen.
+    if (f.Cb == 1 && st * st * f.vlen <= 32 && st <= 4) {
+        BwdClass &b = p->bwd[0];
+        WtMergeArgs &m = b.m;
+        memset(&m, 0, sizeof(m));
+        int padU[2] = {0, 0}, win[2] = {1, 1};
+        for (int ax = 0; ax < 2; ++ax) {
+            const int F = ax == 0 ? d.R : d.S;
+            int *sub = ax == 0 ? m.rsub : m.ssub, *roff = ax == 0 ? m.roff : m.soff;
+            int *sh = ax == 0 ? m.rsh : m.ssh;
+            int padc[4];
+            for (int pp = 0; pp < st; ++pp) {
+                const int ro = (pp + d.pad) % st;
+                sub[pp] = ro < F ? ceil_div(F - ro, st) : 0;
+                roff[pp] = ro;
+                padc[pp] = std::max(sub[pp], 1) - 1 - (pp + d.pad) / st;
+                padU[ax] = pp == 0 ? padc[pp] : std::max(padU[ax], padc[pp]);
+            }
+            for (int pp = 0; pp < st; ++pp) {
+                sh[pp] = padU[ax] - padc[pp];
+                win[ax] = std::max(win[ax], std::max(sub[pp], 1) + sh[pp]);
+            }
+        }
+        m.Kb = f.Kb; m.Kp = f.Kp; m.R = d.R; m.S = d.S; m.R2 = win[0]; m.S2 = win[1]; m.st = st;
+        const int Hc = ceil_div(d.H, st), Wc = ceil_div(d.W, st);
+        if (padU[0] >= 0 && padU[1] >= 0) {
+            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, st * st * f.vlen, Hc, Wc, win[0], win[1], 1,
+                             padU[0], padU[1], d.H, d.W, st, 0, 0, 0);
+            if (b.p.ok) {
+                b.p.a.shuffle = 1;
+                b.p.a.out_kb = 1;
+                b.merged = true;
+                b.ws_off = 0;
+                p->bwd_mode = 3;
+                p->n_bwd = 1;
+                p->bwd_ws = (size_t)f.Kb * win[0] * win[1] * st * st * f.vlen * f.vlen * es;
+                return;
+            }
+        }
+    }
     const int R2 = ceil_div(d.R, st), S2 = ceil_div(d.S, st);
     size_t off = 0;
     int n = 0;
@@ -569,13 +619,21 @@ conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, v
     hipStream_t s = (hipStream_t)stream;
     for (int i = 0; i < h->n_bwd; ++i) {
         const BwdClass &b = h->bwd[i];
-        WtXformArgs x = b.x;
-        x.src = wt;
-        x.dst = static_cast<char *>(ws) + b.ws_off;
-        if (launch_wt_xform(h->d.dtype, x, s) != hipSuccess) return CONV_ELAUNCH;
+        void *wt2 = static_cast<char *>(ws) + b.ws_off;
+        if (b.merged) {
+            WtMergeArgs m = b.m;
+            m.src = wt;
+            m.dst = wt2;
+            if (launch_wt_merge(h->d.dtype, m, s) != hipSuccess) return CONV_ELAUNCH;
+        } else {
+            WtXformArgs x = b.x;
+            x.src = wt;
+            x.dst = wt2;
+            if (launch_wt_xform(h->d.dtype, x, s) != hipSuccess) return CONV_ELAUNCH;
+        }
         IgemmArgs a = b.p.a;
         a.in = dout;
-        a.wt = x.dst;
+        a.wt = wt2;
         a.out = din;
         if (launch_igemm(b.p.v, a, b.p.lds, b.p.grid, s) != hipSuccess) return CONV_ELAUNCH;
     }

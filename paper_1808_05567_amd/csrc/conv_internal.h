@@ -36,6 +36,9 @@ struct IgemmArgs {
     int ostr;      // result pixel (oj,oi) is written at (oj*ostr+oy0, oi*ostr+ox0)
     int oy0, ox0;
     int zero_fill; // ostr>1: also write zeros to the other positions of each ostr x ostr cell
+    int shuffle;   // ostr>1: result channel block b is position (b / ostr, b % ostr) of the
+                   // ostr x ostr cell of an output tensor with ONE channel block
+    int out_kb;    // channel blocks of the output tensor
     int TR, TQ;    // tile = TR linear output rows (n*P+oj) x TQ columns
     int n_qt;      // column tiles
     int n_mt;      // row tiles
@@ -74,6 +77,20 @@ struct WtXformArgs {
     int r_off, s_off, Rsub, Ssub;
 };
 hipError_t launch_wt_xform(int dtype, const WtXformArgs &a, hipStream_t stream);
+
+// Weight transform for a strided backward pass whose dI has one channel block:
+// the sub-filters of all stride-parity classes side by side as the rows of ONE
+// filter over a common window,  dst[kb][u][v][cls*V + c][k%V],  cls = py*st + px.
+// Class row index py uses window rows u with r2 = u - rsh[py] in [0, rsub[py]),
+// source tap r = st*(rsub[py]-1-r2) + roff[py]; columns likewise.
+struct WtMergeArgs {
+    const void *src;  // Wb[1][R][S][Kp][v]
+    void *dst;        // [Kb][R2][S2][st*st*v][v]
+    int Kb, Kp, R, S, R2, S2, st;
+    int rsub[4], roff[4], rsh[4];
+    int ssub[4], soff[4], ssh[4];
+};
+hipError_t launch_wt_merge(int dtype, const WtMergeArgs &a, hipStream_t stream);
 
 // Weight update (Algorithm 8): partial sums over slices of the pixel range,
 // then a fixed-order reduction.

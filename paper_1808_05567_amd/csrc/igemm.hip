@@ -212,7 +212,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     // ---- per-lane pixel bookkeeping for the B fragments and the epilogue
     int bpos[FM];
     unsigned obyte[FM];  // byte offset of the lane's pixel in output channel block 0
-    const int Kb_out = a.Kp / V;
+    const int Kb_out = a.out_kb;
 #pragma unroll
     for (int j = 0; j < FM; ++j) {
         const int m = (wave_m * FM + j) * 32 + l32;
@@ -349,12 +349,23 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
             if (krow0 >= a.Kp) continue;                            // wave-uniform
             // fp32: 8 rows = blocks 2*q (h=0) and 2*q+1 (h=1); bf16: one block, halves by h
-            const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
-            const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
+            // Shuffle mode: the lane's channel block is a position of the ostr x ostr cell.
+            const int blk = krow0 / V + (V == 4 ? h : 0);
+            const int cy = blk / a.ostr, cx = blk - cy * a.ostr;
+            const unsigned skip = a.shuffle ? 0u : (unsigned)(krow0 / V) * (unsigned)oplane;
+            const unsigned lane_off =
+                a.shuffle ? (unsigned)(cy * a.OW + cx) * 16u + (V == 4 ? 0u : (unsigned)h * 8u)
+                          : ((V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u);
 #pragma unroll
             for (int j = 0; j < FM; ++j) {
                 // (fp32: the upper lane half's block may lie beyond the last channel block)
-                const bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
+                bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
+                if (a.shuffle) {
+                    const int pix = (int)(obyte[j] >> 4);
+                    const int ox = pix % a.OW;
+                    const int oy = (pix / a.OW) % a.OH;
+                    live = live && oy + cy < a.OH && ox + cx < a.OW;
+                }
                 const unsigned off = live ? obyte[j] + lane_off : kOutOfRange;
                 E_::store4(ro, off, skip, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
                            acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
@@ -400,8 +411,11 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 1, 1, 2),
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 3, 3, 3),
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 7, 7, 12),
-    // 4x4: the stride-2 residue classes of a 7x7 backward pass (conv1)
+    // 4x4: the stride-2 residue classes of a 7x7 backward pass (conv1), one launch each
+    // or, where dI has a single channel block, all four as the rows of one filter
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 4, 4, 4),
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 4, 4, 6),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 2, 4, 4, 6),
     // bf16
     IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 3, 3, 3),

@@ -102,6 +102,37 @@ __global__ __launch_bounds__(256) void wt_xform_kernel(const WtXformArgs a, int 
     for (int kk = 0; kk < V; ++kk) dst[(size_t)idx * V + kk] = v[kk];
 }
 
+// One thread per (kb, u, v, row): V consecutive output channels k of channel block kb.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void wt_merge_kernel(const WtMergeArgs a, int total)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const T *src = static_cast<const T *>(a.src);
+    T *dst = static_cast<T *>(a.dst);
+    const int rows = a.st * a.st * V;
+    const int row = idx % rows;
+    int t = idx / rows;
+    const int v = t % a.S2;
+    t /= a.S2;
+    const int u = t % a.R2;
+    const int kb = t / a.R2;
+    const int cls = row / V, c = row % V;
+    const int py = cls / a.st, px = cls % a.st;
+    const int r2 = u - a.rsh[py], s2 = v - a.ssh[px];
+    const bool tap_ok = r2 >= 0 && r2 < a.rsub[py] && s2 >= 0 && s2 < a.ssub[px];
+    const int r = a.st * (a.rsub[py] - 1 - r2) + a.roff[py];
+    const int s = a.st * (a.ssub[px] - 1 - s2) + a.soff[px];
+    T val[V];
+#pragma unroll
+    for (int kk = 0; kk < V; ++kk) {
+        const int k = kb * V + kk;
+        val[kk] = tap_ok ? src[(((size_t)r * a.S + s) * a.Kp + k) * V + c] : T(0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < V; ++kk) dst[(size_t)idx * V + kk] = val[kk];
+}
+
 static inline int blocks_for(size_t total) { return (int)((total + 255) / 256); }
 
 hipError_t launch_pack_act(int dtype, const void *nchw, void *blk, int N, int C, int H, int W,
@@ -173,6 +204,19 @@ hipError_t launch_wt_xform(int dtype, const WtXformArgs &a, hipStream_t stream)
                            a, total);
     else
         hipLaunchKernelGGL((wt_xform_kernel<uint32_t, 4>), dim3(blocks_for(total)), dim3(256), 0, stream,
+                           a, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_wt_merge(int dtype, const WtMergeArgs &a, hipStream_t stream)
+{
+    const int V = vlen_of(dtype);
+    const int total = a.Kb * a.R2 * a.S2 * a.st * a.st * V;
+    if (dtype == CONV_BF16)
+        hipLaunchKernelGGL((wt_merge_kernel<uint16_t, 8>), dim3(blocks_for(total)), dim3(256), 0, stream,
+                           a, total);
+    else
+        hipLaunchKernelGGL((wt_merge_kernel<uint32_t, 4>), dim3(blocks_for(total)), dim3(256), 0, stream,
                            a, total);
     return hipGetLastError();
 }
