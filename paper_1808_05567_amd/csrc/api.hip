@@ -44,6 +44,7 @@ struct conv_plan {
     bool upd_ok = false;
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
     bool upd_rows = false; // bf16 row kernel (stride 1)
+    bool upd_bands = false; // fp32 eight-wave band kernel
     UpdRowsVariant urv{};
     int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
@@ -447,6 +448,56 @@ void plan_upd(conv_plan *p)
             }
         }
     }
+    p->upd_bands = false;
+    if (!bf16 && !sampled && upd_f32_bands_exists(d.R, d.S)) {
+        // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
+        // bands; the pixel range is split so that one round of workgroups fills the chip.
+        const int NPI = 16, NPO = 16;
+        const int NP = d.N * f.P;
+        const size_t xch = upd_f32_bands_exchange_bytes(d.R, d.S);
+        UpdArgs &a = p->ua;
+        memset(&a, 0, sizeof(a));
+        a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+        a.Hs = (f.P - 1) * d.stride + d.R;
+        a.LW = std::max((f.Q - 1) * d.stride + d.S, d.W + 2 * d.pad);
+        int TR = std::min(NP, 64);
+        size_t lds = 0;
+        // (rows with an odd number of pixel pairs are shared out whole: even bands)
+        const bool by_rows = (f.Q % 2 == 0) && ((f.Q / 2) % 2 == 1);
+        for (;; --TR) {
+            if (TR < 1) break;
+            if (by_rows && TR > 1 && (TR & 1)) continue;
+            const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
+            a.LRW = LR * a.LW;
+            a.PLS_in = ceil_div(a.LRW, 64) * 64 + 1;
+            a.PLS_out = ceil_div(TR * f.Q + 1, 64) * 64 + 1;  // the band and one zero pixel
+            lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+            if (lds <= (size_t)kMaxLds) break;
+        }
+        if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22)) {
+            a.TR = TR;
+            a.n_ct = ceil_div(f.Cb, NPI);
+            a.n_kt = ceil_div(f.Kb, NPO);
+            const int tiles = a.n_ct * a.n_kt;
+            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            splits = std::max(splits, ceil_div(NP * f.Q, 1 << 16));  // chains of at most 2^15 pixels
+            int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+            splits = ceil_div(NP, rps);
+            a.rows_per_split = rps;
+            a.splits = splits;
+            a.sampled = 0;
+            a.total = tiles * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            p->upd_lds = std::max(lds, xch);
+            p->upd_grid = a.per_xcd * 8;
+            p->upd_copies = splits;
+            p->upd_ws = (size_t)splits * f.dwt_bytes;
+            p->upd_bands = true;
+            p->upd_ok = true;
+            return;
+        }
+    }
     UpdVariant v{};
     if (d.R == 3 && d.S == 3)
         v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
@@ -460,7 +511,9 @@ void plan_upd(conv_plan *p)
     const int TC = v.wc * v.fc * 32, TK = v.wk * v.fk * 32, NPI = TC / V, NPO = TK / V, NT = 256;
     // fp32 pairs pixels along a row (row pitch rounded up to even, zero padded);
     // bf16 walks the band's pixels linearly in steps of 16.
-    const int Qp = bf16 ? f.Q : ((f.Q + 1) & ~1);
+    // (1x1 without padding: both bands are flat pixel lists, no row padding needed,
+    // but a band must hold an even number of pixels)
+    const int Qp = (bf16 || sampled) ? f.Q : ((f.Q + 1) & ~1);
     const int NP = d.N * f.P;
     // staged pixels a band may hold (see the staging maps of the two kernels)
     const int max_px_in = bf16 ? v.ppt_in * NT / NPI : NT / v.ppt_in;
@@ -477,6 +530,7 @@ void plan_upd(conv_plan *p)
             LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * d.pad);
             LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, d.R);
         }
+        if (!bf16 && sampled && (TR * Qp) % 2 != 0 && TR > 1) continue;
         npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
         const size_t lds_est = ((size_t)NPI * (LR * LW + 16) + (size_t)NPO * (npxO + 16)) * 16;
         if (LR * LW <= max_px_in && npxO <= max_px_out && lds_est <= lds_cap) break;
@@ -499,7 +553,7 @@ void plan_upd(conv_plan *p)
     splits = ceil_div(NP, rps);
     a.rows_per_split = rps;
     a.splits = splits;
-    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW;
+    a.Hs = Hs; a.LW = LW; a.LRW = LR * LW; a.Qp = Qp;
     if (bf16) {
         // plane pitch = 8 (mod 16) pixels: the two channel planes a 16-lane
         // transposing read touches sit half an LDS row apart
@@ -654,6 +708,7 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.partial = static_cast<float *>(ws);
     const hipError_t e = h->upd_c4     ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
+                         : h->upd_bands ? launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                                        : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
     if (e != hipSuccess) return CONV_ELAUNCH;
     if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
@@ -748,6 +803,14 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
                      h->d.R, h->d.S, h->urv.wc, h->urv.wk, h->urv.wp, h->urv.fc, h->urv.fk, h->ua.TR,
                      h->ua.runs, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt,
                      h->upd_grid, h->upd_lds);
+            return CONV_OK;
+        }
+        if (h->upd_bands) {
+            snprintf(buf, buflen,
+                     "upd_bands dt=0 RS=%dx%d waves=2x2x2 frags=1x1 TR=%d splits=%d rows/split=%d "
+                     "tiles=%dx%d grid=%d lds=%zu",
+                     h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct,
+                     h->ua.n_kt, h->upd_grid, h->upd_lds);
             return CONV_OK;
         }
         snprintf(buf, buflen,

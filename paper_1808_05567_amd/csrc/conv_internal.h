@@ -107,6 +107,7 @@ struct UpdArgs {
     int sampled;
     int total, per_xcd;
     int runs;        // bf16 row kernel: 8-pixel runs per output row
+    int Qp;          // fp32 kernel: row pitch of the staged dO band (pixels)
 };
 struct UpdVariant {
     int dtype;
@@ -128,6 +129,11 @@ struct UpdRowsVariant {
 bool upd_rows_variant_exists(const UpdRowsVariant &v);
 hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,
                            hipStream_t stream);
+// fp32, filters larger than 1x1: eight waves, double-buffered bands
+bool upd_f32_bands_exists(int r, int s);
+size_t upd_f32_bands_exchange_bytes(int r, int s);
+hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+                                hipStream_t stream);
 // fp32, one input channel block (C <= 4): filter-row formulation, 7x7 and 3x3
 hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream);

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
     const int NP = a.N * a.P;
     const int rho_begin = split * a.rows_per_split;
     const int rho_end = min(NP, rho_begin + a.rows_per_split);
-    const int Qp = (a.Q + 1) & ~1;
+    const int Qp = a.Qp;  // dO row pitch in the staged band
     const int npxO = a.TR * Qp;
     const int HW = a.H * a.W;
     const int PQ = a.P * a.Q;
@@ -169,6 +169,41 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
         const int n0 = rho0 / a.P;
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
         const int rows = min(a.TR, rho_end - rho0);
+        if (NTAPS == 1 && a.sampled) {
+            // 1x1 without padding: the two staged bands hold the same pixels in
+            // the same order, so the band is one flat list; the lane halves
+            // take its even and odd pixels.  (An odd count ends on a staged
+            // zero: the band is staged whole and is an even number of pixels.)
+            // The operands of the next pair are read before this pair's MFMAs.
+            const int npairs = (rows * a.Q + 1) / 2;
+            const int last = 2 * (npairs - 1) + h;
+            float an[FC], bn[FK];
+#pragma unroll
+            for (int i = 0; i < FC; ++i) an[i] = ldsI[a_lane[i] + h * V];
+#pragma unroll
+            for (int j = 0; j < FK; ++j) bn[j] = ldsO[b_lane[j] + h * V];
+#pragma unroll 2
+            for (int pr = 0; pr < npairs; ++pr) {
+                const int px = 2 * pr + h;
+                float av[FC], bv[FK];
+#pragma unroll
+                for (int i = 0; i < FC; ++i) av[i] = an[i];
+#pragma unroll
+                for (int j = 0; j < FK; ++j) bv[j] = bn[j];
+                const int nx = min(px + 2, last);
+#pragma unroll
+                for (int i = 0; i < FC; ++i) an[i] = ldsI[a_lane[i] + nx * V];
+#pragma unroll
+                for (int j = 0; j < FK; ++j) bn[j] = ldsO[b_lane[j] + nx * V];
+#pragma unroll
+                for (int i = 0; i < FC; ++i)
+#pragma unroll
+                    for (int j = 0; j < FK; ++j)
+                        acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[0][i][j],
+                                                                            0, 0, 0);
+            }
+            continue;
+        }
         for (int trow = 0; trow < rows; ++trow) {
             const int rho = rho0 + trow;
             const int n = rho / a.P;

@@ -1,0 +1,260 @@
+// fp32 weight-gradient update (Algorithm 8 of the paper, with padding) for
+// filters larger than 1x1: eight waves per workgroup, bands staged by loads
+// that write straight into LDS, double buffered.
+//
+//   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
+//
+// Same mapping of Section II-I / Algorithm 9 as the four-wave kernel (M = 64
+// input channels, N = 64 output channels, reduction = pixels, all R*S taps of
+// a 32x32 block resident in one wave), with these differences:
+//   * 2 x 2 waves over (input, output) channels times TWO pixel groups: the
+//     groups take alternate pixel pairs of a band into private accumulators, which
+//     are summed through LDS after the last band (the "T copies + reduction"
+//     of Section II-I inside the workgroup).  A CU therefore always runs two
+//     waves per SIMD, which is what keeps the matrix core busy while a wave
+//     issues its LDS reads.
+//   * One workgroup owns the whole LDS: the band of the next step streams in
+//     (Section II-E) while the current one is consumed, one barrier per band.
+#include "conv_internal.h"
+
+namespace convmi {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ODDQ: rows of an odd number of pixels
+template <int R, int S, bool ODDQ>
+__global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
+{
+    constexpr int V = 4;
+    constexpr int NT = 512, NW = NT / 64;
+    constexpr int NTAPS = R * S;
+    constexpr int NPI = 16, NPO = 16;  // staged planes: 64 input and 64 output channels
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int ibytes = NPI * a.PLS_in * 16;
+    const int bufbytes = ibytes + NPO * a.PLS_out * 16;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int wave_c = wave & 1;
+    const int wave_k = (wave >> 1) & 1;
+    const int wave_p = wave >> 2;
+
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int rest = lin / a.n_kt;
+    const int ct = rest % a.n_ct;
+    const int split = rest / a.n_ct;
+    const int cb0 = ct * NPI;
+    const int kb0 = kt * NPO;
+
+    const int NP = a.N * a.P;
+    const int rho_begin = split * a.rows_per_split;
+    const int rho_end = min(NP, rho_begin + a.rows_per_split);
+    const int Qp = a.Q;          // the staged dO band is the plain pixel list ...
+    const int npxO = a.TR * Qp + 1;  // ... followed by one zero
+    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
+    const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P, inv_Q = inv_Qp;
+    const rsrc_t rsrc_in = make_rsrc(a.in, 0, (size_t)a.N * a.Cb * HW * 16);
+    const rsrc_t rsrc_out = make_rsrc(a.dout, 0, (size_t)a.N * a.Kb * PQ * 16);
+
+    // Stage the input halo band and the dO band of linear rows [rho0, rho0+TR)
+    // into buffer `buf`.  A wave-level load fills 64 consecutive positions of one
+    // plane; positions outside the image, the split or the tensor arrive as zeros.
+    auto fetch = [&](int rho0, int buf) {
+        unsigned char *ib = lds + buf * bufbytes;
+        unsigned char *ob = ib + ibytes;
+        const int n0 = fast_div(rho0, inv_P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int cov_in = (a.LRW + 63) & ~63, cov_out = (npxO + 63) & ~63;
+        auto in_off = [&](int p) -> unsigned {
+            if (p >= a.LRW) return kOutOfRange;
+            const int row = fast_div(p, inv_LW);
+            const int col = p - row * a.LW;
+            const int lam = lam0 + row;
+            const int n = fast_div(lam, inv_Hs);
+            const int ih = lam - n * a.Hs - a.pad;
+            const int iw = col - a.pad;
+            const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
+        };
+        auto out_off = [&](int p) -> unsigned {
+            if (p >= npxO - 1) return kOutOfRange;
+            const int trow = fast_div(p, inv_Qp);
+            const int col = p - trow * Qp;
+            const int rho = rho0 + trow;
+            if (rho >= rho_end || col >= a.Q) return kOutOfRange;
+            const int n = fast_div(rho, inv_P);
+            const int oj = rho - n * a.P;
+            return (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
+        };
+        // the (position chunk, plane) pairs are dealt round-robin to the waves
+        int turn = wave;
+        for (int p0 = 0; p0 < cov_in; p0 += 64) {
+            const unsigned off = in_off(p0 + lane);
+            for (int pl = turn % NW; pl < NPI; pl += NW)
+                load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+                               (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
+                               ib + (pl * a.PLS_in + p0) * 16);
+            turn += 3;
+        }
+        for (int p0 = 0; p0 < cov_out; p0 += 64) {
+            const unsigned off = out_off(p0 + lane);
+            for (int pl = turn % NW; pl < NPO; pl += NW)
+                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                               (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
+                               ob + (pl * a.PLS_out + p0) * 16);
+            turn += 3;
+        }
+    };
+
+    f32x16 acc[NTAPS];
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+
+    // LDS float offsets of this lane's channel within a staged pixel
+    const int c_lane = wave_c * 32 + l32, k_lane = wave_k * 32 + l32;
+    const int a_lane = (c_lane / V) * a.PLS_in * V + (c_lane % V);
+    const int b_lane = (k_lane / V) * a.PLS_out * V + (k_lane % V);
+
+    if (rho_begin < rho_end) fetch(rho_begin, 0);
+    wait_all_memory();
+    __syncthreads();
+    int buf = 0;
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, buf ^= 1) {
+        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, buf ^ 1);
+        const float *ldsI = reinterpret_cast<const float *>(lds + buf * bufbytes);
+        const float *ldsO = reinterpret_cast<const float *>(lds + buf * bufbytes + ibytes);
+
+        const int n0 = fast_div(rho0, inv_P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int rows = min(a.TR, rho_end - rho0);
+        // The band's pixels form one list (row-major); a wave's lane halves take
+        // the two pixels of a pair and the pixel groups take alternate pairs.
+        if constexpr (ODDQ) {
+            // Odd rows: pairs straddle rows, so each lane finds its pixel's row
+            // and column itself.  A pixel past the end reads the staged zero
+            // that follows the dO band.
+            const int npx = rows * a.Q;
+            const int npairs = (npx + 1) >> 1;
+#pragma unroll 2
+            for (int pr = wave_p; pr < npairs; pr += 2) {
+                const int p = 2 * pr + h;
+                const int pin = p < npx ? p : 0;
+                const int trow = fast_div(pin, inv_Q);
+                const int col = pin - trow * a.Q;
+                const int rho = rho0 + trow;
+                const int n = fast_div(rho, inv_P);
+                const int oj = rho - n * a.P;
+                const int ipos = (n * a.Hs + oj * a.stride - lam0) * a.LW + col * a.stride;
+                const float bv = ldsO[b_lane + p * V];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int s = 0; s < S; ++s) {
+                        const float av = ldsI[a_lane + (ipos + r * a.LW + s) * V];
+                        acc[r * S + s] =
+                            __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[r * S + s], 0, 0, 0);
+                    }
+            }
+        } else {
+            // Even rows: pairs stay inside a row.  The groups alternate the pairs
+            // of each row if those are an even number, else the rows of the band.
+            const bool by_pairs = ((a.Q >> 1) & 1) == 0;
+            const int row_first = by_pairs ? 0 : wave_p, row_step = by_pairs ? 1 : 2;
+            const int col_first = h + (by_pairs ? 2 * wave_p : 0), col_step = by_pairs ? 4 : 2;
+            for (int trow = row_first; trow < rows; trow += row_step) {
+                const int rho = rho0 + trow;
+                const int n = fast_div(rho, inv_P);
+                const int oj = rho - n * a.P;
+                const int irow = (n * a.Hs + oj * a.stride - lam0) * a.LW;
+                const int orow = trow * a.Q;
+#pragma unroll 2
+                for (int col = col_first; col < a.Q; col += col_step) {
+                    const float bv = ldsO[b_lane + (orow + col) * V];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int s = 0; s < S; ++s) {
+                            const float av =
+                                ldsI[a_lane + (irow + r * a.LW + col * a.stride + s) * V];
+                            acc[r * S + s] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                av, bv, acc[r * S + s], 0, 0, 0);
+                        }
+                }
+            }
+        }
+        wait_all_memory();
+        __syncthreads();
+    }
+
+    // ---- the second pixel group hands its sums to the first through LDS
+    // (all staged bands have been consumed: the last barrier is behind us)
+    f32x4 *xch = reinterpret_cast<f32x4 *>(lds) + (size_t)(wave & 3) * NTAPS * 4 * 64 + lane;
+    if (wave_p == 1) {
+#pragma unroll
+        for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const f32x4 v = {acc[t][4 * vq + 0], acc[t][4 * vq + 1], acc[t][4 * vq + 2],
+                                 acc[t][4 * vq + 3]};
+                xch[(t * 4 + vq) * 64] = v;
+            }
+    }
+    __syncthreads();
+    if (wave_p == 1) return;
+
+    // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
+    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    float *dst = a.partial + (size_t)split * copy;
+    const int k = kb0 * V + k_lane;
+#pragma unroll
+    for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const f32x4 o = xch[(t * 4 + vq) * 64];
+            const int c = cb0 * V + wave_c * 32 + vq * 8 + h * 4;
+            const int cb = c / V;
+            if (k >= a.Kp || cb >= a.Cb) continue;
+            const f32x4 v = {acc[t][4 * vq + 0] + o[0], acc[t][4 * vq + 1] + o[1],
+                             acc[t][4 * vq + 2] + o[2], acc[t][4 * vq + 3] + o[3]};
+            *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V) = v;
+        }
+}
+
+bool upd_f32_bands_exists(int r, int s) { return r == 3 && s == 3; }
+
+// LDS bytes the in-workgroup exchange of the two pixel groups needs
+size_t upd_f32_bands_exchange_bytes(int r, int s) { return (size_t)4 * r * s * 4 * 64 * 16; }
+
+hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+                                hipStream_t stream)
+{
+    typedef void (*fn_t)(const UpdArgs);
+    fn_t fn = nullptr;
+    const int odd = a.Q & 1;
+    if (r == 3 && s == 3) fn = odd ? upd_f32_bands_kernel<3, 3, true> : upd_f32_bands_kernel<3, 3, false>;
+    if (!fn) return hipErrorInvalidDeviceFunction;
+    static size_t attrs[2] = {0, 0};
+    size_t &attr = attrs[odd];
+    if (lds_bytes > attr) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        attr = lds_bytes;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convmi
