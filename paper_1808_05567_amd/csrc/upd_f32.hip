@@ -23,9 +23,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ODDQ: rows of an odd number of pixels
-template <int R, int S, bool ODDQ>
+template <int R, int S, bool ODDQ>  // unit stride
 __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
 {
+    static_assert(S == 3, "the register hand-over between pixel pairs assumes three filter columns");
     constexpr int V = 4;
     constexpr int NT = 512, NW = NT / 64;
     constexpr int NTAPS = R * S;
@@ -38,6 +39,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
     const int h = lane >> 5;
     const int l32 = lane & 31;
     const int wave_c = wave & 1;
@@ -95,23 +97,29 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
             const int oj = rho - n * a.P;
             return (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
         };
-        // the (position chunk, plane) pairs are dealt round-robin to the waves
-        int turn = wave;
-        for (int p0 = 0; p0 < cov_in; p0 += 64) {
-            const unsigned off = in_off(p0 + lane);
-            for (int pl = turn % NW; pl < NPI; pl += NW)
+        // The (64-position chunk, plane) loads, input band first, are shared out
+        // in equal contiguous runs: a wave computes the source offsets of one
+        // chunk (rarely two) and issues its planes.
+        const int nch_in = cov_in >> 6, nch_out = cov_out >> 6;
+        const int total = (nch_in + nch_out) * 16;  // NPI == NPO == 16
+        const int share = (total + NW - 1) / NW;
+        const int first = wave_u * share, last = min(total, first + share);
+        int cur = -1;
+        unsigned off = kOutOfRange;
+        for (int e = first; e < last; ++e) {
+            const int ch = e >> 4, pl = e & 15;
+            if (ch != cur) {
+                cur = ch;
+                off = ch < nch_in ? in_off(ch * 64 + lane) : out_off((ch - nch_in) * 64 + lane);
+            }
+            if (ch < nch_in)
                 load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
                                (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
-                               ib + (pl * a.PLS_in + p0) * 16);
-            turn += 3;
-        }
-        for (int p0 = 0; p0 < cov_out; p0 += 64) {
-            const unsigned off = out_off(p0 + lane);
-            for (int pl = turn % NW; pl < NPO; pl += NW)
+                               ib + (pl * a.PLS_in + ch * 64) * 16);
+            else
                 load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                                (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
-                               ob + (pl * a.PLS_out + p0) * 16);
-            turn += 3;
+                               ob + (pl * a.PLS_out + (ch - nch_in) * 64) * 16);
         }
     };
 
@@ -167,29 +175,62 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
                     }
             }
         } else {
-            // Even rows: pairs stay inside a row.  The groups alternate the pairs
-            // of each row if those are an even number, else the rows of the band.
-            const bool by_pairs = ((a.Q >> 1) & 1) == 0;
-            const int row_first = by_pairs ? 0 : wave_p, row_step = by_pairs ? 1 : 2;
-            const int col_first = h + (by_pairs ? 2 * wave_p : 0), col_step = by_pairs ? 4 : 2;
+            // Even rows: pairs stay inside a row.  Each group walks a contiguous
+            // run of pairs (half a row if the row has an even number of pairs,
+            // else alternate rows), so with unit stride the input value of the
+            // last filter column is the next pair's first-column value and is
+            // kept in a register; the other operands of the next pair are read
+            // before this pair's MFMAs issue.
+            const bool halves = ((a.Q >> 1) & 1) == 0;
+            const int row_first = halves ? 0 : wave_p, row_step = halves ? 1 : 2;
+            const int ncol = halves ? (a.Q >> 1) : a.Q;  // pixels of a row this group takes
+            const int col_first = halves ? wave_p * ncol : 0;
             for (int trow = row_first; trow < rows; trow += row_step) {
                 const int rho = rho0 + trow;
                 const int n = fast_div(rho, inv_P);
                 const int oj = rho - n * a.P;
-                const int irow = (n * a.Hs + oj * a.stride - lam0) * a.LW;
-                const int orow = trow * a.Q;
+                const float *pi = ldsI + a_lane + ((n * a.Hs + oj - lam0) * a.LW + col_first + h) * V;
+                const float *po = ldsO + b_lane + (trow * a.Q + col_first + h) * V;
+                float a0[R], an[R][S - 1], bn;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    a0[r] = pi[(r * a.LW) * V];
+#pragma unroll
+                    for (int s = 1; s < S; ++s) an[r][s - 1] = pi[(r * a.LW + s) * V];
+                }
+                bn = po[0];
 #pragma unroll 2
-                for (int col = col_first; col < a.Q; col += col_step) {
-                    const float bv = ldsO[b_lane + (orow + col) * V];
+                for (int c = 0; c < ncol; c += 2) {
+                    float av[R][S];
+                    const float bv = bn;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        av[r][0] = a0[r];
+#pragma unroll
+                        for (int s = 1; s < S; ++s) av[r][s] = an[r][s - 1];
+                        a0[r] = av[r][S - 1];  // column c+2 of this row's window (S == 3)
+                    }
+                    // next pair (clamped at the end of the run: a harmless re-read)
+                    const int cn = min(c + 2, ncol - 2);
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int s = 0; s < S; ++s) {
-                            const float av =
-                                ldsI[a_lane + (irow + r * a.LW + col * a.stride + s) * V];
+                        for (int s = 1; s < S; ++s) an[r][s - 1] = pi[(r * a.LW + cn + s) * V];
+                    bn = po[cn * V];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int s = 0; s < S; ++s)
                             acc[r * S + s] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                av, bv, acc[r * S + s], 0, 0, 0);
-                        }
+                                av[r][s], bv, acc[r * S + s], 0, 0, 0);
+                    // issue order: each of the next pair's reads behind an MFMA of this pair
+#pragma unroll
+                    for (int k = 0; k < R * S; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
