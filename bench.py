@@ -47,6 +47,10 @@ def parse():
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: turn two rocprofv3 --pmc counter_collection CSVs "
                          "(FETCH_SIZE, WRITE_SIZE) of a --calib-copy run into a traffic summary")
+    ap.add_argument("--lib-gemm", action="store_true",
+                    help="context only, no conv work: time the vendor library's plain GEMM "
+                         "(torch.matmul) at the GEMM shapes the layers' forward passes would have "
+                         "after an im2col expansion that is NOT timed")
     ap.add_argument("--out", default=None)
     return ap.parse_args()
 
@@ -159,8 +163,45 @@ def cpu_baseline(ids, n_cpu):
                       "(%.1f s of CPU time)" % (",".join(map(str, ids)), n_cpu, N_BATCH, secs)}
 
 
+def lib_gemm_context(args):
+    """The vendor BLAS on [K x C*R*S] . [C*R*S x N*P*Q] for each layer: what a GEMM library
+    reaches on this machine at the same sizes with the expanded matrix already in memory.  Context
+    for the MFMA fractions of the conv kernels; nothing here is part of the product path."""
+    import torch
+    from paper_1808_05567_amd import inputs
+    tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    torch.backends.cuda.matmul.allow_tf32 = False
+    peak = MFMA_PEAK[args.dtype]
+    shapes = [("L%d" % i, inputs.layer(i)) for i in (int(x) for x in args.layers.split(","))]
+    rows = [(nm, l.K, args.batch * l.P * l.Q, l.C * l.R * l.S) for nm, l in shapes]
+    rows.append(("8192^3", 8192, 8192, 8192))
+    for nm, M, N, K in rows:
+        a = torch.randn(M, K, device="cuda", dtype=tdt)
+        b = torch.randn(K, N, device="cuda", dtype=tdt)
+        for _ in range(5):
+            a @ b
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(20):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            a @ b
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in evs)[10]
+        tf = 2.0 * M * N * K / ms / 1e9
+        print("# lib gemm %-7s %s M=%d N=%d K=%d: %.3f ms %8.1f TF/s %5.1f%% of MFMA peak" % (
+            nm, args.dtype, M, N, K, ms, tf, 100 * tf / peak), file=sys.stderr)
+        del a, b
+
+
 def main():
     args = parse()
+    if args.lib_gemm:
+        lib_gemm_context(args)
+        return
     if args.summarize_pmc:
         summarize_pmc(args.summarize_pmc[0], args.summarize_pmc[1], args.out)
         return

@@ -78,7 +78,7 @@ int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
 // dynamic LDS at most `lds_cap` bytes.  Returns ok=false if nothing fits.
 IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap)
+                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap, int nb = 2)
 {
     IgemmPlan pl;
     const int V = vlen_of(dtype);
@@ -112,7 +112,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
         const int need = ceil_div(LR * LW, NT);
         ppt = -1;
         for (int cand = need; cand <= 16; ++cand) {
-            IgemmVariant v{dtype, wk, wm, fk, fm, npl, R, S, cand};
+            IgemmVariant v{dtype, wk, wm, fk, fm, npl, R, S, cand, nb};
             if (igemm_variant_exists(v)) {
                 ppt = cand;
                 break;
@@ -120,7 +120,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
         }
         // the plane pitch is a whole number of wave-level (64-lane) loads
         // (a single-step reduction never touches the second buffer)
-        const size_t nbuf = ceil_div(Cb, npl) > 1 ? 2 : 1;
+        const size_t nbuf = ceil_div(Cb, npl) > 1 ? (size_t)nb : 1;
         const size_t lds = nbuf * ((size_t)nent * TK * 16 + (size_t)npl * ceil_div(LR * LW, 64) * 64 * 16);
         if (ppt > 0 && lds <= lds_cap) break;
     }
@@ -140,8 +140,8 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.total = a.n_mt * a.n_qt * a.n_kt;
     a.per_xcd = ceil_div(a.total, 8);
     a.n_stage = ceil_div(Cb, npl);
-    pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt};
-    pl.lds = (a.n_stage > 1 ? 2 : 1) * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
+    pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt, nb};
+    pl.lds = (a.n_stage > 1 ? nb : 1) * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
     pl.grid = a.per_xcd * 8;
     // 32-bit index guards (offsets are kept in 16-byte units / elements)
     // tensors are addressed with 32-bit byte offsets
@@ -204,6 +204,14 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
                 best_cost = cost;
             }
         }
+    // bf16 1x1: a reduction step is two MFMA rounds, far shorter than a trip to memory; a
+    // third buffer keeps the loads two steps ahead where it fits the same LDS budget
+    if (dtype == CONV_BF16 && R * S == 1 && best.ok && best.a.n_stage >= 3) {
+        const size_t cap = best.lds <= (size_t)kMaxLds / 2 ? (size_t)kMaxLds / 2 : (size_t)kMaxLds;
+        IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr,
+                                oy0, ox0, zero_fill, best.v.wk, best.v.wm, best.v.fk, best.v.fm, cap, 3);
+        if (c.ok && c.a.total <= best.a.total) best = c;
+    }
     return best;
 }
 

@@ -61,6 +61,7 @@ struct IgemmVariant {
     int npl;     // reduction planes (channel blocks) staged per step
     int r, s;    // filter extent
     int ppt;     // staged input pixels per thread
+    int nb = 2;  // LDS buffers of the staging ring
 };
 
 hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes,

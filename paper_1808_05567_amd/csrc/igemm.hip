@@ -81,7 +81,8 @@ struct Elem<CONV_BF16> {
     }
 };
 
-template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT>
+// NB: LDS buffers of the staging ring (2 = double buffering; more = the loads run further ahead)
+template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT, int NB = 2>
 __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     constexpr int NLOADS = NPL * PPT + WPT;
     auto fetch_one = [&](int st, int l) {
         const int cb0 = st * NPL;
-        unsigned char *wb = lds + (st & 1) * bufbytes;
+        unsigned char *wb = lds + (st % NB) * bufbytes;
         unsigned char *ib = wb + WBYTES;
         if (l < NPL * PPT) {
             const int pl = l / PPT, i = l - pl * PPT;
@@ -240,11 +241,16 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
 #pragma unroll
             for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
 
+    // the first NB-1 steps' loads; step 0 must have landed before anyone reads it
     fetch(0);
+#pragma unroll
+    for (int d = 1; d < NB - 1; ++d)
+        if (d < a.n_stage) fetch(d);
     staged();
     __syncthreads();
 
     if constexpr (NPL == 1) {
+        static_assert(NB == 2, "the one-plane path is double buffered");
         // One channel block per step: the two lane halves take two taps.
         for (int st = 0; st < a.n_stage; ++st) {
             if (st + 1 < a.n_stage) fetch(st + 1);
@@ -295,16 +301,26 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             for (int j = 0; j < FM; ++j)
                 bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff);
         };
-        auto step = [&](int st, auto more_tag) {
-            constexpr bool MORE = decltype(more_tag)::value;
+        // With NB > 2 buffers the loads of step st+NB-1 issue during step st and a
+        // step waits only for the loads of the step that follows it: a wave's
+        // loads complete in order, so "all but the newest (NB-2)*NLOADS" is that.
+        // Near the end, when nothing further is issued, it waits for everything.
+        constexpr int AHEAD = NB - 1;
+        constexpr int LEAVE = (NB - 2) * NLOADS;
+        static_assert(LEAVE <= 63, "outstanding loads exceed the counter");
+        // s_waitcnt: vmcnt(LEAVE) lgkmcnt(0), export counter untouched
+        constexpr int WAIT_PARTIAL = (LEAVE & 15) | ((LEAVE >> 4) << 14) | (7 << 4) | (0 << 8);
+        auto step = [&](int st, auto more_tag, auto issue_tag) {
+            constexpr bool MORE = decltype(more_tag)::value;    // a step follows
+            constexpr bool ISSUE = decltype(issue_tag)::value;  // step st+AHEAD exists
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 u32x4 an[FK], bn[FM];
                 if (q + 1 < NQ)
-                    read_round(st & 1, q + 1, an, bn);
+                    read_round(st % NB, q + 1, an, bn);
                 else if (MORE)
-                    read_round((st + 1) & 1, 0, an, bn);
-                if (MORE && q == 0) fetch(st + 1);
+                    read_round((st + 1) % NB, 0, an, bn);
+                if (ISSUE && q == 0) fetch(st + AHEAD);
 #pragma unroll
                 for (int i = 0; i < FK; ++i)
 #pragma unroll
@@ -320,7 +336,10 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (MORE && q == NQ - 2) {
-                    staged();
+                    if (ISSUE && NB > 2)
+                        __builtin_amdgcn_s_waitcnt(WAIT_PARTIAL);
+                    else
+                        staged();
                     __syncthreads();
                 }
                 if (q + 1 < NQ || MORE) {
@@ -332,8 +351,10 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             }
         };
         read_round(0, 0, ac, bc);
-        for (int st = 0; st + 1 < a.n_stage; ++st) step(st, std::true_type{});
-        step(a.n_stage - 1, std::false_type{});
+        int st = 0;
+        for (; st + AHEAD < a.n_stage; ++st) step(st, std::true_type{}, std::true_type{});
+        for (; st + 1 < a.n_stage; ++st) step(st, std::true_type{}, std::false_type{});
+        step(st, std::false_type{}, std::false_type{});
     }
 
     // ---- epilogue: each lane owns, per fragment, one pixel and 4x4 channels.
@@ -396,11 +417,13 @@ struct IgemmEntry {
     size_t lds_attr;
 };
 
-#define IGEMM_ENTRY(DT, WK, WM, FK, FM, NPL, R, S, PPT)                         \
+#define IGEMM_ENTRY_NB(DT, WK, WM, FK, FM, NPL, R, S, PPT, NB)                  \
     {                                                                            \
-        {DT, WK, WM, FK, FM, NPL, R, S, PPT},                                    \
-            igemm_kernel<DT, WK, WM, FK, FM, NPL, R, S, PPT>, 0                  \
+        {DT, WK, WM, FK, FM, NPL, R, S, PPT, NB},                                \
+            igemm_kernel<DT, WK, WM, FK, FM, NPL, R, S, PPT, NB>, 0              \
     }
+#define IGEMM_ENTRY(DT, WK, WM, FK, FM, NPL, R, S, PPT) \
+    IGEMM_ENTRY_NB(DT, WK, WM, FK, FM, NPL, R, S, PPT, 2)
 
 static IgemmEntry g_igemm[] = {
     // fp32
@@ -434,6 +457,9 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 3),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 4),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 4, 1, 1, 2),
+    // bf16 1x1: a step is only two MFMA rounds, so the loads run two steps ahead
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),
 };
 
 static IgemmEntry *find_igemm(const IgemmVariant &v)
@@ -441,7 +467,7 @@ static IgemmEntry *find_igemm(const IgemmVariant &v)
     for (auto &e : g_igemm) {
         const IgemmVariant &w = e.v;
         if (w.dtype == v.dtype && w.wk == v.wk && w.wm == v.wm && w.fk == v.fk && w.fm == v.fm &&
-            w.npl == v.npl && w.r == v.r && w.s == v.s && w.ppt == v.ppt)
+            w.npl == v.npl && w.r == v.r && w.s == v.s && w.ppt == v.ppt && w.nb == v.nb)
             return &e;
     }
     return nullptr;
