@@ -72,6 +72,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
     const int h = lane >> 5;
     const int l32 = lane & 31;
     const int grp = (lane >> 4) & 1;
@@ -157,28 +158,24 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
             load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                            (unsigned)(kb0 + pl) * (unsigned)PQ * 16u, ob + (pl * a.PLS_out + p0) * 16);
         };
-        if (cov_in >= 3 * 64) {
-            // several position chunks: a wave takes whole chunks, all planes
-            for (int p0 = wave * 64; p0 < cov_in; p0 += NT) {
-                const unsigned off = in_off(p0 + lane);
+        // Unit of staging work: one 64-position chunk x 8 planes (8 wave-level
+        // loads behind one offset computation).  Input units go to the waves in
+        // ascending order, dO units in descending order, so that a band's units
+        // spread over all waves instead of piling up on the first ones.
+        static_assert(NPI % 8 == 0 && NPO % 8 == 0, "plane groups of 8");
+        constexpr int GI = NPI / 8, GO = NPO / 8;
+        const int nu_in = (cov_in >> 6) * GI, nu_out = (cov_out >> 6) * GO;
+        for (int u = wave_u; u < nu_in; u += NW) {
+            const int ch = u / GI, g = u - ch * GI;
+            const unsigned off = in_off(ch * 64 + lane);
 #pragma unroll
-                for (int pl = 0; pl < NPI; ++pl) load_in(pl, p0, off);
-            }
-            for (int p0 = wave * 64; p0 < cov_out; p0 += NT) {
-                const unsigned off = out_off(p0 + lane);
+            for (int pl = 0; pl < 8; ++pl) load_in(g * 8 + pl, ch * 64, off);
+        }
+        for (int u = NW - 1 - wave_u; u < nu_out; u += NW) {
+            const int ch = u / GO, g = u - ch * GO;
+            const unsigned off = out_off(ch * 64 + lane);
 #pragma unroll
-                for (int pl = 0; pl < NPO; ++pl) load_out(pl, p0, off);
-            }
-        } else {
-            // few chunks (1x1 layers): the planes of a chunk are dealt round-robin to the waves
-            for (int p0 = 0, c = 0; p0 < cov_in; p0 += 64, ++c) {
-                const unsigned off = in_off(p0 + lane);
-                for (int pl = (wave + c) % NW; pl < NPI; pl += NW) load_in(pl, p0, off);
-            }
-            for (int p0 = 0, c = 0; p0 < cov_out; p0 += 64, ++c) {
-                const unsigned off = out_off(p0 + lane);
-                for (int pl = (wave + c) % NW; pl < NPO; pl += NW) load_out(pl, p0, off);
-            }
+            for (int pl = 0; pl < 8; ++pl) load_out(g * 8 + pl, ch * 64, off);
         }
     };
 
