@@ -78,6 +78,21 @@ def test_few_channel_layers_match_oracle(shape):
         L.close()
 
 
+@pytest.mark.parametrize("shape", [FEW_CHANNELS[0], (3, 3, 48, 21, 19, 7, 7, 2, 3)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_first_layer_backward_bf16(shape):
+    """bf16 backward by data of the strided first layer: all stride-parity classes in one
+    launch, 8 channel slots per class, interleaving store (odd extents drop the last cell row)."""
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, conv.CONV_BF16, layer_id=1)
+    L = _layer(shape, conv.CONV_BF16)
+    try:
+        assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[conv.CONV_BF16]
+    finally:
+        L.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", [(3, 32, 48, 14, 14, 3, 3, 1, 1), (2, 64, 32, 12, 12, 1, 1, 2, 0)],
                          ids=["3x3", "1x1s2"])
