@@ -314,14 +314,23 @@ void plan_bwd(conv_plan *p)
             // With no tap in the class the sub-filter is all zero and the
             // launch writes zeros, which is what Algorithm 6 leaves there.
             const int Re = std::max(Rsub, 1), Se = std::max(Ssub, 1);
-            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, Hsub, Wsub, R2, S2, 1,
+            // the class's own sub-filter extent where a kernel exists for it, else
+            // the common extent with zero taps
+            int R2c = Re, S2c = Se;
+            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, Hsub, Wsub, R2c, S2c, 1,
                              Re - 1 - dy0, Se - 1 - dx0, d.H, d.W, st, py, px, 0);
+            if (!b.p.ok) {
+                R2c = R2;
+                S2c = S2;
+                b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, Hsub, Wsub, R2c, S2c, 1,
+                                 Re - 1 - dy0, Se - 1 - dx0, d.H, d.W, st, py, px, 0);
+            }
             if (!b.p.ok) return;
-            b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, d.R, d.S, R2, S2,
+            b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, d.R, d.S, R2c, S2c,
                               st, ry, rx, Rsub, Ssub};
             if (Rsub == 0 || Ssub == 0) { b.x.Rsub = 0; b.x.Ssub = 0; }
             b.ws_off = off;
-            off += (size_t)f.Kb * R2 * S2 * f.Cp * f.vlen * es;
+            off += (size_t)f.Kb * R2c * S2c * f.Cp * f.vlen * es;
             ++n;
         }
     p->bwd_mode = 2;

@@ -457,6 +457,19 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 3),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 3, 3, 4),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 4, 1, 1, 2),
+    // 2x2, 1x2, 2x1: the stride-2 residue classes of a 3x3 backward pass
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 2, 2, 3),
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 2, 2, 2),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 1, 2, 3),
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 1, 2, 2),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 2, 1, 3),
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 2, 1, 2),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 2, 2, 3),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 2, 2, 3),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 1, 2, 3),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 1, 2, 3),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 2, 1, 3),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 2, 1, 3),
     // bf16 1x1: a step is only two MFMA rounds, so the loads run two steps ahead
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),

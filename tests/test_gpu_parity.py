@@ -28,6 +28,9 @@ SMALL = [
     (3, 256, 128, 16, 16, 1, 1, 2, 0),
     (2, 4, 8, 8, 8, 1, 1, 1, 0),          # a single channel block
     (1, 16, 16, 5, 5, 3, 3, 1, 1),        # one tiny image (inference shape)
+    (9, 72, 80, 7, 9, 3, 3, 1, 1),        # odd width, ragged channel tiles both ways, many bands
+    (2, 64, 64, 14, 14, 3, 3, 2, 1),      # 3x3 stride 2: backward = four residue-class launches
+    (3, 32, 48, 15, 13, 3, 3, 2, 1),      # ... odd extents: classes of different sizes
 ]
 
 
