@@ -95,7 +95,10 @@ const char *conv_status_str(conv_status_t s);
 
 /* Algorithm 1 with padding:  out[n,k,oj,oi] = sum_{c,r,s} in[n,c,ij,ii] * wt[k,c,r,s].
  * in: blocked I; wt: blocked W; out: blocked O (fully overwritten, padded
- * channel slots written as zero).  ws unused (may be NULL). */
+ * channel slots written as zero).  ws: workspace_bytes of scratch; read only by
+ * plans that split the reduction over workgroups (few output tiles, e.g. N = 1:
+ * fp32 partial results summed in a fixed order), CONV_EWORKSPACE if such a plan
+ * gets NULL; other plans ignore it. */
 conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out,
                        void *ws, void *stream);
 

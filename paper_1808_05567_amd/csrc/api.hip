@@ -35,6 +35,7 @@ struct conv_plan {
     conv_desc_t d;
     conv_info_t info;
     IgemmPlan fwd;
+    size_t fwd_ws = 0;  // bytes of fp32 partial results if the forward reduction is split
     // backward by data
     int bwd_mode = 0;  // 0 unsupported, 1 one launch (duality), 2 parity classes
     int n_bwd = 0;
@@ -131,6 +132,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.stride = stride; a.pad_h = pad_h; a.pad_w = pad_w;
     a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
     a.shuffle = 0; a.out_kb = Kp / V;
+    a.ksplit = 1;
     a.TR = TR; a.TQ = TQ;
     a.n_qt = ceil_div(Q, TQ);
     a.n_mt = ceil_div(N * P, TR);
@@ -140,6 +142,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.total = a.n_mt * a.n_qt * a.n_kt;
     a.per_xcd = ceil_div(a.total, 8);
     a.n_stage = ceil_div(Cb, npl);
+    a.st_per = a.n_stage;
     pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt, nb};
     pl.lds = (a.n_stage > 1 ? nb : 1) * ((size_t)nent * TK * 16 + (size_t)npl * a.PLS * 16);
     pl.grid = a.per_xcd * 8;
@@ -643,10 +646,24 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
 
     p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, d.pad,
                         d.pad, f.P, f.Q, 1, 0, 0, 0);
+    // Few tiles and a long reduction (small minibatch, inference): split the reduction
+    // over more workgroups, fp32 partial results in the workspace, summed in a fixed order.
+    p->fwd_ws = 0;
+    if (p->fwd.ok && p->fwd.a.total <= 128 && p->fwd.a.n_stage >= 4) {
+        IgemmArgs &a = p->fwd.a;
+        const int want = std::min(a.n_stage / 2, std::max(1, 512 / a.total));
+        if (want >= 2) {
+            a.st_per = ceil_div(a.n_stage, want);
+            a.ksplit = ceil_div(a.n_stage, a.st_per);
+            a.per_xcd = ceil_div(a.total * a.ksplit, 8);
+            p->fwd.grid = a.per_xcd * 8;
+            p->fwd_ws = (size_t)a.ksplit * d.N * f.Kp * f.P * f.Q * sizeof(float);
+        }
+    }
     plan_bwd(p);
     plan_upd(p);
     f.upd_splits = p->upd_ok ? p->upd_copies : 0;
-    f.workspace_bytes = std::max(p->bwd_ws, p->upd_ws);
+    f.workspace_bytes = std::max(std::max(p->bwd_ws, p->upd_ws), p->fwd_ws);
     *out = p;
     return CONV_OK;
 }
@@ -668,15 +685,20 @@ conv_status_t conv_query(conv_handle_t h, conv_info_t *info)
 conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
                        void *stream)
 {
-    (void)ws;
     if (!h || !in || !wt || !out) return CONV_EINVAL;
-    if (!aligned16(in) || !aligned16(wt) || !aligned16(out)) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws)) return CONV_EINVAL;
     if (!h->fwd.ok) return CONV_EUNSUPPORTED;
     IgemmArgs a = h->fwd.a;
+    const bool split = a.ksplit > 1;
+    if (split && !ws) return CONV_EWORKSPACE;
     a.in = in;
     a.wt = wt;
-    a.out = out;
+    a.out = split ? ws : out;
     hipError_t e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
+    if (e == hipSuccess && split)
+        e = launch_split_reduce(h->d.dtype, static_cast<const float *>(ws), out,
+                                (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit,
+                                (hipStream_t)stream);
     return e == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }
 
@@ -798,10 +820,10 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         if (!p->ok) return CONV_EUNSUPPORTED;
         snprintf(buf, buflen,
                  "igemm dt=%d waves=%dx%d frags=%dx%d npl=%d RS=%dx%d ppt=%d TR=%d TQ=%d tiles=%d "
-                 "(m=%d q=%d k=%d) grid=%d lds=%zu stages=%d launches=%d",
+                 "(m=%d q=%d k=%d) grid=%d lds=%zu stages=%d ksplit=%d launches=%d",
                  p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.r, p->v.s, p->v.ppt,
                  p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->grid, p->lds,
-                 p->a.n_stage, pass == 0 ? 1 : h->n_bwd);
+                 p->a.n_stage, p->a.ksplit, pass == 0 ? 1 : h->n_bwd);
         return CONV_OK;
     }
     if (pass == 2) {

@@ -51,6 +51,11 @@ struct IgemmArgs {
     int total;     // workgroups doing work
     int per_xcd;   // ceil(total / 8)
     int n_stage;   // ceil(Cb / planes per stage)
+    // Reduction split (few tiles, long reduction): workgroup lin covers tile
+    // lin % total and reduction steps [sp*st_per, (sp+1)*st_per), sp = lin / total,
+    // and writes an fp32 partial result, copy sp, for split_reduce to sum.
+    int ksplit;    // number of splits (1: none, the result is written directly)
+    int st_per;    // reduction steps per split
 };
 
 // Key of a kernel instantiation; the host picks one per pass at plan time.
@@ -67,6 +72,9 @@ struct IgemmVariant {
 hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes,
                         int grid, hipStream_t stream);
 bool igemm_variant_exists(const IgemmVariant &v);
+// out[e] = sum over copies j (ascending) of partial[j][e], converted to the tensor's type
+hipError_t launch_split_reduce(int dtype, const float *partial, void *out, size_t n_elems, int copies,
+                               hipStream_t stream);
 
 // Weight transform for backward by data:  dst[kb][r'][s'][c][k%v] (tap-flipped,
 // channel roles swapped, optionally a stride-decimated sub-filter).

@@ -112,9 +112,13 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     // over the 8 XCDs; give every XCD a contiguous run of tiles.
     const int bid = blockIdx.x;
     const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
-    if (lin >= a.total) return;
-    const int kt = lin % a.n_kt;
-    const int rest = lin / a.n_kt;
+    if (lin >= a.total * a.ksplit) return;
+    const int sp = lin / a.total;  // reduction split this workgroup serves
+    const int tile = lin - sp * a.total;
+    const int sbeg = sp * a.st_per;                  // its first reduction step ...
+    const int nst = min(a.n_stage - sbeg, a.st_per);  // ... and how many (at least one)
+    const int kt = tile % a.n_kt;
+    const int rest = tile / a.n_kt;
     const int qt = rest % a.n_qt;
     const int mt = rest / a.n_qt;
     const int k0 = kt * TK;
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     // Load number l of a step: the input loads (plane-major) come first, then the weights.
     constexpr int NLOADS = NPL * PPT + WPT;
     auto fetch_one = [&](int st, int l) {
-        const int cb0 = st * NPL;
+        const int cb0 = (sbeg + st) * NPL;
         unsigned char *wb = lds + (st % NB) * bufbytes;
         unsigned char *ib = wb + WBYTES;
         if (l < NPL * PPT) {
@@ -245,15 +249,15 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     fetch(0);
 #pragma unroll
     for (int d = 1; d < NB - 1; ++d)
-        if (d < a.n_stage) fetch(d);
+        if (d < nst) fetch(d);
     staged();
     __syncthreads();
 
     if constexpr (NPL == 1) {
         static_assert(NB == 2, "the one-plane path is double buffered");
         // One channel block per step: the two lane halves take two taps.
-        for (int st = 0; st < a.n_stage; ++st) {
-            if (st + 1 < a.n_stage) fetch(st + 1);
+        for (int st = 0; st < nst; ++st) {
+            if (st + 1 < nst) fetch(st + 1);
             const unsigned char *wb = lds + (st & 1) * bufbytes;
             const unsigned char *ib = wb + WBYTES;
 #pragma unroll 1
@@ -352,8 +356,8 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         };
         read_round(0, 0, ac, bc);
         int st = 0;
-        for (; st + AHEAD < a.n_stage; ++st) step(st, std::true_type{}, std::true_type{});
-        for (; st + 1 < a.n_stage; ++st) step(st, std::true_type{}, std::false_type{});
+        for (; st + AHEAD < nst; ++st) step(st, std::true_type{}, std::true_type{});
+        for (; st + 1 < nst; ++st) step(st, std::true_type{}, std::false_type{});
         step(st, std::false_type{}, std::false_type{});
     }
 
@@ -362,6 +366,31 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     // offset; the per-lane offset is the pixel's.
     const size_t oplane = (size_t)a.OH * a.OW * 16;
     const size_t out_bytes = (size_t)a.N * Kb_out * oplane;
+    if (a.ksplit > 1) {
+        // partial result of this reduction split: fp32, the output tensor's element
+        // order (so for bf16 every byte offset doubles), copy sp
+        constexpr unsigned SC = (V == 8) ? 2u : 1u;
+        const rsrc_t rp = make_rsrc(static_cast<char *>(a.out) + (size_t)sp * out_bytes * SC, 0,
+                                    out_bytes * SC);
+#pragma unroll
+        for (int i = 0; i < FK; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;
+                if (krow0 >= a.Kp) continue;
+                const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
+                const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
+#pragma unroll
+                for (int j = 0; j < FM; ++j) {
+                    const bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
+                    Elem<CONV_F32>::store4(rp, live ? (obyte[j] + lane_off) * SC : kOutOfRange, skip * SC,
+                                           acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
+                                           acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
+                }
+            }
+        }
+        return;
+    }
     const rsrc_t ro = make_rsrc(a.out, 0, out_bytes);
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
@@ -487,6 +516,46 @@ static IgemmEntry *find_igemm(const IgemmVariant &v)
 }
 
 bool igemm_variant_exists(const IgemmVariant &v) { return find_igemm(v) != nullptr; }
+
+// Sum of the fp32 partial results of a split reduction, copies ascending (a fixed
+// order: reproducible), written in the tensor's type.  One thread per 4 elements.
+template <bool BF16>
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ partial,
+                                                           void *__restrict__ out, size_t n4, int copies)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n4) return;
+    const f32x4 *p = reinterpret_cast<const f32x4 *>(partial);
+    f32x4 s = p[idx];
+    for (int j = 1; j < copies; ++j) {
+        const f32x4 v = p[(size_t)j * n4 + idx];
+        s[0] += v[0];
+        s[1] += v[1];
+        s[2] += v[2];
+        s[3] += v[3];
+    }
+    if (BF16) {
+        u32x2 o = {pack_bf16x2(s[0], s[1]), pack_bf16x2(s[2], s[3])};
+        reinterpret_cast<u32x2 *>(out)[idx] = o;
+    } else {
+        reinterpret_cast<f32x4 *>(out)[idx] = s;
+    }
+}
+
+hipError_t launch_split_reduce(int dtype, const float *partial, void *out, size_t n_elems, int copies,
+                               hipStream_t stream)
+{
+    const size_t n4 = n_elems / 4;
+    const unsigned grid = (unsigned)((n4 + 255) / 256);
+    if (dtype == CONV_BF16)
+        hipLaunchKernelGGL(split_reduce_kernel<true>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
+                           copies);
+    else
+        hipLaunchKernelGGL(split_reduce_kernel<false>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
+                           copies);
+    return hipGetLastError();
+}
 
 hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes, int grid,
                         hipStream_t stream)
