@@ -306,8 +306,31 @@ def main():
                              "pct_mfma_peak": round(100 * tf / peak, 1),
                              "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
                              "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
-        # layout conversion, timed on its own (the passes work on resident blocked tensors)
         from paper_1808_05567_amd import conv as _conv
+        # forward pass with bias + residual + ReLU fused into its store, timed on its own
+        # (dy_blk, a tensor of the output's shape, stands in for the residual)
+        for l, L in layers:
+            bias = torch.zeros(L.info.Kp, dtype=torch.float32, device="cuda")
+            kw = dict(bias=bias, residual=L.dy_blk, relu=True, ws=L.ws)
+            _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+            evs = []
+            for _ in range(args.steps):
+                a0 = torch.cuda.Event(enable_timing=True)
+                a1 = torch.cuda.Event(enable_timing=True)
+                a0.record()
+                _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+                a1.record()
+                evs.append((a0, a1))
+            torch.cuda.synchronize()
+            ms = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
+            tf = l.flops(N) / (ms * 1e-3) / 1e12
+            by = algorithmic_bytes(l, N, es, "fwd") + N * l.K * l.P * l.Q * es
+            ceil = min(peak, l.flops(N) / by * HBM_PEAK)
+            rows.append({"layer": l.id, "pass": "fwd_fused", "ms": round(ms, 4), "tflops": round(tf, 2),
+                         "pct_mfma_peak": round(100 * tf / peak, 1),
+                         "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
+                         "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
+        # layout conversion, timed on its own (the passes work on resident blocked tensors)
         for l, L in layers:
             nchw = torch.empty((N, l.C, l.H, l.W), dtype=L.tdtype, device="cuda")
             nkpq = torch.empty((N, l.K, l.P, l.Q), dtype=L.tdtype, device="cuda")

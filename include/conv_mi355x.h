@@ -102,6 +102,21 @@ const char *conv_status_str(conv_status_t s);
 conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out,
                        void *ws, void *stream);
 
+/* Forward pass with fused operators (Section II-G, Algorithm 4: APPLY(L(), O
+ * sub-tensor) once the sub-tensor's reduction is complete -- here while it is
+ * still in registers):
+ *     out[n,k,oj,oi] = L( conv[n,k,oj,oi] + bias[k] + residual[n,k,oj,oi] )
+ * with L(x) = max(x, 0) if relu != 0, else the identity; the sum and L are
+ * evaluated in fp32 before the one rounding to the output type.
+ * bias: device, fp32, Kp entries (entries of padded channels must be 0), or NULL.
+ * residual: device, blocked O layout and the tensors' dtype, or NULL; it may
+ * alias out (each element is read before it is written, by the same lane).
+ * Everything else as conv_fwd; with bias == residual == NULL and relu == 0 the
+ * two calls give identical results. */
+conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, void *out,
+                             const float *bias, const void *residual, int32_t relu, void *ws,
+                             void *stream);
+
 /* Algorithm 6 with padding:  din[n,c,ij,ii] = sum_{k,r,s} dout[n,k,oj,oi] * wt[k,c,r,s]
  * over all (oj,r), (oi,s) that map to (ij,ii); positions no term maps to are 0.
  * dout: blocked dO; wt: blocked W (the same buffer conv_fwd takes); din: blocked

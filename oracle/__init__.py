@@ -96,6 +96,23 @@ def fwd(I, Wt, stride=1, pad=0):
     return O
 
 
+def fwd_fused(I, Wt, stride=1, pad=0, bias=None, residual=None, relu=False):
+    """Algorithm 4 (Section II-G) with L() = bias add, residual add, ReLU, applied to each
+    output element once its reduction is complete:
+        O = L(conv(I, Wt) + bias[k] + residual[n,k,oj,oi]),  L = max(., 0) if relu.
+    Written out with numpy on top of ``fwd``; all in float64."""
+    O = fwd(I, Wt, stride, pad)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        for k in range(O.shape[1]):
+            O[:, k, :, :] += b[k]
+    if residual is not None:
+        O = O + np.asarray(residual, dtype=np.float64)
+    if relu:
+        O = np.where(O > 0.0, O, 0.0)
+    return O
+
+
 def bwd_data(dO, Wt, H, W, stride=1, pad=0):
     """Algorithm 6.  dO[N,K,P,Q], Wt[K,C,R,S] -> dI[N,C,H,W]."""
     N, K, P, Q = dO.shape

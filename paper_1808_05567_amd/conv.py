@@ -20,7 +20,7 @@ CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5
 
 EXPORTS = (
     "conv_create", "conv_destroy", "conv_query", "conv_status_str",
-    "conv_fwd", "conv_bwd_data", "conv_upd",
+    "conv_fwd", "conv_fwd_fused", "conv_bwd_data", "conv_upd",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
@@ -73,6 +73,7 @@ def load():
     lib.conv_status_str.restype = ctypes.c_char_p
     for name in ("conv_fwd", "conv_bwd_data", "conv_upd"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.conv_fwd_fused.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
     for name in ("conv_pack_in", "conv_pack_out", "conv_pack_wt", "conv_unpack_in",
                  "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp]
@@ -136,6 +137,11 @@ def conv_describe(h, which: int) -> str:
 
 def conv_fwd(h, inp, wt, out, ws=None, stream=None):
     _check(load().conv_fwd(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(ws), _stream(stream)), "conv_fwd")
+
+
+def conv_fwd_fused(h, inp, wt, out, bias=None, residual=None, relu=False, ws=None, stream=None):
+    _check(load().conv_fwd_fused(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(bias), _ptr(residual),
+                                 1 if relu else 0, _ptr(ws), _stream(stream)), "conv_fwd_fused")
 
 
 def conv_bwd_data(h, dout, wt, din, ws, stream=None):
@@ -224,6 +230,10 @@ class ConvLayer:
     # -- passes on the blocked buffers
     def fwd(self):
         conv_fwd(self.h, self.in_blk, self.wt_blk, self.out_blk, self.ws)
+
+    def fwd_fused(self, bias=None, residual=None, relu=False):
+        """bias: fp32 device tensor of Kp entries; residual: blocked tensor like out_blk."""
+        conv_fwd_fused(self.h, self.in_blk, self.wt_blk, self.out_blk, bias, residual, relu, self.ws)
 
     def bwd_data(self):
         conv_bwd_data(self.h, self.out_blk, self.wt_blk, self.in_blk, self.ws)

@@ -133,6 +133,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
     a.shuffle = 0; a.out_kb = Kp / V;
     a.ksplit = 1;
+    a.bias = nullptr; a.resid = nullptr; a.relu = 0;
     a.TR = TR; a.TQ = TQ;
     a.n_qt = ceil_div(Q, TQ);
     a.n_mt = ceil_div(N * P, TR);
@@ -682,11 +683,14 @@ conv_status_t conv_query(conv_handle_t h, conv_info_t *info)
     return CONV_OK;
 }
 
-conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
-                       void *stream)
+conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, void *out,
+                             const float *bias, const void *residual, int32_t relu, void *ws,
+                             void *stream)
 {
     if (!h || !in || !wt || !out) return CONV_EINVAL;
-    if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws)) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws) || !aligned16(bias) ||
+        !aligned16(residual))
+        return CONV_EINVAL;
     if (!h->fwd.ok) return CONV_EUNSUPPORTED;
     IgemmArgs a = h->fwd.a;
     const bool split = a.ksplit > 1;
@@ -694,12 +698,23 @@ conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *ou
     a.in = in;
     a.wt = wt;
     a.out = split ? ws : out;
+    // a split reduction applies the operators where the partial results are summed
+    a.bias = split ? nullptr : bias;
+    a.resid = split ? nullptr : residual;
+    a.relu = split ? 0 : (relu != 0);
     hipError_t e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
     if (e == hipSuccess && split)
         e = launch_split_reduce(h->d.dtype, static_cast<const float *>(ws), out,
-                                (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit,
+                                (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit, bias,
+                                residual, relu != 0, h->info.P * h->info.Q, h->info.Kb,
                                 (hipStream_t)stream);
     return e == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
+                       void *stream)
+{
+    return conv_fwd_fused(h, in, wt, out, nullptr, nullptr, 0, ws, stream);
 }
 
 conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, void *din, void *ws,

@@ -30,6 +30,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
 struct Elem;
@@ -46,6 +47,14 @@ struct Elem<CONV_F32> {
         for (int t = 0; t < 4; ++t)
             c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[t]), __uint_as_float(b[t]),
                                                      c, 0, 0, 0);
+    }
+    // Load 4 consecutive channels of one pixel (zeros if byte_off is out of range).
+    static __device__ __forceinline__ void load4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
+                                                 float (&x)[4])
+    {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, uniform_off, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) x[t] = __uint_as_float(v[t]);
     }
     // Store 4 consecutive channels of one pixel (dropped if byte_off is out of range).
     static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
@@ -72,6 +81,15 @@ struct Elem<CONV_BF16> {
     {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                     __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void load4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
+                                                 float (&x)[4])
+    {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, uniform_off, 0);
+        x[0] = __uint_as_float(v[0] << 16);
+        x[1] = __uint_as_float(v[0] & 0xFFFF0000u);
+        x[2] = __uint_as_float(v[1] << 16);
+        x[3] = __uint_as_float(v[1] & 0xFFFF0000u);
     }
     static __device__ __forceinline__ void store4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
                                                   float x0, float x1, float x2, float x3)
@@ -392,6 +410,54 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         return;
     }
     const rsrc_t ro = make_rsrc(a.out, 0, out_bytes);
+    if (a.bias != nullptr || a.resid != nullptr || a.relu != 0) {
+        // L() of Algorithm 4 on the finished accumulators: bias, residual, ReLU (forward
+        // pass: plain store geometry).  The residual values of a row group are all
+        // requested before the first of them is used, and before any store of the group
+        // (the residual may be the output buffer itself).
+        const rsrc_t rres = make_rsrc(a.resid ? a.resid : a.out, 0, out_bytes);
+#pragma unroll
+        for (int i = 0; i < FK; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
+                if (krow0 >= a.Kp) continue;                            // wave-uniform
+                const bool rows_live = krow0 + 4 * h < a.Kp;
+                float b4[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a.bias && rows_live) {
+                    const f32x4 b = *reinterpret_cast<const f32x4 *>(a.bias + krow0 + 4 * h);
+                    b4[0] = b[0]; b4[1] = b[1]; b4[2] = b[2]; b4[3] = b[3];
+                }
+                const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
+                const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
+                float r4[FM][4];
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) r4[j][t] = 0.0f;
+                if (a.resid) {
+#pragma unroll
+                    for (int j = 0; j < FM; ++j) {
+                        const bool live = obyte[j] != kOutOfRange && rows_live;
+                        E_::load4(rres, live ? obyte[j] + lane_off : kOutOfRange, skip, r4[j]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < FM; ++j) {
+                    const bool live = obyte[j] != kOutOfRange && rows_live;
+                    float o4[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        o4[t] = acc[i][j][4 * vq + t] + r4[j][t] + b4[t];
+                        if (a.relu) o4[t] = fmaxf(o4[t], 0.0f);
+                    }
+                    E_::store4(ro, live ? obyte[j] + lane_off : kOutOfRange, skip, o4[0], o4[1], o4[2],
+                               o4[3]);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
 #pragma unroll
@@ -521,9 +587,11 @@ bool igemm_variant_exists(const IgemmVariant &v) { return find_igemm(v) != nullp
 // order: reproducible), written in the tensor's type.  One thread per 4 elements.
 template <bool BF16>
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ partial,
-                                                           void *__restrict__ out, size_t n4, int copies)
+                                                           void *out, size_t n4, int copies,
+                                                           const float *__restrict__ bias,
+                                                           const void *resid, int relu, int pq, int kb)
 {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int V = BF16 ? 8 : 4;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= n4) return;
     const f32x4 *p = reinterpret_cast<const f32x4 *>(partial);
@@ -535,6 +603,29 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
         s[2] += v[2];
         s[3] += v[3];
     }
+    if (resid) {
+        if (BF16) {
+            const u32x2 r = reinterpret_cast<const u32x2 *>(resid)[idx];
+            s[0] += __uint_as_float(r[0] << 16);
+            s[1] += __uint_as_float(r[0] & 0xFFFF0000u);
+            s[2] += __uint_as_float(r[1] << 16);
+            s[3] += __uint_as_float(r[1] & 0xFFFF0000u);
+        } else {
+            const f32x4 r = reinterpret_cast<const f32x4 *>(resid)[idx];
+            s[0] += r[0]; s[1] += r[1]; s[2] += r[2]; s[3] += r[3];
+        }
+    }
+    if (bias) {
+        // element e of [n][kb][pixel][V]: channel = block * V + e % V
+        const size_t e = idx * 4;
+        const int blk = (int)((e / ((size_t)pq * V)) % (size_t)kb);
+        const f32x4 b = *reinterpret_cast<const f32x4 *>(bias + blk * V + (int)(e % V));
+        s[0] += b[0]; s[1] += b[1]; s[2] += b[2]; s[3] += b[3];
+    }
+    if (relu) {
+        s[0] = fmaxf(s[0], 0.f); s[1] = fmaxf(s[1], 0.f);
+        s[2] = fmaxf(s[2], 0.f); s[3] = fmaxf(s[3], 0.f);
+    }
     if (BF16) {
         u32x2 o = {pack_bf16x2(s[0], s[1]), pack_bf16x2(s[2], s[3])};
         reinterpret_cast<u32x2 *>(out)[idx] = o;
@@ -544,16 +635,17 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
 }
 
 hipError_t launch_split_reduce(int dtype, const float *partial, void *out, size_t n_elems, int copies,
+                               const float *bias, const void *resid, int relu, int pq, int kb,
                                hipStream_t stream)
 {
     const size_t n4 = n_elems / 4;
     const unsigned grid = (unsigned)((n4 + 255) / 256);
     if (dtype == CONV_BF16)
         hipLaunchKernelGGL(split_reduce_kernel<true>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
-                           copies);
+                           copies, bias, resid, relu, pq, kb);
     else
         hipLaunchKernelGGL(split_reduce_kernel<false>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
-                           copies);
+                           copies, bias, resid, relu, pq, kb);
     return hipGetLastError();
 }
 

@@ -158,3 +158,57 @@ def test_upd_is_bitwise_deterministic():
         assert L.info.upd_splits > 1
     finally:
         L.close()
+
+
+FUSED = [
+    (2, 64, 64, 14, 14, 3, 3, 1, 1),      # reduction split over workgroups: operators in the reduce
+    (5, 128, 128, 28, 28, 3, 3, 1, 1),    # many tiles: operators in the convolution's store
+    (3, 64, 256, 56, 56, 1, 1, 1, 0),
+    (2, 20, 24, 8, 8, 3, 3, 1, 1),        # padded channel slots stay zero
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", FUSED, ids=lambda s: "x".join(map(str, s)))
+def test_fused_forward_matches_oracle(shape, dtype):
+    """Section II-G / Algorithm 4: bias, residual and ReLU applied before the result is stored."""
+    import torch
+    from paper_1808_05567_amd import inputs
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=7)
+    P, Q = oracle.out_hw(H, W, R, S, stride, pad)
+    rng = np.random.default_rng(5)
+    bias = rng.standard_normal(K).astype(np.float32)
+    res = rng.uniform(-1, 1, size=(N, K, P, Q)).astype(np.float32)
+    if dtype == conv.CONV_BF16:
+        res = inputs.round_to_bf16(res)
+    L = _layer(shape, dtype)
+    try:
+        info = conv.conv_query(L.h)
+        bias_dev = torch.zeros(info.Kp, dtype=torch.float32, device="cuda")
+        bias_dev[:K] = torch.from_numpy(bias)
+        L.set_outgrad(res)                 # blocked tensor of the output's shape ...
+        res_blk = L.out_blk.clone()        # ... used as the residual
+        L.set_input(I)
+        L.set_weights(Wt)
+        for kw in (dict(bias=bias_dev), dict(residual=res_blk, relu=True),
+                   dict(bias=bias_dev, residual=res_blk, relu=True)):
+            L.out_blk.fill_(float("nan"))
+            L.fwd_fused(**kw)
+            torch.cuda.synchronize()
+            got = L.get_output().float().cpu().numpy()
+            ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias if "bias" in kw else None,
+                                   residual=res if "residual" in kw else None,
+                                   relu=kw.get("relu", False))
+            assert rel_l2(got, ref) <= TOL[dtype], kw.keys()
+            if kw.get("relu"):
+                assert got.min() >= 0.0
+        # in place: the residual is the output buffer itself
+        L.out_blk.copy_(res_blk)
+        L.fwd_fused(bias=bias_dev, residual=L.out_blk, relu=True)
+        torch.cuda.synchronize()
+        got = L.get_output().float().cpu().numpy()
+        ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias, residual=res, relu=True)
+        assert rel_l2(got, ref) <= TOL[dtype]
+    finally:
+        L.close()

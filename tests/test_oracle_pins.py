@@ -302,3 +302,25 @@ def test_thread_count_does_not_change_result(rng):
         env = dict(os.environ, OMP_NUM_THREADS=t, PYTHONPATH=root)
         outs.add(subprocess.check_output([sys.executable, "-c", code], env=env, cwd=root).strip())
     assert len(outs) == 1
+
+
+def test_fused_forward_reduces_to_its_parts():
+    """Algorithm 4's L(): with zero weights the result is relu(bias + residual); with no
+    operator it is the plain forward pass; ReLU only clamps; bias shifts channel k alone."""
+    rng = np.random.default_rng(11)
+    N, C, K, H, W, R, S = 2, 3, 4, 5, 6, 3, 3
+    I = rng.standard_normal((N, C, H, W))
+    Wt = rng.standard_normal((K, C, R, S))
+    b = rng.standard_normal(K)
+    plain = oracle.fwd(I, Wt, 1, 1)
+    res = rng.standard_normal(plain.shape)
+    assert np.array_equal(oracle.fwd_fused(I, Wt, 1, 1), plain)
+    z = oracle.fwd_fused(I, np.zeros_like(Wt), 1, 1, bias=b, residual=res, relu=True)
+    assert np.array_equal(z, np.maximum(b[None, :, None, None] + res, 0.0))
+    full = oracle.fwd_fused(I, Wt, 1, 1, bias=b, residual=res, relu=True)
+    lin = oracle.fwd_fused(I, Wt, 1, 1, bias=b, residual=res, relu=False)
+    assert np.array_equal(full, np.maximum(lin, 0.0))
+    assert full.min() == 0.0 and (lin < 0).any()
+    only_b = oracle.fwd_fused(I, Wt, 1, 1, bias=b)
+    for k in range(K):
+        assert np.allclose(only_b[:, k] - plain[:, k], b[k], rtol=0, atol=1e-12)
