@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=N_BATCH)
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--cpu-batch", type=int, default=16)
+    ap.add_argument("--cpu-batch", type=int, default=128)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
