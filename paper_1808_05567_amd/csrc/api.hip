@@ -140,6 +140,8 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.n_kt = ceil_div(Kp, TK);
     a.Hs = Hs; a.LW = LW; a.LRW = LR * LW; a.PLS = ceil_div(LR * LW, 64) * 64;
     a.sampled = sampled ? 1 : 0;
+    a.inv_P = 1.0f / (float)P; a.inv_Hs = 1.0f / (float)Hs;
+    a.inv_LW = 1.0f / (float)LW; a.inv_TQ = 1.0f / (float)TQ;
     a.total = a.n_mt * a.n_qt * a.n_kt;
     a.per_xcd = ceil_div(a.total, 8);
     a.n_stage = ceil_div(Cb, npl);
@@ -153,6 +155,8 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     if (in_units * 16 > 4.0e9 || out_units * 16 > 4.0e9) return pl;
     // the kernels divide small indices through a float reciprocal, exact below 2^22
     if ((double)(N + 1) * std::max(Hs, P) >= 4.0e6 || a.LRW >= (1 << 22)) return pl;
+    // ... and multiply row indices (image x channel block x row) as 24-bit integers
+    if ((double)(N + 1) * std::max(Cb, Kp / V) * std::max(std::max(H, OH), Hs) >= 8.0e6) return pl;
     pl.ok = true;
     return pl;
 }

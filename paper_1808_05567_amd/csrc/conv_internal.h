@@ -48,6 +48,8 @@ struct IgemmArgs {
     int LRW;       // staged tile size   (pixels) = rows * LW
     int PLS;       // LDS plane pitch    (16-byte units)
     int sampled;   // R=S=1, pad=0: stage only the pixels that are read
+    // 1.0f / P, Hs, LW, TQ for the kernel's exact small divisions (see fast_div)
+    float inv_P, inv_Hs, inv_LW, inv_TQ;
     int total;     // workgroups doing work
     int per_xcd;   // ceil(total / 8)
     int n_stage;   // ceil(Cb / planes per stage)
@@ -171,6 +173,16 @@ hipError_t launch_unpack_wt(int dtype, const void *blk, void *kcrs, int K, int C
 static __device__ __forceinline__ int fast_div(int x, float inv)
 {
     return (int)(((float)x + 0.5f) * inv);
+}
+
+// Product of two integers that each fit 24 bits (signed): one full-rate instruction where
+// a 32-bit multiply takes four.  The planner bounds every operand it is used on.
+// `u` must be wave-uniform (a kernel argument or derived from one): it rides in a scalar register.
+static __device__ __forceinline__ int mul24(int a, int u)
+{
+    int r;  // (spelled out: the compiler turns the library's 24-bit multiply back into a 32-bit one)
+    asm("v_mul_i32_i24 %0, %1, %2" : "=v"(r) : "s"(u), "v"(a));
+    return r;
 }
 
 // Buffer addressing: a tensor is reached through a buffer resource

@@ -101,7 +101,7 @@ struct Elem<CONV_BF16> {
 
 // NB: LDS buffers of the staging ring (2 = double buffering; more = the loads run further ahead)
 template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT, int NB = 2>
-__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 64 ? 3 : FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
     constexpr int V = E_::V;
@@ -120,7 +120,9 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    // (the wave index is the same in all lanes: tell the compiler, so that everything
+    // derived from it lives in scalar registers and store offsets need no per-lane loop)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5;
     const int l32 = lane & 31;
     const int wave_k = wave % WK;
@@ -143,8 +145,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     const int q0 = qt * a.TQ;
     const int rho0 = mt * a.TR;
     const int NP = a.N * a.P;
-    const float inv_P = 1.0f / (float)a.P, inv_Hs = 1.0f / (float)a.Hs;
-    const float inv_LW = 1.0f / (float)a.LW, inv_TQ = 1.0f / (float)a.TQ;
+    const float inv_P = a.inv_P, inv_Hs = a.inv_Hs, inv_LW = a.inv_LW, inv_TQ = a.inv_TQ;
     const int n0 = fast_div(rho0, inv_P);
     const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
     const int HW = a.H * a.W;
@@ -170,23 +171,23 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         unsigned off = kOutOfRange;
         if (p < a.LRW) {
             const int row = fast_div(p, inv_LW);
-            const int col = p - row * a.LW;
+            const int col = p - mul24(row, a.LW);
             int n, ih, iw;
             bool ok;
             if (a.sampled) {
                 const int rho = rho0 + row;
                 n = fast_div(rho, inv_P);
-                ih = (rho - n * a.P) * a.stride;
-                iw = (q0 + col) * a.stride;
+                ih = mul24(rho - mul24(n, a.P), a.stride);
+                iw = mul24(q0 + col, a.stride);
                 ok = rho < NP && (q0 + col) < a.Q;
             } else {
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
-                ih = lam - n * a.Hs - a.pad_h;
+                ih = lam - mul24(n, a.Hs) - a.pad_h;
                 iw = q0 * a.stride - a.pad_w + col;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
-            if (ok) off = (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u;
+            if (ok) off = (unsigned)(mul24(mul24(mul24(n, a.Cb), a.H) + ih, a.W) + iw) * 16u;
         }
         g_off[i] = off;
     }
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         const int tap = e / NPL;
         const int pl = e - tap * NPL;
         if (tap < NTAPS && k0 + k < a.Kp)
-            off = (unsigned)((pl * NTAPS + tap) * a.Kp + k0 + k) * 16u;
+            off = (unsigned)(mul24(pl * NTAPS + tap, a.Kp) + k0 + k) * 16u;
         w_off[i] = off;
     }
 
@@ -240,17 +241,20 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     for (int j = 0; j < FM; ++j) {
         const int m = (wave_m * FM + j) * 32 + l32;
         const int trow = fast_div(m, inv_TQ);
-        const int tcol = m - trow * a.TQ;
+        const int tcol = m - mul24(trow, a.TQ);
         const int rho = rho0 + trow;
         const bool ok = trow < a.TR && rho < NP && (q0 + tcol) < a.Q;
         const int n = fast_div(rho, inv_P);
-        const int oj = rho - n * a.P;
-        int pos = a.sampled ? m : (n * a.Hs + oj * a.stride - lam0) * a.LW + tcol * a.stride;
+        const int oj = rho - mul24(n, a.P);
+        int pos = a.sampled ? m
+                            : mul24(mul24(n, a.Hs) + mul24(oj, a.stride) - lam0, a.LW) +
+                                  mul24(tcol, a.stride);
         if (!ok) pos = 0;
         // lane halves read two channel planes, or (one plane per step) two taps
         bpos[j] = ((NPL == 1 ? 0 : h) * a.PLS + pos) * 16;
-        obyte[j] = ok ? (unsigned)((n * Kb_out * a.OH + oj * a.ostr + a.oy0) * a.OW +
-                                   (q0 + tcol) * a.ostr + a.ox0) * 16u
+        obyte[j] = ok ? (unsigned)(mul24(mul24(mul24(n, Kb_out), a.OH) + mul24(oj, a.ostr) + a.oy0,
+                                         a.OW) +
+                                   mul24(q0 + tcol, a.ostr) + a.ox0) * 16u
                       : kOutOfRange;
     }
     const int a_base = (h * TK + wave_k * FK * 32 + l32) * 16;
@@ -458,6 +462,50 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         }
         return;
     }
+    if (!a.shuffle && !a.zero_fill) {
+        // Plain store: the lane's byte offsets (pixel, lane half) are formed once; per group
+        // of 8 channel rows only the scalar offset (the channel block) changes.
+        const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
+        unsigned ooff[FM];
+#pragma unroll
+        for (int j = 0; j < FM; ++j) ooff[j] = obyte[j] != kOutOfRange ? obyte[j] + lane_off : kOutOfRange;
+#pragma unroll
+        for (int i = 0; i < FK; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
+                if (krow0 >= a.Kp) continue;                            // wave-uniform
+                const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
+                // (fp32: the upper lane half's block may lie beyond the last channel block)
+                const bool upper_dead = (V == 4) && krow0 + 4 >= a.Kp;  // wave-uniform
+                if (!upper_dead) {
+#pragma unroll
+                    for (int j = 0; j < FM; ++j)
+                        E_::store4(ro, ooff[j], skip, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
+                                   acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < FM; ++j)
+                        E_::store4(ro, h ? kOutOfRange : ooff[j], skip, acc[i][j][4 * vq + 0],
+                                   acc[i][j][4 * vq + 1], acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
+                }
+            }
+        }
+        return;
+    }
+    // Scattering store (strided backward): position of the lane's result pixels in the
+    // output tensor, recomputed here rather than kept in registers across the main loop.
+    int sy[FM], sx[FM];
+#pragma unroll
+    for (int j = 0; j < FM; ++j) {
+        const int m = (wave_m * FM + j) * 32 + l32;
+        const int trow = fast_div(m, inv_TQ);
+        const int tcol = m - mul24(trow, a.TQ);
+        const int rho = rho0 + trow;
+        const int n = fast_div(rho, inv_P);
+        sy[j] = mul24(rho - mul24(n, a.P), a.ostr) + a.oy0;
+        sx[j] = mul24(q0 + tcol, a.ostr) + a.ox0;
+    }
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
 #pragma unroll
@@ -476,23 +524,15 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             for (int j = 0; j < FM; ++j) {
                 // (fp32: the upper lane half's block may lie beyond the last channel block)
                 bool live = obyte[j] != kOutOfRange && krow0 + 4 * h < a.Kp;
-                if (a.shuffle) {
-                    const int pix = (int)(obyte[j] >> 4);
-                    const int ox = pix % a.OW;
-                    const int oy = (pix / a.OW) % a.OH;
-                    live = live && oy + cy < a.OH && ox + cx < a.OW;
-                }
+                if (a.shuffle) live = live && sy[j] + cy < a.OH && sx[j] + cx < a.OW;
                 const unsigned off = live ? obyte[j] + lane_off : kOutOfRange;
                 E_::store4(ro, off, skip, acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1],
                            acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
                 if (a.zero_fill) {
-                    const int pix = (int)(obyte[j] >> 4);
-                    const int ox = pix % a.OW;
-                    const int oy = (pix / a.OW) % a.OH;
                     for (int dy = 0; dy < a.ostr; ++dy)
                         for (int dx = 0; dx < a.ostr; ++dx) {
                             if ((dy | dx) == 0) continue;
-                            const bool in = live && oy + dy < a.OH && ox + dx < a.OW;
+                            const bool in = live && sy[j] + dy < a.OH && sx[j] + dx < a.OW;
                             E_::store4(ro, in ? off + (unsigned)(dy * a.OW + dx) * 16u : kOutOfRange,
                                        skip, 0.f, 0.f, 0.f, 0.f);
                         }
@@ -568,6 +608,10 @@ static IgemmEntry g_igemm[] = {
     // bf16 1x1: a step is only two MFMA rounds, so the loads run two steps ahead
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),
+    // 64 accumulator registers per wave: three workgroups per CU
+    IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 4, 4, 1, 1, 1),
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 4, 4, 1, 1, 1, 3),
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 4, 4, 1, 1, 1),
 };
 
 static IgemmEntry *find_igemm(const IgemmVariant &v)
