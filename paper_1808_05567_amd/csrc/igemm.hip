@@ -101,7 +101,7 @@ struct Elem<CONV_BF16> {
 
 // NB: LDS buffers of the staging ring (2 = double buffering; more = the loads run further ahead)
 template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT, int NB = 2>
-__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 64 ? 3 : FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
     constexpr int V = E_::V;
@@ -608,10 +608,6 @@ static IgemmEntry g_igemm[] = {
     // bf16 1x1: a step is only two MFMA rounds, so the loads run two steps ahead
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),
-    // 64 accumulator registers per wave: three workgroups per CU
-    IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 4, 4, 1, 1, 1),
-    IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 4, 4, 1, 1, 1, 3),
-    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 4, 4, 1, 1, 1),
 };
 
 static IgemmEntry *find_igemm(const IgemmVariant &v)

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: kept in a scalar register)
     const int h = lane >> 5;
     const int l32 = lane & 31;
     const int wave_c = wave & 1;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void upd_c4_f32_kernel(const UpdArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: kept in a scalar register)
     const int h = lane >> 5;
     const int l32 = lane & 31;
 
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: kept in a scalar register)
     const int h = lane >> 5;
     const int l32 = lane & 31;
     const int grp = (lane >> 4) & 1;  // which 16 rows of the 32-row fragment

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: kept in a scalar register)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
     const int h = lane >> 5;
     const int l32 = lane & 31;
