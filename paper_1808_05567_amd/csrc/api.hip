@@ -46,6 +46,9 @@ struct conv_plan {
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
     bool upd_rows = false; // bf16 row kernel (stride 1)
     bool upd_bands = false; // fp32 eight-wave band kernel
+    bool upd_flat = false;  // fp32 1x1 eight-wave kernel on the flat pixel list
+    int upd_wb = 0;         //   its waves along the narrower tensor's channels
+    bool upd_a_is_in = false; //   whether the wider tensor is the input
     UpdRowsVariant urv{};
     int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
@@ -396,6 +399,47 @@ void plan_upd(conv_plan *p)
         p->upd_ok = true;
         (void)NT;
         return;
+    }
+    p->upd_flat = false;
+    if (!bf16 && sampled) {
+        // fp32 1x1: 256 channels of the wider tensor x up to 256 of the other per workgroup,
+        // the pixel list split so that one round of workgroups fills the chip
+        const bool a_is_in = f.Cp >= f.Kp;
+        const int chA = a_is_in ? f.Cp : f.Kp, chB = a_is_in ? f.Kp : f.Cp;
+        const double npix = (double)d.N * f.P * f.Q;
+        const int plA = a_is_in ? f.Cb : f.Kb, plB = a_is_in ? f.Kb : f.Cb;
+        if (chA >= 256 && chB >= 32 && npix < 4.0e6 &&
+            (double)(d.N + 1) * std::max(f.Cb, f.Kb) < 8.0e6 && (double)d.H * d.W < 8.0e6 &&
+            (double)d.N * f.Cp * d.H * d.W * 4 < 4.0e9 && (double)d.N * f.Kp * f.P * f.Q * 4 < 4.0e9) {
+            const int wb = chB >= 192 ? 4 : chB >= 96 ? 2 : 1, wp = 4 / wb, BP = 32;
+            UpdArgs &a = p->ua;
+            memset(&a, 0, sizeof(a));
+            a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0;
+            const int n_at = ceil_div(plA, 64), n_bt = ceil_div(plB, 16 * wb);
+            a.n_ct = a_is_in ? n_at : n_bt;
+            a.n_kt = a_is_in ? n_bt : n_at;
+            const int tiles = n_at * n_bt;
+            const int np = (int)npix;
+            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            splits = std::max(splits, ceil_div(np, 1 << 16));
+            const int pps = ceil_div(ceil_div(np, splits), BP) * BP;
+            splits = ceil_div(np, pps);
+            a.rows_per_split = pps;
+            a.splits = splits;
+            a.sampled = 1;
+            a.total = tiles * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            p->upd_wb = wb;
+            p->upd_a_is_in = a_is_in;
+            p->upd_lds = upd_f32_1x1_lds_bytes(wb);
+            p->upd_grid = a.per_xcd * 8;
+            p->upd_copies = splits * wp;
+            p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+            p->upd_flat = true;
+            p->upd_ok = true;
+            return;
+        }
     }
     p->upd_rows = false;
     const bool rows_3x3 = d.R == 3 && d.S == 3 && d.stride == 1;
@@ -764,7 +808,8 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.in = in;
     a.dout = dout;
     a.partial = static_cast<float *>(ws);
-    const hipError_t e = h->upd_c4     ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
+    const hipError_t e = h->upd_flat   ? launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s)
+                         : h->upd_c4   ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_bands ? launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                                        : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
@@ -847,6 +892,15 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
     }
     if (pass == 2) {
         if (!h->upd_ok) return CONV_EUNSUPPORTED;
+        if (h->upd_flat) {
+            snprintf(buf, buflen,
+                     "upd_1x1 dt=0 waves=2x%dx%d tile=256x%d (%s) pixels/split=%d splits=%d tiles=%dx%d "
+                     "grid=%d lds=%zu",
+                     h->upd_wb, 4 / h->upd_wb, 64 * h->upd_wb, h->upd_a_is_in ? "in x out" : "out x in",
+                     h->ua.rows_per_split, h->ua.splits, h->ua.n_ct, h->ua.n_kt, h->upd_grid,
+                     h->upd_lds);
+            return CONV_OK;
+        }
         if (h->upd_c4) {
             snprintf(buf, buflen,
                      "upd_c4 dt=0 RS=%dx%d TR=%d splits=%d x4 copies rows/split=%d ktiles=%d grid=%d lds=%zu",

@@ -152,6 +152,11 @@ bool upd_f32_bands_exists(int r, int s);
 size_t upd_f32_bands_exchange_bytes(int r, int s);
 hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                                 hipStream_t stream);
+// fp32, 1x1 without padding, at least 256 channels on one side: eight waves, 256 x (64*wb)
+// channel tile, bands of 32 pixels of the flat pixel list (UpdArgs::rows_per_split = pixels
+// per split, a multiple of 32; n_ct / n_kt = tiles over input / output channels)
+size_t upd_f32_1x1_lds_bytes(int wb);
+hipError_t launch_upd_f32_1x1(int wb, bool a_is_in, const UpdArgs &a, int grid, hipStream_t stream);
 // fp32, one input channel block (C <= 4): filter-row formulation, 7x7 and 3x3
 hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream);

@@ -31,6 +31,11 @@ SMALL = [
     (9, 72, 80, 7, 9, 3, 3, 1, 1),        # odd width, ragged channel tiles both ways, many bands
     (2, 64, 64, 14, 14, 3, 3, 2, 1),      # 3x3 stride 2: backward = four residue-class launches
     (3, 32, 48, 15, 13, 3, 3, 2, 1),      # ... odd extents: classes of different sizes
+    # 1x1 with at least 256 channels on one side (fp32: the eight-wave update kernel)
+    (2, 264, 72, 9, 9, 1, 1, 1, 0),       # ragged channel blocks on both sides, in x out
+    (2, 100, 320, 7, 5, 1, 1, 1, 0),      # out x in, 128-channel narrow side, bands cross images
+    (1, 512, 256, 6, 6, 1, 1, 2, 0),      # 256 x 256 tile, stride 2
+    (2, 256, 36, 5, 5, 1, 1, 1, 0),       # narrow side below 64 channels, a single ragged band
 ]
 
 
@@ -97,8 +102,9 @@ def test_first_layer_backward_bf16(shape):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("shape", [(3, 32, 48, 14, 14, 3, 3, 1, 1), (2, 64, 32, 12, 12, 1, 1, 2, 0)],
-                         ids=["3x3", "1x1s2"])
+@pytest.mark.parametrize("shape", [(3, 32, 48, 14, 14, 3, 3, 1, 1), (2, 64, 32, 12, 12, 1, 1, 2, 0),
+                                   (2, 288, 96, 10, 10, 1, 1, 2, 0)],
+                         ids=["3x3", "1x1s2", "1x1s2wide"])
 def test_integer_inputs_are_exact(shape, dtype):
     """Small integers: every product and partial sum is exact in fp32 (and the
     values are exact in bf16), so any summation order gives the oracle's bits."""
