@@ -404,7 +404,9 @@ void plan_upd(conv_plan *p)
     if (!bf16 && sampled) {
         // fp32 1x1: 256 channels of the wider tensor x up to 256 of the other per workgroup,
         // the pixel list split so that one round of workgroups fills the chip
-        const bool a_is_in = f.Cp >= f.Kp;
+        // (the wider side, but the input wherever it has 256 channels: partial dW keeps 4
+        // input channels together, which the rows of an accumulator tile store as 16 bytes)
+        const bool a_is_in = f.Cp >= f.Kp || f.Cp >= 256;
         const int chA = a_is_in ? f.Cp : f.Kp, chB = a_is_in ? f.Kp : f.Cp;
         const double npix = (double)d.N * f.P * f.Q;
         const int plA = a_is_in ? f.Cb : f.Kb, plB = a_is_in ? f.Kb : f.Cb;
