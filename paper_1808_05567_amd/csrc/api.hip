@@ -46,6 +46,7 @@ struct conv_plan {
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
     bool upd_rows = false; // bf16 row kernel (stride 1)
     bool upd_bands = false; // fp32 eight-wave band kernel
+    bool upd_flat_bf16 = false; // bf16 1x1 eight-wave kernel on the flat pixel list (variant: urv)
     bool upd_flat = false;  // fp32 1x1 eight-wave kernel on the flat pixel list
     int upd_wb = 0;         //   its waves along the narrower tensor's channels
     bool upd_a_is_in = false; //   whether the wider tensor is the input
@@ -436,9 +437,61 @@ void plan_upd(conv_plan *p)
             p->upd_a_is_in = a_is_in;
             p->upd_lds = upd_f32_1x1_lds_bytes(wb);
             p->upd_grid = a.per_xcd * 8;
-            p->upd_copies = splits * wp;
+            p->upd_copies = splits;
             p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
             p->upd_flat = true;
+            (void)wp;
+            p->upd_ok = true;
+            return;
+        }
+    }
+    p->upd_flat_bf16 = false;
+    if (bf16 && sampled && (double)d.N * f.P * f.Q < 4.0e6 &&
+        (double)(d.N + 1) * std::max(f.Cb, f.Kb) < 8.0e6 && (double)d.H * d.W < 8.0e6 &&
+        (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 && (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
+        // bf16 1x1: the channel block that re-reads the least (the input is read once per
+        // output-channel block, dO once per input-channel block), then the smaller block;
+        // the pixel list is split so that one round of workgroups fills the chip
+        static const UpdRowsVariant kFlat[9] = {
+            {1, 1, 4, 2, 1, 2, 4}, {1, 1, 2, 2, 2, 2, 4}, {1, 1, 1, 2, 4, 2, 4},
+            {1, 1, 4, 1, 2, 2, 4}, {1, 1, 2, 1, 4, 2, 4}, {1, 1, 2, 2, 2, 1, 2},
+            {1, 1, 4, 1, 2, 2, 2}, {1, 1, 2, 1, 4, 2, 2}, {1, 1, 2, 2, 2, 1, 1}};
+        UpdRowsVariant rv{};
+        bool have = false;
+        double best = 0;
+        for (const UpdRowsVariant &c : kFlat) {
+            if (!upd_bf16_1x1_variant_exists(c)) continue;
+            const int TC = c.wc * c.fc * 32, TK = c.wk * c.fk * 32;
+            const double bytes = (double)f.in_bytes / (d.stride * d.stride) * ceil_div(f.Kp, TK) +
+                                 (double)f.out_bytes * ceil_div(f.Cp, TC);
+            const double cost = bytes * (1.0 + 1e-4 * (TC + TK));
+            if (!have || cost < best) { rv = c; best = cost; have = true; }
+        }
+        if (have) {
+            const int TC = rv.wc * rv.fc * 32, TK = rv.wk * rv.fk * 32, BP = 64;
+            UpdArgs &a = p->ua;
+            memset(&a, 0, sizeof(a));
+            a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0;
+            a.n_ct = ceil_div(f.Cp, TC);
+            a.n_kt = ceil_div(f.Kp, TK);
+            const int tiles = a.n_ct * a.n_kt;
+            const int np = d.N * f.P * f.Q;
+            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            splits = std::max(splits, ceil_div(np, 1 << 16));
+            const int pps = ceil_div(ceil_div(np, splits), BP) * BP;
+            splits = ceil_div(np, pps);
+            a.rows_per_split = pps;
+            a.splits = splits;
+            a.sampled = 1;
+            a.total = tiles * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            p->urv = rv;
+            p->upd_lds = upd_bf16_1x1_lds_bytes(rv);
+            p->upd_grid = a.per_xcd * 8;
+            p->upd_copies = splits;
+            p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+            p->upd_flat_bf16 = true;
             p->upd_ok = true;
             return;
         }
@@ -810,7 +863,8 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.in = in;
     a.dout = dout;
     a.partial = static_cast<float *>(ws);
-    const hipError_t e = h->upd_flat   ? launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s)
+    const hipError_t e = h->upd_flat_bf16 ? launch_upd_bf16_1x1(h->urv, a, h->upd_grid, s)
+                         : h->upd_flat ? launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s)
                          : h->upd_c4   ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_bands ? launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
@@ -894,6 +948,14 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
     }
     if (pass == 2) {
         if (!h->upd_ok) return CONV_EUNSUPPORTED;
+        if (h->upd_flat_bf16) {
+            snprintf(buf, buflen,
+                     "upd_1x1 dt=1 waves=%dx%dx%d frags=%dx%d pixels/split=%d splits=%d tiles=%dx%d "
+                     "grid=%d lds=%zu",
+                     h->urv.wc, h->urv.wk, h->urv.wp, h->urv.fc, h->urv.fk, h->ua.rows_per_split,
+                     h->ua.splits, h->ua.n_ct, h->ua.n_kt, h->upd_grid, h->upd_lds);
+            return CONV_OK;
+        }
         if (h->upd_flat) {
             snprintf(buf, buflen,
                      "upd_1x1 dt=0 waves=2x%dx%d tile=256x%d (%s) pixels/split=%d splits=%d tiles=%dx%d "

@@ -152,6 +152,11 @@ bool upd_f32_bands_exists(int r, int s);
 size_t upd_f32_bands_exchange_bytes(int r, int s);
 hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                                 hipStream_t stream);
+// bf16, 1x1 without padding: eight waves on the flat pixel list, bands of 64 pixels
+// (UpdArgs::rows_per_split = pixels per split, a multiple of 64)
+bool upd_bf16_1x1_variant_exists(const UpdRowsVariant &v);
+size_t upd_bf16_1x1_lds_bytes(const UpdRowsVariant &v);
+hipError_t launch_upd_bf16_1x1(const UpdRowsVariant &v, const UpdArgs &a, int grid, hipStream_t stream);
 // fp32, 1x1 without padding, at least 256 channels on one side: eight waves, 256 x (64*wb)
 // channel tile, bands of 32 pixels of the flat pixel list (UpdArgs::rows_per_split = pixels
 // per split, a multiple of 32; n_ct / n_kt = tiles over input / output channels)

@@ -20,9 +20,9 @@
 //     band; the loads of the next band are in flight while this one is consumed;
 //   * parallelisation: the grid is (split of the pixel list) x (channel blocks);
 //     where side B has fewer than 256 channels the spare waves take alternate
-//     pixel pairs into private accumulators ("T copies + reduction" of Section
-//     II-I).  Every (split, pixel group) writes a private partial dW that the
-//     reduce kernel sums in a fixed order.
+//     pixel pairs into private accumulators, summed through LDS after the last
+//     band ("T copies + reduction" of Section II-I inside the workgroup).  Every
+//     split writes a private partial dW that the reduce kernel sums in a fixed order.
 #include "conv_internal.h"
 
 namespace convmi {
@@ -185,11 +185,49 @@ __global__ __launch_bounds__(512) void upd_f32_1x1_kernel(const UpdArgs a)
         __syncthreads();
     }
 
-    // ---- this (split, pixel group)'s partial dW tile: [copy][cb][k][c%V]
+    // ---- the pixel groups' sums are added up through LDS, group after group in a fixed
+    // order, two accumulator tiles per round (all staged bands have been consumed: the
+    // last barrier is behind us)
+    if constexpr (WP > 1) {
+        f32x4 *xch = reinterpret_cast<f32x4 *>(lds) + (size_t)(wave_a + 2 * wave_b) * 2 * 4 * 64 + lane;
+#pragma unroll
+        for (int g = 1; g < WP; ++g) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (wave_p == g) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int vq = 0; vq < 4; ++vq) {
+                            const f32x4 v = {acc[t][u][4 * vq + 0], acc[t][u][4 * vq + 1],
+                                             acc[t][u][4 * vq + 2], acc[t][u][4 * vq + 3]};
+                            xch[(u * 4 + vq) * 64] = v;
+                        }
+                }
+                __syncthreads();
+                if (wave_p == 0) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int vq = 0; vq < 4; ++vq) {
+                            const f32x4 v = xch[(u * 4 + vq) * 64];
+                            acc[t][u][4 * vq + 0] += v[0];
+                            acc[t][u][4 * vq + 1] += v[1];
+                            acc[t][u][4 * vq + 2] += v[2];
+                            acc[t][u][4 * vq + 3] += v[3];
+                        }
+                }
+                __syncthreads();
+            }
+        }
+        if (wave_p != 0) return;
+    }
+
+    // ---- this split's partial dW tile: [split][cb][k][c%V]
     // Tile (t,u): row i = side-A channel 4*(pa0 + wave_a*32 + i) + t, column l32 = side-B
     // channel 4*(pb0 + blkB) + 2*subB + u; register e of a lane holds row 8*(e/4) + 4*h + e%4.
     const size_t copy = (size_t)a.Cb * a.Kp * V;
-    float *dst = a.partial + (size_t)(split * WP + wave_p) * copy;
+    float *dst = a.partial + (size_t)split * copy;
     const int bB = pb0 + blkB;
     if (bB < nplB) {
 #pragma unroll
