@@ -360,8 +360,8 @@ void plan_upd(conv_plan *p)
     const bool bf16 = d.dtype == CONV_BF16;
     p->upd_c4 = false;
     if (!bf16 && f.Cb == 1 && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
-        // one input channel block: filter-row formulation
-        const int NT = 256, NPO = 16;
+        // one input channel block: filter-row formulation, eight waves, two LDS buffers
+        const int NPO = 16;
         const int Qp = (f.Q + 1) & ~1;
         const int NP = d.N * f.P;
         UpdArgs &a = p->ua;
@@ -376,15 +376,18 @@ void plan_upd(conv_plan *p)
             a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * d.pad);
             const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
             a.LRW = LR * a.LW;
-            a.PLS_in = a.LRW + 8;
-            a.PLS_out = ((TR * Qp + 7) / 8) * 8 + 1;
-            p->upd_lds = ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+            // whole wave-level loads of 64 positions; the dO plane pitch is 1 (mod 8) pixels
+            a.PLS_in = ceil_div(a.LRW, 64) * 64 + 8;
+            a.PLS_out = ceil_div(TR * Qp, 64) * 64 + 1;
+            p->upd_lds = 2 * ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
             if (p->upd_lds <= (size_t)kMaxLds) break;
         }
         a.TR = TR;
         a.n_ct = 1;
         a.n_kt = ceil_div(f.Kb, NPO);
-        int splits = std::max(1, 512 / a.n_kt);
+        // one workgroup per CU, one round
+        int splits = std::max(1, 256 / a.n_kt);
+        splits = std::max(splits, ceil_div(NP * f.Q, 1 << 17));  // chains of at most 2^15 pixels
         int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
         splits = ceil_div(NP, rps);
         a.rows_per_split = rps;
@@ -392,13 +395,15 @@ void plan_upd(conv_plan *p)
         a.sampled = 0;
         a.total = a.n_kt * splits;
         a.per_xcd = ceil_div(a.total, 8);
-        if ((double)(d.N + 1) * a.Hs >= 4.0e6 || NPO * TR * Qp >= (1 << 22)) return;
+        if ((double)(d.N + 1) * std::max(a.Hs, std::max(d.H, f.P * f.Kb)) >= 8.0e6 ||
+            a.LRW >= (1 << 22) || TR * Qp >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
+            (double)d.N * f.Kp * f.P * f.Q * 4 >= 4.0e9)
+            return;
         p->upd_grid = a.per_xcd * 8;
-        p->upd_copies = splits * 4;
+        p->upd_copies = splits;
         p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
         p->upd_c4 = true;
         p->upd_ok = true;
-        (void)NT;
         return;
     }
     p->upd_flat = false;
@@ -967,7 +972,7 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         }
         if (h->upd_c4) {
             snprintf(buf, buflen,
-                     "upd_c4 dt=0 RS=%dx%d TR=%d splits=%d x4 copies rows/split=%d ktiles=%d grid=%d lds=%zu",
+                     "upd_c4 dt=0 RS=%dx%d waves=2x4 TR=%d splits=%d rows/split=%d ktiles=%d grid=%d lds=%zu",
                      h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
                      h->upd_grid, h->upd_lds);
             return CONV_OK;

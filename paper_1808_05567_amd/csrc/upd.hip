@@ -257,141 +257,6 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
             }
 }
 
-// fp32 layers with at most 4 input channels (one channel block: the first
-// layer of an image network).  With so few channels the roles are swapped:
-// M = output channels (dO is the A operand), N = (s, c) -- the S taps of one
-// filter row times the 4 channel slots, which are S*4 consecutive floats of the
-// staged input row -- and one accumulator tile per filter row r.  The four
-// waves take every fourth pixel pair and write four private copies, which the
-// reduce kernel sums together with the copies of the other splits.
-template <int R, int S>
-__global__ __launch_bounds__(256) void upd_c4_f32_kernel(const UpdArgs a)
-{
-    constexpr int V = 4;
-    constexpr int NTAPS = R * S;
-    constexpr int FK = 2;        // 64 output channels per workgroup
-    constexpr int NPO = 16;      // staged dO planes
-    static_assert(S * V <= 32, "one filter row must fit the 32 columns of a fragment");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    float *ldsI = reinterpret_cast<float *>(lds);
-    float *ldsO = ldsI + (size_t)a.PLS_in * V;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: kept in a scalar register)
-    const int h = lane >> 5;
-    const int l32 = lane & 31;
-
-    const int bid = blockIdx.x;
-    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
-    if (lin >= a.total) return;
-    const int kt = lin % a.n_kt;
-    const int split = lin / a.n_kt;
-    const int kb0 = kt * NPO;
-
-    const int NP = a.N * a.P;
-    const int rho_begin = split * a.rows_per_split;
-    const int rho_end = min(NP, rho_begin + a.rows_per_split);
-    const int Qp = (a.Q + 1) & ~1;
-    const int npxO = a.TR * Qp;
-    const int PQ = a.P * a.Q;
-    const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
-    const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P;
-    const float inv_npx = 1.0f / (float)npxO;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-    auto stage = [&](int rho0) {
-        const int n0 = fast_div(rho0, inv_P);
-        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
-        for (int p = tid; p < a.LRW; p += 256) {
-            const int row = fast_div(p, inv_LW);
-            const int col = p - row * a.LW;
-            const int lam = lam0 + row;
-            const int n = fast_div(lam, inv_Hs);
-            const int ih = lam - n * a.Hs - a.pad;
-            const int iw = col - a.pad;
-            u32x4 v = zero4;
-            if (n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                v = static_cast<const u32x4 *>(a.in)[((size_t)n * a.H + ih) * a.W + iw];
-            *reinterpret_cast<u32x4 *>(ldsI + (size_t)p * V) = v;
-        }
-        for (int ci = tid; ci < NPO * npxO; ci += 256) {
-            const int pl = fast_div(ci, inv_npx);
-            const int p = ci - pl * npxO;
-            const int trow = fast_div(p, inv_Qp);
-            const int col = p - trow * Qp;
-            const int rho = rho0 + trow;
-            u32x4 v = zero4;
-            if (rho < rho_end && col < a.Q && kb0 + pl < a.Kb) {
-                const int n = fast_div(rho, inv_P);
-                const int oj = rho - n * a.P;
-                v = static_cast<const u32x4 *>(a.dout)[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Q + col];
-            }
-            *reinterpret_cast<u32x4 *>(ldsO + ((size_t)pl * a.PLS_out + p) * V) = v;
-        }
-    };
-
-    f32x16 acc[R][FK];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < FK; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[r][j][e] = 0.0f;
-
-    int a_lane[FK];
-#pragma unroll
-    for (int j = 0; j < FK; ++j) {
-        const int k = j * 32 + l32;
-        a_lane[j] = (k / V) * a.PLS_out * V + (k % V);
-    }
-    // column (s, c) of the B operand = float l32 of the S*4 floats starting at the pixel
-    const int b_lane = l32 < S * V ? l32 : 0;
-
-    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR) {
-        __syncthreads();
-        stage(rho0);
-        __syncthreads();
-        const int n0 = rho0 / a.P;
-        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
-        const int rows = min(a.TR, rho_end - rho0);
-        for (int trow = 0; trow < rows; ++trow) {
-            const int rho = rho0 + trow;
-            const int n = rho / a.P;
-            const int oj = rho - n * a.P;
-            const int irow = (n * a.Hs + oj * a.stride - lam0) * a.LW;
-            const int orow = trow * Qp;
-            for (int col = 2 * wave + h; col < Qp; col += 8) {
-                float av[FK];
-#pragma unroll
-                for (int j = 0; j < FK; ++j) av[j] = ldsO[a_lane[j] + (orow + col) * V];
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const float bv = ldsI[(irow + r * a.LW + col * a.stride) * V + b_lane];
-#pragma unroll
-                    for (int j = 0; j < FK; ++j)
-                        acc[r][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j], bv, acc[r][j], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // partial copy (split, wave): [tap][k][c] (one channel block)
-    const size_t copy = (size_t)NTAPS * a.Kp * V;
-    float *dst = a.partial + ((size_t)split * 4 + wave) * copy;
-    const int s = l32 / V, c = l32 % V;
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < FK; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int k = kb0 * V + j * 32 + (e / 4) * 8 + h * 4 + (e % 4);
-                if (s < S && k < a.Kp) dst[((size_t)(r * S + s) * a.Kp + k) * V + c] = acc[r][j][e];
-            }
-}
-
 // bf16 activations and gradients (vlen 8), fp32 accumulation and output.
 //
 // The MFMA wants 8 consecutive reduction indices (pixels) per lane, while the
@@ -739,27 +604,6 @@ hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, i
         e->lds_attr = lds_bytes;
     }
     hipLaunchKernelGGL(e->fn, dim3(grid), dim3(256), lds_bytes, stream, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
-                         hipStream_t stream)
-{
-    typedef void (*fn_t)(const UpdArgs);
-    fn_t fn = nullptr;
-    if (r == 7 && s == 7) fn = upd_c4_f32_kernel<7, 7>;
-    if (r == 3 && s == 3) fn = upd_c4_f32_kernel<3, 3>;
-    if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attr[2] = {0, 0};
-    size_t &cur = attr[r == 7 ? 0 : 1];
-    if (lds_bytes > cur) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        cur = lds_bytes;
-    }
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(256), lds_bytes, stream, a);
     return hipGetLastError();
 }
 

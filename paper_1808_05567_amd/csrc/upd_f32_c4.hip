@@ -1,0 +1,230 @@
+// fp32 weight-gradient update (Algorithm 8 of the paper, with padding) for layers
+// with at most 4 input channels (one channel block: the first layer of an image
+// network), any stride.
+//
+//   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
+//
+// With so few channels the roles of Algorithm 9's small GEMM are swapped: M = output
+// channels (dO is the A operand), N = (s, c) -- the S taps of one filter row times
+// the 4 channel slots, which are S*4 consecutive floats of the staged input row --
+// and one accumulator tile per filter row r, all R rows resident in the wave.
+// Eight waves = 2 x 32 output channels x FOUR pixel groups that take alternate pixel
+// pairs of a band into private accumulators, summed through LDS after the last band
+// (the "T copies + reduction" of Section II-I inside the workgroup).  The band of the
+// next step (dO rows and the input rows they touch) streams into the second LDS buffer
+// while the current one is consumed (Section II-E), one barrier per band.
+#include "conv_internal.h"
+
+namespace convmi {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int R, int S>
+__global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
+{
+    constexpr int V = 4;
+    constexpr int NTAPS = R * S;
+    constexpr int NW = 8;
+    constexpr int NPO = 16;  // staged dO planes: 64 output channels per workgroup
+    static_assert(S * V <= 32, "one filter row must fit the 32 columns of a fragment");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int ibytes = a.PLS_in * 16;
+    const int bufbytes = ibytes + NPO * a.PLS_out * 16;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int wave_k = wave & 1;
+    const int wave_p = wave >> 1;
+
+    const int bid = blockIdx.x;
+    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+    if (lin >= a.total) return;
+    const int kt = lin % a.n_kt;
+    const int split = lin / a.n_kt;
+    const int kb0 = kt * NPO;
+
+    const int NP = a.N * a.P;
+    const int rho_begin = split * a.rows_per_split;
+    const int rho_end = min(NP, rho_begin + a.rows_per_split);
+    const int Qp = (a.Q + 1) & ~1;  // dO row pitch in the staged band: pairs stay inside a row
+    const int npxO = a.TR * Qp;
+    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
+    const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P;
+    const rsrc_t rsrc_in = make_rsrc(a.in, 0, (size_t)a.N * HW * 16);
+    const rsrc_t rsrc_out = make_rsrc(a.dout, 0, (size_t)a.N * a.Kb * PQ * 16);
+
+    // Stage the input rows and the dO rows of linear output rows [rho0, rho0+TR) into
+    // buffer `buf`: wave-level loads of 64 consecutive positions of one plane straight
+    // into LDS; positions outside the image, the split or the tensor arrive as zeros.
+    auto fetch = [&](int rho0, int buf) {
+        unsigned char *ib = lds + buf * bufbytes;
+        unsigned char *ob = ib + ibytes;
+        const int n0 = fast_div(rho0, inv_P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int nch_in = (a.LRW + 63) >> 6, nch_out = (npxO + 63) >> 6;
+        auto in_off = [&](int p) -> unsigned {
+            if (p >= a.LRW) return kOutOfRange;
+            const int row = fast_div(p, inv_LW);
+            const int col = p - mul24(row, a.LW);
+            const int lam = lam0 + row;
+            const int n = fast_div(lam, inv_Hs);
+            const int ih = lam - mul24(n, a.Hs) - a.pad;
+            const int iw = col - a.pad;
+            const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            return ok ? (unsigned)(mul24(mul24(n, a.H) + ih, a.W) + iw) * 16u : kOutOfRange;
+        };
+        auto out_off = [&](int p) -> unsigned {
+            if (p >= npxO) return kOutOfRange;
+            const int trow = fast_div(p, inv_Qp);
+            const int col = p - mul24(trow, Qp);
+            const int rho = rho0 + trow;
+            if (rho >= rho_end || col >= a.Q) return kOutOfRange;
+            const int n = fast_div(rho, inv_P);
+            const int oj = rho - mul24(n, a.P);
+            return (unsigned)(mul24(mul24(mul24(n, a.Kb), a.P) + oj, a.Q) + col) * 16u;
+        };
+        // units: the input chunks, then (dO chunk, plane) pairs; equal contiguous shares
+        const int total = nch_in + nch_out * NPO;
+        const int share = (total + NW - 1) / NW;
+        const int first = wave * share, last = min(total, first + share);
+        int cur = -1;
+        unsigned off = kOutOfRange;
+        for (int e = first; e < last; ++e) {
+            if (e < nch_in) {
+                load_to_lds_16(rsrc_in, in_off(e * 64 + lane), 0u, ib + e * 64 * 16);
+            } else {
+                const int u = e - nch_in;
+                const int ch = u >> 4, pl = u & 15;
+                if (ch != cur) {
+                    cur = ch;
+                    off = out_off(ch * 64 + lane);
+                }
+                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                               (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
+                               ob + (pl * a.PLS_out + ch * 64) * 16);
+            }
+        }
+    };
+
+    f32x16 acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[r][e] = 0.0f;
+
+    // A operand: output channel wave_k*32 + l32 of the staged dO pixel
+    const int k_lane = wave_k * 32 + l32;
+    const int a_lane = (k_lane / V) * a.PLS_out * V + (k_lane % V);
+    // column (s, c) of the B operand = float l32 of the S*4 floats starting at the pixel
+    const int b_lane = l32 < S * V ? l32 : 0;
+
+    if (rho_begin < rho_end) fetch(rho_begin, 0);
+    wait_all_memory();
+    __syncthreads();
+    int buf = 0;
+    for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, buf ^= 1) {
+        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, buf ^ 1);
+        const float *ldsI = reinterpret_cast<const float *>(lds + buf * bufbytes);
+        const float *ldsO = reinterpret_cast<const float *>(lds + buf * bufbytes + ibytes);
+        const int n0 = fast_div(rho0, inv_P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int rows = min(a.TR, rho_end - rho0);
+        for (int trow = 0; trow < rows; ++trow) {
+            const int rho = rho0 + trow;
+            const int n = fast_div(rho, inv_P);
+            const int oj = rho - n * a.P;
+            const int irow = (n * a.Hs + oj * a.stride - lam0) * a.LW;
+            const int orow = trow * Qp;
+            // the lane halves take the two pixels of a pair, the pixel groups alternate pairs
+#pragma unroll 2
+            for (int col = 2 * wave_p + h; col < Qp; col += 8) {
+                const float av = ldsO[a_lane + (orow + col) * V];
+                float bv[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    bv[r] = ldsI[(irow + r * a.LW + col * a.stride) * V + b_lane];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[r], acc[r], 0, 0, 0);
+            }
+        }
+        wait_all_memory();
+        __syncthreads();
+    }
+
+    // ---- the pixel groups' sums are added up through LDS, group after group in a fixed
+    // order, two accumulator tiles per round (all staged bands have been consumed)
+    f32x4 *xch = reinterpret_cast<f32x4 *>(lds) + (size_t)wave_k * 2 * 4 * 64 + lane;
+#pragma unroll
+    for (int g = 1; g < 4; ++g) {
+#pragma unroll
+        for (int r0 = 0; r0 < R; r0 += 2) {
+            if (wave_p == g) {
+#pragma unroll
+                for (int rr = 0; rr < 2 && r0 + rr < R; ++rr)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const f32x4 v = {acc[r0 + rr][4 * vq + 0], acc[r0 + rr][4 * vq + 1],
+                                         acc[r0 + rr][4 * vq + 2], acc[r0 + rr][4 * vq + 3]};
+                        xch[(rr * 4 + vq) * 64] = v;
+                    }
+            }
+            __syncthreads();
+            if (wave_p == 0) {
+#pragma unroll
+                for (int rr = 0; rr < 2 && r0 + rr < R; ++rr)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const f32x4 v = xch[(rr * 4 + vq) * 64];
+                        acc[r0 + rr][4 * vq + 0] += v[0];
+                        acc[r0 + rr][4 * vq + 1] += v[1];
+                        acc[r0 + rr][4 * vq + 2] += v[2];
+                        acc[r0 + rr][4 * vq + 3] += v[3];
+                    }
+            }
+            __syncthreads();
+        }
+    }
+    if (wave_p != 0) return;
+
+    // ---- this split's partial dW: [split][tap][k][c] (one channel block)
+    const size_t copy = (size_t)NTAPS * a.Kp * V;
+    float *dst = a.partial + (size_t)split * copy;
+    const int s = l32 / V, c = l32 % V;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int k = kb0 * V + wave_k * 32 + (e / 4) * 8 + h * 4 + (e % 4);
+            if (s < S && k < a.Kp) dst[((size_t)(r * S + s) * a.Kp + k) * V + c] = acc[r][e];
+        }
+}
+
+hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+                         hipStream_t stream)
+{
+    typedef void (*fn_t)(const UpdArgs);
+    fn_t fn = nullptr;
+    if (r == 7 && s == 7) fn = upd_c4_f32_kernel<7, 7>;
+    if (r == 3 && s == 3) fn = upd_c4_f32_kernel<3, 3>;
+    if (!fn) return hipErrorInvalidDeviceFunction;
+    static size_t attr[2] = {0, 0};
+    size_t &cur = attr[r == 7 ? 0 : 1];
+    if (lds_bytes > cur) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        cur = lds_bytes;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace convmi
