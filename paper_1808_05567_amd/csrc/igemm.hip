@@ -282,24 +282,36 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
             if (st + 1 < nst) fetch(st + 1);
             const unsigned char *wb = lds + (st & 1) * bufbytes;
             const unsigned char *ib = wb + WBYTES;
-#pragma unroll 1
-            for (int q = 0; q < NENT / 2; ++q) {
+            // (the operands of tap pair q+1 are read before the MFMAs of pair q issue)
+            auto read_pair = [&](int q, u32x4(&af)[FK], u32x4(&bf)[FM]) {
                 const int t0 = 2 * q;
                 const int t1 = (2 * q + 1 < NTAPS) ? 2 * q + 1 : NTAPS - 1;
                 const int off0 = ((t0 / S) * a.LW + (t0 % S)) * 16;
                 const int off1 = ((t1 / S) * a.LW + (t1 % S)) * 16;
                 const int toff = h ? off1 : off0;
-                u32x4 af[FK], bf[FM];
 #pragma unroll
                 for (int i = 0; i < FK; ++i)
                     af[i] = *reinterpret_cast<const u32x4 *>(wb + a_base + (2 * q * TK + 32 * i) * 16);
 #pragma unroll
                 for (int j = 0; j < FM; ++j)
                     bf[j] = *reinterpret_cast<const u32x4 *>(ib + bpos[j] + toff);
+            };
+            u32x4 ac[FK], bc[FM];
+            read_pair(0, ac, bc);
+#pragma unroll
+            for (int q = 0; q < NENT / 2; ++q) {
+                u32x4 an[FK], bn[FM];
+                if (q + 1 < NENT / 2) read_pair(q + 1, an, bn);
 #pragma unroll
                 for (int i = 0; i < FK; ++i)
 #pragma unroll
-                    for (int j = 0; j < FM; ++j) E_::mma(af[i], bf[j], acc[i][j]);
+                    for (int j = 0; j < FM; ++j) E_::mma(ac[i], bc[j], acc[i][j]);
+                if (q + 1 < NENT / 2) {
+#pragma unroll
+                    for (int i = 0; i < FK; ++i) ac[i] = an[i];
+#pragma unroll
+                    for (int j = 0; j < FM; ++j) bc[j] = bn[j];
+                }
             }
             staged();
             __syncthreads();
