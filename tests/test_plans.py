@@ -1,0 +1,108 @@
+"""Host-side checks of the planner (no GPU): every plan it hands out must fit the
+machine (LDS per workgroup, a non-empty grid, a workspace that covers the partial
+results), for the benchmark layers and for a seeded sweep of other descriptors, and
+the kernel families must be chosen where they apply."""
+import re
+
+import numpy as np
+import pytest
+
+from paper_1808_05567_amd import conv, inputs
+
+LDS_PER_CU = 160 * 1024
+
+
+def _plans(shape, dt):
+    h = conv.conv_create(*shape, dt)
+    out = {}
+    try:
+        info = conv.conv_query(h)
+        for which in (conv.PASS_FWD, conv.PASS_BWD_DATA, conv.PASS_UPD):
+            try:
+                out[which] = conv.conv_describe(h, which)
+            except conv.ConvError as e:
+                assert e.status == conv.CONV_EUNSUPPORTED
+                out[which] = None
+    finally:
+        conv.conv_destroy(h)
+    return info, out
+
+
+def _field(text, name):
+    m = re.search(r"\b%s=(\d+)" % name, text)
+    assert m, (name, text)
+    return int(m.group(1))
+
+
+def _check(info, plans):
+    for which, text in plans.items():
+        if text is None:
+            continue
+        assert 0 < _field(text, "lds") <= LDS_PER_CU, text
+        assert _field(text, "grid") >= 1, text
+    if plans[conv.PASS_UPD] is not None:
+        # every partial copy of dW the update kernel writes fits the workspace
+        assert info.upd_splits >= 1
+        assert info.workspace_bytes >= info.upd_splits * info.dwt_bytes
+    if plans[conv.PASS_BWD_DATA] is not None:
+        # the transformed weights of the backward pass live in the workspace
+        assert info.workspace_bytes >= 16
+
+
+@pytest.mark.parametrize("dt", [conv.CONV_F32, conv.CONV_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 256])
+def test_table1_plans_fit_the_machine(N, dt):
+    for l in inputs.TABLE_I:
+        info, plans = _plans((N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad), dt)
+        _check(info, plans)
+        if not (l.id == 1 and dt == conv.CONV_BF16):
+            assert all(p is not None for p in plans.values()), (l.id, plans)
+
+
+def test_seeded_descriptor_sweep_plans_fit_the_machine():
+    rng = np.random.default_rng(180805567)
+    planned = 0
+    for _ in range(400):
+        R = int(rng.choice([1, 1, 3, 3, 7]))
+        stride = int(rng.choice([1, 1, 2, 3]))
+        pad = int(rng.integers(0, R // 2 + 1))
+        H = int(rng.integers(max(R, 1), 70))
+        W = int(rng.integers(max(R, 1), 70))
+        C = int(rng.choice([1, 3, 4, 8, 20, 64, 100, 128, 256, 264, 512, 1030]))
+        K = int(rng.choice([1, 8, 12, 64, 72, 128, 256, 320, 1024, 2048]))
+        N = int(rng.choice([1, 2, 3, 16, 64]))
+        for dt in (conv.CONV_F32, conv.CONV_BF16):
+            info, plans = _plans((N, C, K, H, W, R, R, stride, pad), dt)
+            _check(info, plans)
+            planned += sum(p is not None for p in plans.values())
+    assert planned > 1500  # the sweep is not vacuous: most passes have a kernel
+
+
+def test_kernel_families_are_chosen_where_they_apply():
+    # fp32 1x1 with 256 channels on one side: eight-wave kernel on the flat pixel list
+    _, p = _plans((256, 256, 1024, 14, 14, 1, 1, 1, 0), conv.CONV_F32)
+    assert p[conv.PASS_UPD].startswith("upd_1x1 dt=0") and "in x out" in p[conv.PASS_UPD]
+    _, p = _plans((256, 64, 256, 56, 56, 1, 1, 1, 0), conv.CONV_F32)
+    assert p[conv.PASS_UPD].startswith("upd_1x1 dt=0") and "out x in" in p[conv.PASS_UPD]
+    # ... below that, the four-wave kernel
+    _, p = _plans((256, 64, 64, 56, 56, 1, 1, 1, 0), conv.CONV_F32)
+    assert p[conv.PASS_UPD].startswith("upd dt=0")
+    # bf16 1x1: flat pixel list at every width
+    for C, K in ((64, 64), (64, 256), (1024, 2048)):
+        _, p = _plans((256, C, K, 14, 14, 1, 1, 1, 0), conv.CONV_BF16)
+        assert p[conv.PASS_UPD].startswith("upd_1x1 dt=1")
+    # 3x3 stride 1: band kernel (fp32), row kernel (bf16)
+    _, p = _plans((256, 256, 256, 14, 14, 3, 3, 1, 1), conv.CONV_F32)
+    assert p[conv.PASS_UPD].startswith("upd_bands")
+    _, p = _plans((256, 256, 256, 14, 14, 3, 3, 1, 1), conv.CONV_BF16)
+    assert p[conv.PASS_UPD].startswith("upd_rows")
+    # one input channel block, fp32: filter-row kernel; backward: all classes in one launch
+    _, p = _plans((256, 3, 64, 224, 224, 7, 7, 2, 3), conv.CONV_F32)
+    assert p[conv.PASS_UPD].startswith("upd_c4")
+    assert "launches=1" in p[conv.PASS_BWD_DATA]
+    # 3x3 stride 2 backward: one launch per residue class
+    _, p = _plans((4, 64, 64, 14, 14, 3, 3, 2, 1), conv.CONV_F32)
+    assert "launches=4" in p[conv.PASS_BWD_DATA]
+    # small minibatch, long reduction: the forward reduction is split
+    _, p = _plans((1, 512, 512, 7, 7, 3, 3, 1, 1), conv.CONV_F32)
+    assert _field(p[conv.PASS_FWD], "ksplit") > 1
