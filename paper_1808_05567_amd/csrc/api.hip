@@ -359,7 +359,7 @@ void plan_upd(conv_plan *p)
     const bool sampled = (d.R == 1 && d.S == 1 && d.pad == 0);
     const bool bf16 = d.dtype == CONV_BF16;
     p->upd_c4 = false;
-    if (!bf16 && f.Cb == 1 && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
+    if (d.C <= 4 && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
         // one input channel block: filter-row formulation, eight waves, two LDS buffers
         const int NPO = 16;
         const int Qp = (f.Q + 1) & ~1;
@@ -384,7 +384,9 @@ void plan_upd(conv_plan *p)
         }
         a.TR = TR;
         a.n_ct = 1;
-        a.n_kt = ceil_div(f.Kb, NPO);
+        a.n_kt = ceil_div(f.Kp, 64);  // 64 output channels per workgroup
+        // (bf16 tensors: the staged band must fit the kernel's register staging)
+        if (bf16 && (a.PLS_in - 8 > 8 * 512 || 8 * TR * Qp > 4 * 512)) return;
         // one workgroup per CU, one round
         int splits = std::max(1, 256 / a.n_kt);
         splits = std::max(splits, ceil_div(NP * f.Q, 1 << 17));  // chains of at most 2^15 pixels
@@ -396,7 +398,7 @@ void plan_upd(conv_plan *p)
         a.total = a.n_kt * splits;
         a.per_xcd = ceil_div(a.total, 8);
         if ((double)(d.N + 1) * std::max(a.Hs, std::max(d.H, f.P * f.Kb)) >= 8.0e6 ||
-            a.LRW >= (1 << 22) || TR * Qp >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
+            a.LRW >= (1 << 22) || 8 * TR * Qp >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
             (double)d.N * f.Kp * f.P * f.Q * 4 >= 4.0e9)
             return;
         p->upd_grid = a.per_xcd * 8;
@@ -870,7 +872,7 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.partial = static_cast<float *>(ws);
     const hipError_t e = h->upd_flat_bf16 ? launch_upd_bf16_1x1(h->urv, a, h->upd_grid, s)
                          : h->upd_flat ? launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s)
-                         : h->upd_c4   ? launch_upd_c4(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
+                         : h->upd_c4   ? launch_upd_c4(h->d.dtype, h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
                          : h->upd_bands ? launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
                                        : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
@@ -972,8 +974,8 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         }
         if (h->upd_c4) {
             snprintf(buf, buflen,
-                     "upd_c4 dt=0 RS=%dx%d waves=2x4 TR=%d splits=%d rows/split=%d ktiles=%d grid=%d lds=%zu",
-                     h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
+                     "upd_c4 dt=%d RS=%dx%d waves=2x4 TR=%d splits=%d rows/split=%d ktiles=%d grid=%d lds=%zu",
+                     (int)h->d.dtype, h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
                      h->upd_grid, h->upd_lds);
             return CONV_OK;
         }

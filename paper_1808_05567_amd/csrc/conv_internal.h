@@ -162,8 +162,9 @@ hipError_t launch_upd_bf16_1x1(const UpdRowsVariant &v, const UpdArgs &a, int gr
 // per split, a multiple of 32; n_ct / n_kt = tiles over input / output channels)
 size_t upd_f32_1x1_lds_bytes(int wb);
 hipError_t launch_upd_f32_1x1(int wb, bool a_is_in, const UpdArgs &a, int grid, hipStream_t stream);
-// fp32, one input channel block (C <= 4): filter-row formulation, 7x7 and 3x3
-hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+// at most 4 input channels: filter-row formulation, 7x7 and 3x3; fp32 tensors, or bf16
+// tensors widened on their way into LDS (then UpdArgs::Kb counts blocks of 8 channels)
+hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream);
 hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
                              hipStream_t stream);

@@ -586,6 +586,9 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 4, 4, 4),
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 4, 4, 6),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 2, 4, 4, 6),
+    // (an odd number of channel blocks of dO: one block per step)
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 1, 4, 4, 6),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 1, 4, 4, 6),
     // bf16
     IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 3, 3, 3),
@@ -593,6 +596,7 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 1, 1, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 3, 3, 3),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 7, 7, 12),
     // bf16, two channel fragments per wave: every staged-input fragment read
     // from LDS feeds two MFMAs (LDS bandwidth is what bounds bf16 otherwise)
     IGEMM_ENTRY(CONV_BF16, 2, 2, 2, 7, 2, 3, 3, 3),

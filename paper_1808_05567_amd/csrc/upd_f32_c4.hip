@@ -1,6 +1,7 @@
-// fp32 weight-gradient update (Algorithm 8 of the paper, with padding) for layers
-// with at most 4 input channels (one channel block: the first layer of an image
-// network), any stride.
+// Weight-gradient update (Algorithm 8 of the paper, with padding) for layers with
+// at most 4 input channels (the first layer of an image network), any stride; fp32
+// tensors, or bf16 tensors widened to fp32 on their way into LDS (the products are
+// then exact, accumulation and output are fp32 as for every bf16 update).
 //
 //   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
 //
@@ -12,15 +13,20 @@
 // pairs of a band into private accumulators, summed through LDS after the last band
 // (the "T copies + reduction" of Section II-I inside the workgroup).  The band of the
 // next step (dO rows and the input rows they touch) streams into the second LDS buffer
-// while the current one is consumed (Section II-E), one barrier per band.
+// while the current one is consumed (Section II-E), one barrier per band: fp32 by loads
+// that write straight into LDS, bf16 through registers (where it is converted).
 #include "conv_internal.h"
 
 namespace convmi {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <int R, int S>
+// BF16IN: the tensors are bf16 in blocks of 8 channels (the input's first 4 slots are
+// used); LDS holds the same fp32 bands either way.
+template <int R, int S, bool BF16IN>
 __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
 {
     constexpr int V = 4;
@@ -56,39 +62,49 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
     const int HW = a.H * a.W, PQ = a.P * a.Q;
     const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
     const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P;
+    const float inv_npx = 1.0f / (float)npxO;
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, (size_t)a.N * HW * 16);
     const rsrc_t rsrc_out = make_rsrc(a.dout, 0, (size_t)a.N * a.Kb * PQ * 16);
+    // (bf16: a.Kb counts blocks of 8 channels; a pixel's block is 16 bytes in both types)
 
     // Stage the input rows and the dO rows of linear output rows [rho0, rho0+TR) into
+    // buffer `buf`: wave-level loads of 64 consecutive positions of one plane straight
+    // into LDS; positions outside the image, the split or the tensor arrive as zeros.
+    // byte offset of staged input position p / staged dO position p (channel block 0) of
+    // the band that starts at linear output row rho0
+    auto in_off = [&](int p, int lam0) -> unsigned {
+        if (p >= a.LRW) return kOutOfRange;
+        const int row = fast_div(p, inv_LW);
+        const int col = p - mul24(row, a.LW);
+        const int lam = lam0 + row;
+        const int n = fast_div(lam, inv_Hs);
+        const int ih = lam - mul24(n, a.Hs) - a.pad;
+        const int iw = col - a.pad;
+        const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        return ok ? (unsigned)(mul24(mul24(n, a.H) + ih, a.W) + iw) * 16u : kOutOfRange;
+    };
+    auto out_off = [&](int p, int rho0) -> unsigned {
+        if (p >= npxO) return kOutOfRange;
+        const int trow = fast_div(p, inv_Qp);
+        const int col = p - mul24(trow, Qp);
+        const int rho = rho0 + trow;
+        if (rho >= rho_end || col >= a.Q) return kOutOfRange;
+        const int n = fast_div(rho, inv_P);
+        const int oj = rho - mul24(n, a.P);
+        return (unsigned)(mul24(mul24(mul24(n, a.Kb), a.P) + oj, a.Q) + col) * 16u;
+    };
+    auto band_lam0 = [&](int rho0) {
+        const int n0 = fast_div(rho0, inv_P);
+        return n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+    };
+    // fp32: stage the input rows and the dO rows of linear output rows [rho0, rho0+TR) into
     // buffer `buf`: wave-level loads of 64 consecutive positions of one plane straight
     // into LDS; positions outside the image, the split or the tensor arrive as zeros.
     auto fetch = [&](int rho0, int buf) {
         unsigned char *ib = lds + buf * bufbytes;
         unsigned char *ob = ib + ibytes;
-        const int n0 = fast_div(rho0, inv_P);
-        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
+        const int lam0 = band_lam0(rho0);
         const int nch_in = (a.LRW + 63) >> 6, nch_out = (npxO + 63) >> 6;
-        auto in_off = [&](int p) -> unsigned {
-            if (p >= a.LRW) return kOutOfRange;
-            const int row = fast_div(p, inv_LW);
-            const int col = p - mul24(row, a.LW);
-            const int lam = lam0 + row;
-            const int n = fast_div(lam, inv_Hs);
-            const int ih = lam - mul24(n, a.Hs) - a.pad;
-            const int iw = col - a.pad;
-            const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-            return ok ? (unsigned)(mul24(mul24(n, a.H) + ih, a.W) + iw) * 16u : kOutOfRange;
-        };
-        auto out_off = [&](int p) -> unsigned {
-            if (p >= npxO) return kOutOfRange;
-            const int trow = fast_div(p, inv_Qp);
-            const int col = p - mul24(trow, Qp);
-            const int rho = rho0 + trow;
-            if (rho >= rho_end || col >= a.Q) return kOutOfRange;
-            const int n = fast_div(rho, inv_P);
-            const int oj = rho - mul24(n, a.P);
-            return (unsigned)(mul24(mul24(mul24(n, a.Kb), a.P) + oj, a.Q) + col) * 16u;
-        };
         // units: the input chunks, then (dO chunk, plane) pairs; equal contiguous shares
         const int total = nch_in + nch_out * NPO;
         const int share = (total + NW - 1) / NW;
@@ -97,17 +113,70 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
         unsigned off = kOutOfRange;
         for (int e = first; e < last; ++e) {
             if (e < nch_in) {
-                load_to_lds_16(rsrc_in, in_off(e * 64 + lane), 0u, ib + e * 64 * 16);
+                load_to_lds_16(rsrc_in, in_off(e * 64 + lane, lam0), 0u, ib + e * 64 * 16);
             } else {
                 const int u = e - nch_in;
                 const int ch = u >> 4, pl = u & 15;
                 if (ch != cur) {
                     cur = ch;
-                    off = out_off(ch * 64 + lane);
+                    off = out_off(ch * 64 + lane, rho0);
                 }
                 load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                                (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
                                ob + (pl * a.PLS_out + ch * 64) * 16);
+            }
+        }
+    };
+    // bf16: the same band through registers.  Thread t takes input positions t, t+512, ...
+    // (8 bytes each: channel slots 0-3) and (dO position, block of 8 channels) pairs
+    // t, t+512, ... (16 bytes each), widens them and writes fp32 planes of 4 channels.
+    constexpr int NI = 8, NO = 4;  // at most 4096 input positions, 256 dO positions x 8 blocks
+    u32x2 ri[BF16IN ? NI : 1];
+    u32x4 ro[BF16IN ? NO : 1];
+    const int kbb0 = kt * (NPO / 2);  // first block of 8 output channels
+    auto fetch_regs = [&](int rho0) {
+        const int lam0 = band_lam0(rho0);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int p = tid + 512 * i;
+            ri[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, in_off(p, lam0), 0u, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NO; ++i) {
+            const int u = tid + 512 * i;  // = block * npxO + position
+            const int blk = fast_div(u, inv_npx), p = u - blk * npxO;
+            unsigned off = out_off(p, rho0);
+            // (the block rides in the per-lane offset: the lanes of a wave differ in it)
+            if (blk < NPO / 2 && kbb0 + blk < a.Kb && off != kOutOfRange)
+                off += (unsigned)(kbb0 + blk) * (unsigned)PQ * 16u;
+            else
+                off = kOutOfRange;
+            ro[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_out, off, 0u, 0);
+        }
+    };
+    auto commit_regs = [&](int buf) {
+        float *bi = reinterpret_cast<float *>(lds + buf * bufbytes);
+        float *bo = reinterpret_cast<float *>(lds + buf * bufbytes + ibytes);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int p = tid + 512 * i;
+            if (p < a.PLS_in - 8) {
+                const f32x4 v = {__uint_as_float(ri[i][0] << 16), __uint_as_float(ri[i][0] & 0xFFFF0000u),
+                                 __uint_as_float(ri[i][1] << 16), __uint_as_float(ri[i][1] & 0xFFFF0000u)};
+                *reinterpret_cast<f32x4 *>(bi + (size_t)p * V) = v;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NO; ++i) {
+            const int u = tid + 512 * i;
+            const int blk = fast_div(u, inv_npx), p = u - blk * npxO;
+            if (blk < NPO / 2) {
+                const f32x4 lo = {__uint_as_float(ro[i][0] << 16), __uint_as_float(ro[i][0] & 0xFFFF0000u),
+                                  __uint_as_float(ro[i][1] << 16), __uint_as_float(ro[i][1] & 0xFFFF0000u)};
+                const f32x4 hi = {__uint_as_float(ro[i][2] << 16), __uint_as_float(ro[i][2] & 0xFFFF0000u),
+                                  __uint_as_float(ro[i][3] << 16), __uint_as_float(ro[i][3] & 0xFFFF0000u)};
+                *reinterpret_cast<f32x4 *>(bo + ((size_t)(2 * blk) * a.PLS_out + p) * V) = lo;
+                *reinterpret_cast<f32x4 *>(bo + ((size_t)(2 * blk + 1) * a.PLS_out + p) * V) = hi;
             }
         }
     };
@@ -124,12 +193,26 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
     // column (s, c) of the B operand = float l32 of the S*4 floats starting at the pixel
     const int b_lane = l32 < S * V ? l32 : 0;
 
-    if (rho_begin < rho_end) fetch(rho_begin, 0);
+    if (rho_begin < rho_end) {
+        if constexpr (BF16IN) {
+            fetch_regs(rho_begin);
+            wait_all_memory();
+            commit_regs(0);
+        } else {
+            fetch(rho_begin, 0);
+        }
+    }
     wait_all_memory();
     __syncthreads();
     int buf = 0;
     for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, buf ^= 1) {
-        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, buf ^ 1);
+        const bool more = rho0 + a.TR < rho_end;
+        if (more) {
+            if constexpr (BF16IN)
+                fetch_regs(rho0 + a.TR);
+            else
+                fetch(rho0 + a.TR, buf ^ 1);
+        }
         const float *ldsI = reinterpret_cast<const float *>(lds + buf * bufbytes);
         const float *ldsO = reinterpret_cast<const float *>(lds + buf * bufbytes + ibytes);
         const int n0 = fast_div(rho0, inv_P);
@@ -155,6 +238,9 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
             }
         }
         wait_all_memory();
+        if constexpr (BF16IN) {
+            if (more) commit_regs(buf ^ 1);
+        }
         __syncthreads();
     }
 
@@ -193,29 +279,37 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
     }
     if (wave_p != 0) return;
 
-    // ---- this split's partial dW: [split][tap][k][c] (one channel block)
-    const size_t copy = (size_t)NTAPS * a.Kp * V;
+    // ---- this split's partial dW: [split][tap][k][c] (one channel block of 4 slots, or of
+    // 8 for bf16 tensors, whose upper four stay zero)
+    constexpr int VB = BF16IN ? 8 : 4;
+    const size_t copy = (size_t)NTAPS * a.Kp * VB;
     float *dst = a.partial + (size_t)split * copy;
     const int s = l32 / V, c = l32 % V;
+    const int kbase = (BF16IN ? kbb0 * 8 : kb0 * V) + wave_k * 32;
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int k = kb0 * V + wave_k * 32 + (e / 4) * 8 + h * 4 + (e % 4);
-            if (s < S && k < a.Kp) dst[((size_t)(r * S + s) * a.Kp + k) * V + c] = acc[r][e];
+            const int k = kbase + (e / 4) * 8 + h * 4 + (e % 4);
+            if (s < S && k < a.Kp) {
+                float *d = dst + ((size_t)(r * S + s) * a.Kp + k) * VB;
+                d[c] = acc[r][e];
+                if (BF16IN) d[4 + c] = 0.0f;
+            }
         }
 }
 
-hipError_t launch_upd_c4(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream)
 {
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
-    if (r == 7 && s == 7) fn = upd_c4_f32_kernel<7, 7>;
-    if (r == 3 && s == 3) fn = upd_c4_f32_kernel<3, 3>;
+    const bool bf = dtype == CONV_BF16;
+    if (r == 7 && s == 7) fn = bf ? upd_c4_f32_kernel<7, 7, true> : upd_c4_f32_kernel<7, 7, false>;
+    if (r == 3 && s == 3) fn = bf ? upd_c4_f32_kernel<3, 3, true> : upd_c4_f32_kernel<3, 3, false>;
     if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attr[2] = {0, 0};
-    size_t &cur = attr[r == 7 ? 0 : 1];
+    static size_t attr[4] = {0, 0, 0, 0};
+    size_t &cur = attr[(r == 7 ? 0 : 1) + (bf ? 2 : 0)];
     if (lds_bytes > cur) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                              hipFuncAttributeMaxDynamicSharedMemorySize,

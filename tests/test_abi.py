@@ -75,8 +75,6 @@ def test_every_table1_layer_is_planned():
     """Planning is host-only: all passes of the benchmark layers must have a kernel."""
     for l in inputs.TABLE_I:
         for dt in (conv.CONV_F32, conv.CONV_BF16):
-            if l.id == 1 and dt == conv.CONV_BF16:
-                continue  # the 3-channel first layer is an fp32 workload only
             h = conv.conv_create(256, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dt)
             for which in (conv.PASS_FWD, conv.PASS_BWD_DATA, conv.PASS_UPD):
                 assert conv.conv_describe(h, which)

@@ -19,7 +19,7 @@ N = 256
 CASES = [(1, conv.CONV_F32), (4, conv.CONV_F32), (8, conv.CONV_F32), (13, conv.CONV_F32), (18, conv.CONV_F32),
          (2, conv.CONV_F32), (6, conv.CONV_F32), (17, conv.CONV_F32), (20, conv.CONV_F32),
          (4, conv.CONV_BF16), (13, conv.CONV_BF16), (18, conv.CONV_BF16), (7, conv.CONV_BF16),
-         (14, conv.CONV_BF16)]
+         (14, conv.CONV_BF16), (1, conv.CONV_BF16)]
 
 
 def _entries(rng, K, C, R, S, count):

@@ -39,7 +39,7 @@ SMALL = [
 ]
 
 
-# few input channels (the first layer of an image network): fp32 only
+# few input channels (the first layer of an image network)
 FEW_CHANNELS = [
     (2, 3, 64, 32, 32, 7, 7, 2, 3),       # conv1 geometry: 7x7, stride 2, pad 3
     (3, 3, 40, 21, 19, 7, 7, 2, 3),       # odd extents, ragged channel tile
@@ -70,17 +70,19 @@ def test_three_passes_match_oracle(shape, dtype):
         L.close()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", FEW_CHANNELS, ids=lambda s: "x".join(map(str, s)))
-def test_few_channel_layers_match_oracle(shape):
+def test_few_channel_layers_match_oracle(shape, dtype):
     """C below the channel block: padded slots, tap pairing in the forward kernel,
-    residue-class decomposition of the strided backward pass, filter-row update."""
+    residue-class decomposition of the strided backward pass, filter-row update
+    (bf16 tensors are widened on their way into LDS there)."""
     N, C, K, H, W, R, S, stride, pad = shape
-    I, Wt, dO = make_inputs(shape, conv.CONV_F32, layer_id=1)
-    L = _layer(shape, conv.CONV_F32)
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=1)
+    L = _layer(shape, dtype)
     try:
-        assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= 1e-5
+        assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
         assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
-                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= 1e-5
+                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
         assert rel_l2(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
     finally:
         L.close()

@@ -55,8 +55,7 @@ def test_table1_plans_fit_the_machine(N, dt):
     for l in inputs.TABLE_I:
         info, plans = _plans((N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad), dt)
         _check(info, plans)
-        if not (l.id == 1 and dt == conv.CONV_BF16):
-            assert all(p is not None for p in plans.values()), (l.id, plans)
+        assert all(p is not None for p in plans.values()), (l.id, plans)
 
 
 def test_seeded_descriptor_sweep_plans_fit_the_machine():
