@@ -47,6 +47,10 @@ def parse():
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: turn two rocprofv3 --pmc counter_collection CSVs "
                          "(FETCH_SIZE, WRITE_SIZE) of a --calib-copy run into a traffic summary")
+    ap.add_argument("--summarize-counters", metavar="COUNTER_CSV",
+                    help="no GPU work: turn a rocprofv3 --pmc counter_collection CSV (GRBM_GUI_ACTIVE, "
+                         "SQ_VALU_MFMA_BUSY_CYCLES, SQ_LDS_BANK_CONFLICT, SQ_LDS_IDX_ACTIVE, SQ_INSTS_LDS, "
+                         "SQ_WAIT_INST_LDS, SQ_WAVE_CYCLES, SQ_BUSY_CYCLES) into a per-kernel table")
     ap.add_argument("--lib-gemm", action="store_true",
                     help="context only, no conv work: time the vendor library's plain GEMM "
                          "(torch.matmul) at the GEMM shapes the layers' forward passes would have "
@@ -92,6 +96,41 @@ def summarize_pmc(fetch_csv, write_csv, out):
         print("%-90s calls %4d  fetch %9.1f MB  write %9.1f MB" % (
             k[:90], r["calls"], r["fetch_bytes"] / 1e6, r["write_bytes"] / 1e6))
     print("scales: fetch %.4f write %.4f (copy kernel: %s)" % (f_scale, w_scale, copy))
+
+
+def summarize_counters(path, out):
+    """Per kernel (averages over its dispatches): matrix-core utilisation = MFMA busy cycles
+    of all SIMDs / (1024 SIMDs x the kernel's duration in clocks; GRBM_GUI_ACTIVE sums the 8
+    XCDs), LDS bank-conflict cycles as a share of the LDS-active cycles, the share of wave
+    time spent waiting for LDS instructions, LDS instructions per dispatch."""
+    import collections
+    import csv
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(path)):
+        acc[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    lines = ["%-88s %6s %9s %8s %10s %9s %11s" % ("kernel", "calls", "clocks", "MFMA %", "LDS confl %",
+                                                 "LDS wait %", "LDS insts")]
+    rows = []
+    for k, v in acc.items():
+        if "convmi" not in k:
+            continue
+        m = {c: sum(x) / len(x) for c, x in v.items()}
+        clocks = m.get("GRBM_GUI_ACTIVE", 0.0) / 8.0
+        if clocks <= 0:
+            continue
+        mfma = 100.0 * m.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / (1024.0 * clocks)
+        idx = m.get("SQ_LDS_IDX_ACTIVE", 0.0)
+        confl = 100.0 * m.get("SQ_LDS_BANK_CONFLICT", 0.0) / idx if idx else 0.0
+        wc = m.get("SQ_WAVE_CYCLES", 0.0)
+        wait = 100.0 * m.get("SQ_WAIT_INST_LDS", 0.0) / wc if wc else 0.0
+        rows.append((clocks * len(v["GRBM_GUI_ACTIVE"]), "%-88s %6d %9.0f %8.1f %10.1f %9.2f %11.0f" % (
+            k[:88], len(v["GRBM_GUI_ACTIVE"]), clocks, mfma, confl, wait, m.get("SQ_INSTS_LDS", 0.0))))
+    lines += [t for _, t in sorted(rows, reverse=True)]
+    text = "\n".join(lines) + "\n"
+    if out:
+        with open(out, "a") as f:
+            f.write(text)
+    print(text, end="")
 
 
 def algorithmic_bytes(l, N, es, which):
@@ -204,6 +243,9 @@ def main():
         return
     if args.summarize_pmc:
         summarize_pmc(args.summarize_pmc[0], args.summarize_pmc[1], args.out)
+        return
+    if args.summarize_counters:
+        summarize_counters(args.summarize_counters, args.out)
         return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
