@@ -17,13 +17,15 @@
 //   * spatial blocking: bands of 64 pixels of the flat pixel list (n, oj, oi) --
 //     no row structure, so no pixel slot is padding, whatever the image extent --
 //     staged through registers into a double-buffered LDS tile, one barrier per
-//     band; the loads of the next band are in flight while this one is consumed;
+//     band; the loads of the next two bands are in flight while this one is consumed;
 //   * parallelisation: grid = (split of the pixel list) x (channel blocks); where
 //     the channel block needs fewer than eight waves the spare waves take
 //     alternate 16-pixel groups into private accumulators, summed through LDS
 //     after the last band ("T copies + reduction" of Section II-I inside the
 //     workgroup).  Every split writes a private partial dW that the reduce kernel
 //     sums in a fixed order.
+#include <type_traits>
+
 #include "conv_internal.h"
 
 namespace convmi {
@@ -96,9 +98,12 @@ __global__ __launch_bounds__(512) void upd_bf16_1x1_kernel(const UpdArgs a)
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, (size_t)a.N * a.Cb * HW * 16);
     const rsrc_t rsrc_out = make_rsrc(a.dout, 0, (size_t)a.N * a.Kb * PQ * 16);
 
-    // Staging map: lane -> pixel `lane` of the band, planes wave + 8*j.
-    u32x4 si[LI], so[LO];
-    auto fetch = [&](int band) {
+    // Staging map: lane -> pixel `lane` of the band, planes wave + 8*j.  Two register sets:
+    // a band's loads are issued two bands ahead of its use (a band is only ~1 us of MFMA
+    // work, less than a trip to memory).
+    u32x4 si[2][LI], so[2][LO];
+    auto fetch = [&](int band, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
         const int g = g_begin + band * BP + lane;
         unsigned off_in = kOutOfRange, off_out = kOutOfRange;
         if (g < g_end) {
@@ -117,24 +122,25 @@ __global__ __launch_bounds__(512) void upd_bf16_1x1_kernel(const UpdArgs a)
         // is wave-uniform)
 #pragma unroll
         for (int j = 0; j < LI; ++j)
-            si[j] = __builtin_amdgcn_raw_buffer_load_b128(
+            si[SET][j] = __builtin_amdgcn_raw_buffer_load_b128(
                 rsrc_in, cb0 + wave + 8 * j < a.Cb ? off_in : kOutOfRange,
                 (unsigned)(cb0 + wave + 8 * j) * (unsigned)HW * 16u, 0);
 #pragma unroll
         for (int j = 0; j < LO; ++j)
-            so[j] = __builtin_amdgcn_raw_buffer_load_b128(
+            so[SET][j] = __builtin_amdgcn_raw_buffer_load_b128(
                 rsrc_out, kb0 + wave + 8 * j < a.Kb ? off_out : kOutOfRange,
                 (unsigned)(kb0 + wave + 8 * j) * (unsigned)PQ * 16u, 0);
     };
-    auto commit = [&](int buf) {
+    auto commit = [&](int buf, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
         unsigned char *bi = lds + buf * BUF;
         unsigned char *bo = bi + IBYTES;
 #pragma unroll
         for (int j = 0; j < LI; ++j)
-            *reinterpret_cast<u32x4 *>(bi + ((wave + 8 * j) * PL + lane) * 16) = si[j];
+            *reinterpret_cast<u32x4 *>(bi + ((wave + 8 * j) * PL + lane) * 16) = si[SET][j];
 #pragma unroll
         for (int j = 0; j < LO; ++j)
-            *reinterpret_cast<u32x4 *>(bo + ((wave + 8 * j) * PL + lane) * 16) = so[j];
+            *reinterpret_cast<u32x4 *>(bo + ((wave + 8 * j) * PL + lane) * 16) = so[SET][j];
     };
 
     f32x16 acc[FC][FK];
@@ -160,15 +166,20 @@ __global__ __launch_bounds__(512) void upd_bf16_1x1_kernel(const UpdArgs a)
         b_lane[j] = IBYTES + ((k / V) * PL + (i16 >> 2) + 8 * h) * 16 + (k % V) * 2;
     }
 
-    if (nbands > 0) {
-        fetch(0);
-        wait_all_memory();
-        commit(0);
-    }
+    // (Every band issues the same loads in the same order, beyond the end of the split with
+    // out-of-range offsets that move no data: with straight-line code the compiler can wait
+    // for exactly the loads a register needs and leaves the newer ones in flight.)
+    using set0_t = std::integral_constant<int, 0>;
+    using set1_t = std::integral_constant<int, 1>;
+    fetch(0, set0_t{});
+    fetch(1, set1_t{});
+    commit(0, set0_t{});
     __syncthreads();
-    for (int band = 0; band < nbands; ++band) {
-        const bool more = band + 1 < nbands;
-        if (more) fetch(band + 1);
+    // One band: LDS buffer band & 1 is consumed; register set band & 1, whose contents are
+    // in LDS already, takes the loads of band + 2; then the loads of band + 1 are awaited
+    // and written to the other LDS buffer.
+    auto do_band = [&](int band, auto set_tag, auto other_tag) {
+        fetch(band + 2, set_tag);
         const unsigned char *buf = lds + (band & 1) * BUF;
         // 16-pixel steps wave_p, wave_p + WP, ... of the band
 #pragma unroll
@@ -195,12 +206,15 @@ __global__ __launch_bounds__(512) void upd_bf16_1x1_kernel(const UpdArgs a)
                         __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j],
                         0, 0, 0);
         }
-        if (more) {
-            wait_all_memory();
-            commit((band + 1) & 1);
-        }
+        commit((band + 1) & 1, other_tag);  // (after the last band: zeros nobody reads)
         __syncthreads();
+    };
+    int band = 0;
+    for (; band + 1 < nbands; band += 2) {
+        do_band(band, set0_t{}, set1_t{});
+        do_band(band + 1, set1_t{}, set0_t{});
     }
+    if (band < nbands) do_band(band, set0_t{}, set1_t{});
 
     // ---- the pixel groups' sums are added up through LDS, group after group in a fixed
     // order, two accumulator tiles per round (all staged bands have been consumed: the
