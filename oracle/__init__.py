@@ -7,7 +7,8 @@ code with the HIP path.
 All tensors are numpy float64 arrays in the logical layouts of Section II of
 the paper: ``I[N,C,H,W]``, ``W[K,C,R,S]``, ``O[N,K,P,Q]``.  The functions are
 the naive loop nests of Algorithms 1, 6 and 8 with zero padding added (see the
-header of ``conv_oracle.c`` for the readings taken).
+header of ``conv_oracle.c`` for the readings taken).  Wherever a function takes
+``pad`` it is one value for both axes or a pair ``(pad_h, pad_w)``.
 """
 from __future__ import annotations
 
@@ -24,7 +25,16 @@ _lib = None
 
 
 class _Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("N", "C", "K", "H", "W", "R", "S", "stride", "pad")]
+    _fields_ = [(n, ctypes.c_int)
+                for n in ("N", "C", "K", "H", "W", "R", "S", "stride", "pad_h", "pad_w")]
+
+
+def _pads(pad):
+    """``pad`` is one value for both axes, or a pair (pad_h, pad_w)."""
+    if isinstance(pad, (tuple, list)):
+        ph, pw = pad
+        return int(ph), int(pw)
+    return int(pad), int(pad)
 
 
 def build(force: bool = False) -> str:
@@ -71,8 +81,8 @@ def _ptr(a):
 
 
 def out_hw(H, W, R, S, stride, pad):
-    """Output extent (P, Q) = floor((H + 2 pad - R)/stride) + 1, likewise Q."""
-    g = _Shape(1, 1, 1, H, W, R, S, stride, pad)
+    """Output extent P = floor((H + 2 pad_h - R)/stride) + 1, Q likewise with pad_w."""
+    g = _Shape(1, 1, 1, H, W, R, S, stride, *_pads(pad))
     lib = _load()
     return lib.oracle_out_h(ctypes.byref(g)), lib.oracle_out_w(ctypes.byref(g))
 
@@ -87,7 +97,7 @@ def fwd(I, Wt, stride=1, pad=0):
     K, C2, R, S = Wt.shape
     if C2 != C:
         raise ValueError("channel mismatch")
-    g = _Shape(N, C, K, H, W, R, S, stride, pad)
+    g = _Shape(N, C, K, H, W, R, S, stride, *_pads(pad))
     P, Q = out_hw(H, W, R, S, stride, pad)
     I = _f64(I, (N, C, H, W))
     Wt = _f64(Wt, (K, C, R, S))
@@ -121,7 +131,7 @@ def bwd_data(dO, Wt, H, W, stride=1, pad=0):
         raise ValueError("channel mismatch")
     if (P, Q) != out_hw(H, W, R, S, stride, pad):
         raise ValueError("dO spatial extent does not match the geometry")
-    g = _Shape(N, C, K, H, W, R, S, stride, pad)
+    g = _Shape(N, C, K, H, W, R, S, stride, *_pads(pad))
     dO = _f64(dO, (N, K, P, Q))
     Wt = _f64(Wt, (K, C, R, S))
     dI = np.empty((N, C, H, W), dtype=np.float64)
@@ -135,7 +145,7 @@ def upd(I, dO, R, S, stride=1, pad=0):
     N2, K, P, Q = dO.shape
     if N2 != N or (P, Q) != out_hw(H, W, R, S, stride, pad):
         raise ValueError("dO does not match the geometry")
-    g = _Shape(N, C, K, H, W, R, S, stride, pad)
+    g = _Shape(N, C, K, H, W, R, S, stride, *_pads(pad))
     I = _f64(I, (N, C, H, W))
     dO = _f64(dO, (N, K, P, Q))
     dW = np.empty((K, C, R, S), dtype=np.float64)
@@ -152,7 +162,7 @@ def upd_entries(I, dO, R, S, stride, pad, entries):
     e = np.ascontiguousarray(entries, dtype=np.int32).reshape(-1, 4)
     if e.size and (e.min() < 0 or (e.max(axis=0) >= np.array([K, C, R, S])).any()):
         raise ValueError("entry index out of range")
-    g = _Shape(N, C, K, H, W, R, S, stride, pad)
+    g = _Shape(N, C, K, H, W, R, S, stride, *_pads(pad))
     I = _f64(I, (N, C, H, W))
     dO = _f64(dO, (N, K, P, Q))
     out = np.empty((e.shape[0],), dtype=np.float64)

@@ -14,12 +14,13 @@
  * O[N][K][P][Q] (row-major, last index fastest), in fp64 throughout.
  *
  * Readings where the paper is silent (all three are the usual conventions):
- *   - zero padding, symmetric, one value for both axes: the input position
- *     touched by output (oj,oi) and tap (r,s) is
- *         ij = stride*oj - pad + r ,  ii = stride*oi - pad + s ,
+ *   - zero padding, symmetric on each axis (one value per axis, so that the
+ *     1xS and Rx1 filters of Inception-style layers can pad along their long
+ *     side only): the input position touched by output (oj,oi) and tap (r,s) is
+ *         ij = stride*oj - pad_h + r ,  ii = stride*oi - pad_w + s ,
  *     and a term whose (ij,ii) falls outside [0,H)x[0,W) is skipped.  The
  *     printed loops are the pad = 0 case.
- *   - P = floor((H + 2 pad - R)/stride) + 1, Q likewise.
+ *   - P = floor((H + 2 pad_h - R)/stride) + 1, Q = floor((W + 2 pad_w - S)/stride) + 1.
  *   - the "+=" targets start from zero: outputs are overwritten.
  *
  * No blocking, no reordering, no vectorisation tricks: loop order is the
@@ -41,7 +42,7 @@
 #endif
 
 typedef struct {
-    int N, C, K, H, W, R, S, stride, pad;
+    int N, C, K, H, W, R, S, stride, pad_h, pad_w;
 } oracle_shape_t;
 
 static int out_extent(int in, int pad, int filt, int stride)
@@ -51,8 +52,8 @@ static int out_extent(int in, int pad, int filt, int stride)
     return span / stride + 1;
 }
 
-int oracle_out_h(const oracle_shape_t *g) { return out_extent(g->H, g->pad, g->R, g->stride); }
-int oracle_out_w(const oracle_shape_t *g) { return out_extent(g->W, g->pad, g->S, g->stride); }
+int oracle_out_h(const oracle_shape_t *g) { return out_extent(g->H, g->pad_h, g->R, g->stride); }
+int oracle_out_w(const oracle_shape_t *g) { return out_extent(g->W, g->pad_w, g->S, g->stride); }
 
 int oracle_num_threads(void)
 {
@@ -67,7 +68,7 @@ int oracle_num_threads(void)
 void oracle_conv_fwd(const oracle_shape_t *g, const double *I, const double *Wt, double *O)
 {
     const int N = g->N, C = g->C, K = g->K, H = g->H, W = g->W, R = g->R, S = g->S;
-    const int stride = g->stride, pad = g->pad;
+    const int stride = g->stride, pad_h = g->pad_h, pad_w = g->pad_w;
     const int P = oracle_out_h(g), Q = oracle_out_w(g);
     memset(O, 0, sizeof(double) * (size_t)N * K * P * Q);
 #pragma omp parallel for schedule(static)
@@ -76,8 +77,8 @@ void oracle_conv_fwd(const oracle_shape_t *g, const double *I, const double *Wt,
             for (int c = 0; c < C; ++c)
                 for (int oj = 0; oj < P; ++oj)
                     for (int oi = 0; oi < Q; ++oi) {
-                        const int ij = stride * oj - pad;
-                        const int ii = stride * oi - pad;
+                        const int ij = stride * oj - pad_h;
+                        const int ii = stride * oi - pad_w;
                         for (int r = 0; r < R; ++r)
                             for (int s = 0; s < S; ++s) {
                                 if (ij + r < 0 || ij + r >= H) continue;
@@ -93,7 +94,7 @@ void oracle_conv_fwd(const oracle_shape_t *g, const double *I, const double *Wt,
 void oracle_conv_bwd_data(const oracle_shape_t *g, const double *dO, const double *Wt, double *dI)
 {
     const int N = g->N, C = g->C, K = g->K, H = g->H, W = g->W, R = g->R, S = g->S;
-    const int stride = g->stride, pad = g->pad;
+    const int stride = g->stride, pad_h = g->pad_h, pad_w = g->pad_w;
     const int P = oracle_out_h(g), Q = oracle_out_w(g);
     memset(dI, 0, sizeof(double) * (size_t)N * C * H * W);
 #pragma omp parallel for schedule(static)
@@ -102,8 +103,8 @@ void oracle_conv_bwd_data(const oracle_shape_t *g, const double *dO, const doubl
             for (int c = 0; c < C; ++c)
                 for (int oj = 0; oj < P; ++oj)
                     for (int oi = 0; oi < Q; ++oi) {
-                        const int ij = stride * oj - pad;
-                        const int ii = stride * oi - pad;
+                        const int ij = stride * oj - pad_h;
+                        const int ii = stride * oi - pad_w;
                         for (int r = 0; r < R; ++r)
                             for (int s = 0; s < S; ++s) {
                                 if (ij + r < 0 || ij + r >= H) continue;
@@ -122,7 +123,7 @@ void oracle_conv_bwd_data(const oracle_shape_t *g, const double *dO, const doubl
 void oracle_conv_upd(const oracle_shape_t *g, const double *I, const double *dO, double *dW)
 {
     const int N = g->N, C = g->C, K = g->K, H = g->H, W = g->W, R = g->R, S = g->S;
-    const int stride = g->stride, pad = g->pad;
+    const int stride = g->stride, pad_h = g->pad_h, pad_w = g->pad_w;
     const int P = oracle_out_h(g), Q = oracle_out_w(g);
     memset(dW, 0, sizeof(double) * (size_t)K * C * R * S);
 #pragma omp parallel for schedule(static)
@@ -131,8 +132,8 @@ void oracle_conv_upd(const oracle_shape_t *g, const double *I, const double *dO,
             for (int c = 0; c < C; ++c)
                 for (int oj = 0; oj < P; ++oj)
                     for (int oi = 0; oi < Q; ++oi) {
-                        const int ij = stride * oj - pad;
-                        const int ii = stride * oi - pad;
+                        const int ij = stride * oj - pad_h;
+                        const int ii = stride * oi - pad_w;
                         for (int r = 0; r < R; ++r)
                             for (int s = 0; s < S; ++s) {
                                 if (ij + r < 0 || ij + r >= H) continue;
@@ -151,7 +152,7 @@ void oracle_conv_upd_entries(const oracle_shape_t *g, const double *I, const dou
                              int n_entries, const int *idx, double *out)
 {
     const int N = g->N, C = g->C, K = g->K, H = g->H, W = g->W;
-    const int stride = g->stride, pad = g->pad;
+    const int stride = g->stride, pad_h = g->pad_h, pad_w = g->pad_w;
     const int P = oracle_out_h(g), Q = oracle_out_w(g);
 #pragma omp parallel for schedule(dynamic, 8)
     for (int e = 0; e < n_entries; ++e) {
@@ -160,8 +161,8 @@ void oracle_conv_upd_entries(const oracle_shape_t *g, const double *I, const dou
         for (int n = 0; n < N; ++n)
             for (int oj = 0; oj < P; ++oj)
                 for (int oi = 0; oi < Q; ++oi) {
-                    const int ij = stride * oj - pad;
-                    const int ii = stride * oi - pad;
+                    const int ij = stride * oj - pad_h;
+                    const int ii = stride * oi - pad_w;
                     if (ij + r < 0 || ij + r >= H) continue;
                     if (ii + s < 0 || ii + s >= W) continue;
                     acc += I[(((size_t)n * C + c) * H + (ij + r)) * W + (ii + s)] *

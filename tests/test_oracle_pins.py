@@ -324,3 +324,91 @@ def test_fused_forward_reduces_to_its_parts():
     only_b = oracle.fwd_fused(I, Wt, 1, 1, bias=b)
     for k in range(K):
         assert np.allclose(only_b[:, k] - plain[:, k], b[k], rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- per-axis padding
+# N, C, K, H, W, R, S, stride, pad_h, pad_w: rectangular filters padded along their long side
+# only (the 1x7 / 7x1 / 1x3 / 3x1 shapes of Inception-style layers), and unequal pads in general.
+RECT = [(2, 3, 4, 7, 9, 1, 7, 1, 0, 3), (2, 2, 3, 9, 7, 7, 1, 1, 3, 0), (1, 3, 2, 8, 8, 1, 3, 1, 0, 1),
+        (2, 2, 2, 6, 7, 3, 1, 2, 1, 0), (1, 2, 3, 9, 9, 5, 5, 1, 2, 2), (2, 2, 2, 8, 10, 3, 5, 2, 0, 2),
+        (1, 2, 2, 7, 6, 3, 3, 1, 2, 0)]
+
+
+def _padded(I, ph, pw):
+    return np.pad(I, ((0, 0), (0, 0), (ph, ph), (pw, pw)))
+
+
+def window_fwd(I, Wt, stride, ph, pw):
+    """Explicitly padded input, then the pad-free window sum per output element."""
+    Ip = _padded(I, ph, pw)
+    K, _, R, S = Wt.shape
+    P = (Ip.shape[2] - R) // stride + 1
+    Q = (Ip.shape[3] - S) // stride + 1
+    O = np.zeros((I.shape[0], K, P, Q))
+    for n, k, p, q in itertools.product(range(I.shape[0]), range(K), range(P), range(Q)):
+        O[n, k, p, q] = np.sum(Ip[n, :, p * stride:p * stride + R, q * stride:q * stride + S] * Wt[k])
+    return O
+
+
+def window_bwd(dO, Wt, H, W, stride, ph, pw):
+    """Scatter every output gradient over its window of a padded dI, then crop the padding."""
+    N, K, P, Q = dO.shape
+    _, C, R, S = Wt.shape
+    dIp = np.zeros((N, C, H + 2 * ph + stride, W + 2 * pw + stride))
+    for n, k, p, q in itertools.product(range(N), range(K), range(P), range(Q)):
+        dIp[n, :, p * stride:p * stride + R, q * stride:q * stride + S] += dO[n, k, p, q] * Wt[k]
+    return dIp[:, :, ph:ph + H, pw:pw + W]
+
+
+def window_upd(I, dO, R, S, stride, ph, pw):
+    Ip = _padded(I, ph, pw)
+    N, K, P, Q = dO.shape
+    dW = np.zeros((K, I.shape[1], R, S))
+    for n, k, p, q in itertools.product(range(N), range(K), range(P), range(Q)):
+        dW[k] += dO[n, k, p, q] * Ip[n, :, p * stride:p * stride + R, q * stride:q * stride + S]
+    return dW
+
+
+@pytest.mark.parametrize("shape", RECT)
+def test_per_axis_padding_against_explicitly_padded_windows(shape, rng):
+    N, C, K, H, W, R, S, stride, ph, pw = shape
+    P, Q = oracle.out_hw(H, W, R, S, stride, (ph, pw))
+    assert P == (H + 2 * ph - R) // stride + 1 and Q == (W + 2 * pw - S) // stride + 1
+    I, Wt, dO = _rand(rng, N, C, H, W), _rand(rng, K, C, R, S), _rand(rng, N, K, P, Q)
+    np.testing.assert_allclose(oracle.fwd(I, Wt, stride, (ph, pw)), window_fwd(I, Wt, stride, ph, pw),
+                               rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.bwd_data(dO, Wt, H, W, stride, (ph, pw)),
+                               window_bwd(dO, Wt, H, W, stride, ph, pw), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.upd(I, dO, R, S, stride, (ph, pw)),
+                               window_upd(I, dO, R, S, stride, ph, pw), rtol=0, atol=1e-13)
+    ent = np.array(list(itertools.product(range(K), range(C), range(R), range(S))))[::3]
+    np.testing.assert_allclose(oracle.upd_entries(I, dO, R, S, stride, (ph, pw), ent),
+                               window_upd(I, dO, R, S, stride, ph, pw)[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]],
+                               atol=1e-13)
+
+
+@pytest.mark.parametrize("shape", RECT)
+def test_per_axis_padding_against_torch_and_adjoints(shape, rng):
+    import torch
+    N, C, K, H, W, R, S, stride, ph, pw = shape
+    P, Q = oracle.out_hw(H, W, R, S, stride, (ph, pw))
+    I, Wt, dO = _rand(rng, N, C, H, W), _rand(rng, K, C, R, S), _rand(rng, N, K, P, Q)
+    x = torch.tensor(I, dtype=torch.float64, requires_grad=True)
+    w = torch.tensor(Wt, dtype=torch.float64, requires_grad=True)
+    y = torch.nn.functional.conv2d(x, w, stride=stride, padding=(ph, pw))
+    assert tuple(y.shape) == (N, K, P, Q)
+    y.backward(torch.tensor(dO, dtype=torch.float64))
+    O = oracle.fwd(I, Wt, stride, (ph, pw))
+    dI = oracle.bwd_data(dO, Wt, H, W, stride, (ph, pw))
+    dW = oracle.upd(I, dO, R, S, stride, (ph, pw))
+    np.testing.assert_allclose(O, y.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(dI, x.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(dW, w.grad.numpy(), atol=1e-12)
+    a = np.vdot(dO, O)
+    assert abs(a - np.vdot(dI, I)) < 1e-12 * max(1.0, abs(a))
+    assert abs(a - np.vdot(dW, Wt)) < 1e-12 * max(1.0, abs(a))
+
+
+def test_equal_pads_as_pair_or_scalar_agree(rng):
+    I, Wt = _rand(rng, 2, 3, 7, 8), _rand(rng, 4, 3, 3, 3)
+    np.testing.assert_array_equal(oracle.fwd(I, Wt, 2, 1), oracle.fwd(I, Wt, 2, (1, 1)))
