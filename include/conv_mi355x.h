@@ -89,6 +89,16 @@ typedef struct conv_plan *conv_handle_t;
 /* Host only: validate the descriptor and plan tile shapes, grids and the
  * weight-update split (everything the paper does once per layer at set-up). */
 conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
+/* As conv_create, with one pad per axis (desc->pad is ignored):
+ *     ij = stride*oj - pad_h + r,  ii = stride*oi - pad_w + s,
+ *     P = floor((H + 2 pad_h - R)/stride) + 1,  Q = floor((W + 2 pad_w - S)/stride) + 1,
+ * the same reading of padding applied to each axis on its own.  It serves the 1xS and
+ * Rx1 filters of Inception-style layers, which pad along their long side only (the paper
+ * reports averages over such a topology next to ResNet-50, Section III).  Everything else
+ * is as for conv_create: CONV_EINVAL for a negative pad or an empty output; a pass whose
+ * filter shape no kernel serves returns CONV_EUNSUPPORTED when it is called. */
+conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
+                               conv_handle_t *out);
 conv_status_t conv_destroy(conv_handle_t h);
 conv_status_t conv_query(conv_handle_t h, conv_info_t *info);
 const char *conv_status_str(conv_status_t s);

@@ -19,7 +19,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_UPD = 0, 1, 2
 CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5)
 
 EXPORTS = (
-    "conv_create", "conv_destroy", "conv_query", "conv_status_str",
+    "conv_create", "conv_create_rect", "conv_destroy", "conv_query", "conv_status_str",
     "conv_fwd", "conv_fwd_fused", "conv_bwd_data", "conv_upd",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
@@ -67,6 +67,8 @@ def load():
     lib = ctypes.CDLL(LIB_PATH)
     vp = ctypes.c_void_p
     lib.conv_create.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(vp)]
+    lib.conv_create_rect.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.POINTER(vp)]
     lib.conv_destroy.argtypes = [vp]
     lib.conv_query.argtypes = [vp, ctypes.POINTER(ConvInfo)]
     lib.conv_status_str.argtypes = [ctypes.c_int]
@@ -113,9 +115,20 @@ def _check(status, what):
 
 
 def conv_create(N, C, K, H, W, R, S, stride, pad, dtype=CONV_F32):
+    """``pad``: one value for both axes, or a pair (pad_h, pad_w) (conv_create_rect)."""
+    if isinstance(pad, (tuple, list)):
+        return conv_create_rect(N, C, K, H, W, R, S, stride, pad[0], pad[1], dtype)
     d = ConvDesc(N, C, K, H, W, R, S, stride, pad, dtype)
     h = ctypes.c_void_p()
     _check(load().conv_create(ctypes.byref(d), ctypes.byref(h)), "conv_create")
+    return h
+
+
+def conv_create_rect(N, C, K, H, W, R, S, stride, pad_h, pad_w, dtype=CONV_F32):
+    d = ConvDesc(N, C, K, H, W, R, S, stride, 0, dtype)
+    h = ctypes.c_void_p()
+    _check(load().conv_create_rect(ctypes.byref(d), int(pad_h), int(pad_w), ctypes.byref(h)),
+           "conv_create_rect")
     return h
 
 

@@ -33,6 +33,7 @@ struct BwdClass {  // one stride-parity class of the generic backward pass
 
 struct conv_plan {
     conv_desc_t d;
+    int pad_h = 0, pad_w = 0;  // zero padding per axis (d.pad is not used past conv_create)
     conv_info_t info;
     IgemmPlan fwd;
     size_t fwd_ws = 0;  // bytes of fp32 partial results if the forward reduction is split
@@ -53,6 +54,7 @@ struct conv_plan {
     UpdRowsVariant urv{};
     int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
+    int upd_row_launches = 1;  // > 1: one launch of a 1 x S kernel per filter row
     UpdArgs ua{};
     size_t upd_lds = 0;
     int upd_grid = 0;
@@ -235,10 +237,11 @@ void plan_bwd(conv_plan *p)
     p->bwd_mode = 0;
     p->n_bwd = 0;
     p->bwd_ws = 0;
-    if (d.stride == 1 && d.pad <= d.R - 1 && d.pad <= d.S - 1) {
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    if (d.stride == 1 && pad_h <= d.R - 1 && pad_w <= d.S - 1) {
         BwdClass &b = p->bwd[0];
-        b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, d.H, d.W, d.R, d.S, 1, d.R - 1 - d.pad,
-                         d.S - 1 - d.pad, d.H, d.W, 1, 0, 0, 0);
+        b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, d.H, d.W, d.R, d.S, 1, d.R - 1 - pad_h,
+                         d.S - 1 - pad_w, d.H, d.W, 1, 0, 0, 0);
         b.x = WtXformArgs{nullptr, nullptr, f.Cb, f.Kb, f.Cp, f.Kp, d.R, d.S, d.R, d.S,
                           1, 0, 0, d.R, d.S};
         b.ws_off = 0;
@@ -249,7 +252,7 @@ void plan_bwd(conv_plan *p)
         }
         return;
     }
-    if (d.R == 1 && d.S == 1 && d.pad == 0) {
+    if (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0) {
         BwdClass &b = p->bwd[0];
         b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, f.Cp, f.P, f.Q, 1, 1, 1, 0, 0, d.H, d.W,
                          d.stride, 0, 0, 1);
@@ -278,14 +281,15 @@ void plan_bwd(conv_plan *p)
         int padU[2] = {0, 0}, win[2] = {1, 1};
         for (int ax = 0; ax < 2; ++ax) {
             const int F = ax == 0 ? d.R : d.S;
+            const int pad_ax = ax == 0 ? pad_h : pad_w;
             int *sub = ax == 0 ? m.rsub : m.ssub, *roff = ax == 0 ? m.roff : m.soff;
             int *sh = ax == 0 ? m.rsh : m.ssh;
             int padc[4];
             for (int pp = 0; pp < st; ++pp) {
-                const int ro = (pp + d.pad) % st;
+                const int ro = (pp + pad_ax) % st;
                 sub[pp] = ro < F ? ceil_div(F - ro, st) : 0;
                 roff[pp] = ro;
-                padc[pp] = std::max(sub[pp], 1) - 1 - (pp + d.pad) / st;
+                padc[pp] = std::max(sub[pp], 1) - 1 - (pp + pad_ax) / st;
                 padU[ax] = pp == 0 ? padc[pp] : std::max(padU[ax], padc[pp]);
             }
             for (int pp = 0; pp < st; ++pp) {
@@ -315,10 +319,10 @@ void plan_bwd(conv_plan *p)
     int n = 0;
     for (int py = 0; py < st; ++py)
         for (int px = 0; px < st; ++px) {
-            const int ry = (py + d.pad) % st, rx = (px + d.pad) % st;
+            const int ry = (py + pad_h) % st, rx = (px + pad_w) % st;
             const int Rsub = ry < d.R ? ceil_div(d.R - ry, st) : 0;
             const int Ssub = rx < d.S ? ceil_div(d.S - rx, st) : 0;
-            const int dy0 = (py + d.pad) / st, dx0 = (px + d.pad) / st;
+            const int dy0 = (py + pad_h) / st, dx0 = (px + pad_w) / st;
             const int Hsub = py < d.H ? ceil_div(d.H - py, st) : 0;
             const int Wsub = px < d.W ? ceil_div(d.W - px, st) : 0;
             if (Hsub == 0 || Wsub == 0) continue;
@@ -356,10 +360,13 @@ void plan_upd(conv_plan *p)
     const conv_info_t &f = p->info;
     p->upd_ok = false;
     p->upd_ws = 0;
-    const bool sampled = (d.R == 1 && d.S == 1 && d.pad == 0);
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
     const bool bf16 = d.dtype == CONV_BF16;
+    const bool square_pad = pad_h == pad_w;  // the filter-specific kernels take one pad
+    p->upd_row_launches = 1;
     p->upd_c4 = false;
-    if (d.C <= 4 && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
+    if (d.C <= 4 && square_pad && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
         // one input channel block: filter-row formulation, eight waves, two LDS buffers
         const int NPO = 16;
         const int Qp = (f.Q + 1) & ~1;
@@ -367,13 +374,14 @@ void plan_upd(conv_plan *p)
         UpdArgs &a = p->ua;
         memset(&a, 0, sizeof(a));
         a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+        a.tap0 = 0; a.ntaps_all = d.R * d.S;
         int TR = std::min(NP, std::max(1, 256 / Qp));
         for (;; --TR) {
             if (TR < 1) return;
             a.Hs = (f.P - 1) * d.stride + d.R;
             // a lane reads up to 8 pixels (32 floats) past the pair's first pixel
-            a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * d.pad);
+            a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * pad_w);
             const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
             a.LRW = LR * a.LW;
             // whole wave-level loads of 64 positions; the dO plane pitch is 1 (mod 8) pixels
@@ -425,7 +433,7 @@ void plan_upd(conv_plan *p)
             UpdArgs &a = p->ua;
             memset(&a, 0, sizeof(a));
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0;
+            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0; a.pad_w = 0; a.tap0 = 0; a.ntaps_all = 1;
             const int n_at = ceil_div(plA, 64), n_bt = ceil_div(plB, 16 * wb);
             a.n_ct = a_is_in ? n_at : n_bt;
             a.n_kt = a_is_in ? n_bt : n_at;
@@ -479,7 +487,7 @@ void plan_upd(conv_plan *p)
             UpdArgs &a = p->ua;
             memset(&a, 0, sizeof(a));
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0;
+            a.R = 1; a.S = 1; a.stride = d.stride; a.pad = 0; a.pad_w = 0; a.tap0 = 0; a.ntaps_all = 1;
             a.n_ct = ceil_div(f.Cp, TC);
             a.n_kt = ceil_div(f.Kp, TK);
             const int tiles = a.n_ct * a.n_kt;
@@ -504,7 +512,7 @@ void plan_upd(conv_plan *p)
         }
     }
     p->upd_rows = false;
-    const bool rows_3x3 = d.R == 3 && d.S == 3 && d.stride == 1;
+    const bool rows_3x3 = d.R == 3 && d.S == 3 && d.stride == 1 && square_pad;
     if (bf16 && (rows_3x3 || sampled)) {
         // bf16 row kernel: 8-pixel runs, filter-column shifts in registers.
         // 3x3: all nine taps in the wave (144 accumulators).  1x1: the layer is bound by
@@ -537,12 +545,13 @@ void plan_upd(conv_plan *p)
             UpdArgs &a = p->ua;
             memset(&a, 0, sizeof(a));
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+            a.tap0 = 0; a.ntaps_all = d.R * d.S;
             a.runs = ceil_div(f.Q, 8);
             const int RP = a.runs * 8;
             a.sampled = sampled ? 1 : 0;
             a.Hs = sampled ? f.P : f.P - 1 + d.R;
-            a.LW = sampled ? RP : std::max(d.W + 2 * d.pad, RP + 4);
+            a.LW = sampled ? RP : std::max(d.W + 2 * pad_w, RP + 4);
             int TR = std::min(NP, 64);
             for (;; --TR) {
                 if (TR < 1) return;
@@ -580,7 +589,7 @@ void plan_upd(conv_plan *p)
         }
     }
     p->upd_bands = false;
-    if (!bf16 && !sampled && d.stride == 1 && upd_f32_bands_exists(d.R, d.S)) {
+    if (!bf16 && !sampled && d.stride == 1 && square_pad && upd_f32_bands_exists(d.R, d.S)) {
         // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
         // bands; the pixel range is split so that one round of workgroups fills the chip.
         const int NPI = 16, NPO = 16;
@@ -589,9 +598,10 @@ void plan_upd(conv_plan *p)
         UpdArgs &a = p->ua;
         memset(&a, 0, sizeof(a));
         a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+        a.tap0 = 0; a.ntaps_all = d.R * d.S;
         a.Hs = (f.P - 1) * d.stride + d.R;
-        a.LW = std::max((f.Q - 1) * d.stride + d.S, d.W + 2 * d.pad);
+        a.LW = std::max((f.Q - 1) * d.stride + d.S, d.W + 2 * pad_w);
         int TR = std::min(NP, 64);
         size_t lds = 0;
         // (rows with an odd number of pixel pairs are shared out whole: even bands)
@@ -629,15 +639,22 @@ void plan_upd(conv_plan *p)
             return;
         }
     }
+    // General kernels.  3x3 and 1x1 in one launch; any other filter with S in {1, 3, 5, 7} as
+    // one launch of the 1 x S kernel per filter row r (run with pad_h - r rows of padding,
+    // writing taps [r*S, (r+1)*S) of the partial copies).
+    const int kR = (d.R == 3 && d.S == 3) ? 3 : 1;  // filter rows one launch serves
     UpdVariant v{};
-    if (d.R == 3 && d.S == 3)
+    if (kR == 3)
         v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
-    else if (d.R == 1 && d.S == 1)
+    else if (d.S == 1)
         v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8}
                  : UpdVariant{CONV_F32, 1, 1, 2, 2, f.Cp > 64 ? 2 : 1, f.Kp > 64 ? 2 : 1, 4, 4};
+    else if (d.S == 3 || d.S == 5 || d.S == 7)
+        v = bf16 ? UpdVariant{CONV_BF16, 1, d.S, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 1, d.S, 2, 2, 1, 1, 1, 4};
     else
         return;
     if (!upd_variant_exists(v)) return;
+    p->upd_row_launches = kR == 3 ? 1 : d.R;
     const int V = f.vlen;
     const int TC = v.wc * v.fc * 32, TK = v.wk * v.fk * 32, NPI = TC / V, NPO = TK / V, NT = 256;
     // fp32 pairs pixels along a row (row pitch rounded up to even, zero padded);
@@ -657,9 +674,9 @@ void plan_upd(conv_plan *p)
         if (TR < 1) return;
         if (sampled) { Hs = f.P; LW = Qp; LR = TR; }
         else {
-            Hs = (f.P - 1) * d.stride + d.R;
-            LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * d.pad);
-            LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, d.R);
+            Hs = (f.P - 1) * d.stride + kR;
+            LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * pad_w);
+            LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, kR);
         }
         if (!bf16 && sampled && (TR * Qp) % 2 != 0 && TR > 1) continue;
         npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
@@ -669,7 +686,8 @@ void plan_upd(conv_plan *p)
     UpdArgs &a = p->ua;
     memset(&a, 0, sizeof(a));
     a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-    a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = d.pad;
+    a.R = kR; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+    a.tap0 = 0; a.ntaps_all = d.R * d.S;
     a.TR = TR;
     a.n_ct = ceil_div(f.Cb, NPI);
     a.n_kt = ceil_div(f.Kb, NPO);
@@ -728,22 +746,31 @@ const char *conv_status_str(conv_status_t s)
 
 conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
 {
+    if (!desc) return CONV_EINVAL;
+    return conv_create_rect(desc, desc->pad, desc->pad, out);
+}
+
+conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w, conv_handle_t *out)
+{
     if (!desc || !out) return CONV_EINVAL;
     *out = nullptr;
     const conv_desc_t &d = *desc;
     if (d.N < 1 || d.C < 1 || d.K < 1 || d.H < 1 || d.W < 1 || d.R < 1 || d.S < 1 || d.stride < 1 ||
-        d.pad < 0)
+        pad_h < 0 || pad_w < 0)
         return CONV_EINVAL;
     if (d.dtype != CONV_F32 && d.dtype != CONV_BF16) return CONV_EINVAL;
-    if (d.H + 2 * d.pad < d.R || d.W + 2 * d.pad < d.S) return CONV_EINVAL;
+    if (d.H + 2 * pad_h < d.R || d.W + 2 * pad_w < d.S) return CONV_EINVAL;
 
     conv_plan *p = new (std::nothrow) conv_plan();
     if (!p) return CONV_EINVAL;
     p->d = d;
+    p->d.pad = pad_h;
+    p->pad_h = pad_h;
+    p->pad_w = pad_w;
     conv_info_t &f = p->info;
     memset(&f, 0, sizeof(f));
-    f.P = (d.H + 2 * d.pad - d.R) / d.stride + 1;
-    f.Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
+    f.P = (d.H + 2 * pad_h - d.R) / d.stride + 1;
+    f.Q = (d.W + 2 * pad_w - d.S) / d.stride + 1;
     f.vlen = vlen_of(d.dtype);
     f.Cb = ceil_div(d.C, f.vlen);
     f.Kb = ceil_div(d.K, f.vlen);
@@ -755,8 +782,8 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
     f.wt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * es;
     f.dwt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * sizeof(float);
 
-    p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, d.pad,
-                        d.pad, f.P, f.Q, 1, 0, 0, 0);
+    p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, pad_h,
+                        pad_w, f.P, f.Q, 1, 0, 0, 0);
     // Few tiles and a long reduction (small minibatch, inference): split the reduction
     // over more workgroups, fp32 partial results in the workspace, summed in a fixed order.
     p->fwd_ws = 0;
@@ -870,12 +897,24 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     a.in = in;
     a.dout = dout;
     a.partial = static_cast<float *>(ws);
-    const hipError_t e = h->upd_flat_bf16 ? launch_upd_bf16_1x1(h->urv, a, h->upd_grid, s)
-                         : h->upd_flat ? launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s)
-                         : h->upd_c4   ? launch_upd_c4(h->d.dtype, h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
-                         : h->upd_rows ? launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s)
-                         : h->upd_bands ? launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s)
-                                       : launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+    hipError_t e = hipSuccess;
+    if (h->upd_flat_bf16)
+        e = launch_upd_bf16_1x1(h->urv, a, h->upd_grid, s);
+    else if (h->upd_flat)
+        e = launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s);
+    else if (h->upd_c4)
+        e = launch_upd_c4(h->d.dtype, h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
+    else if (h->upd_rows)
+        e = launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s);
+    else if (h->upd_bands)
+        e = launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
+    else
+        for (int r = 0; r < h->upd_row_launches && e == hipSuccess; ++r) {
+            // (one launch, or filter row r of a taller filter: its taps, its share of the padding)
+            a.pad = h->pad_h - r;
+            a.tap0 = r * h->d.S * (h->upd_row_launches > 1 ? 1 : 0);
+            e = launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+        }
     if (e != hipSuccess) return CONV_ELAUNCH;
     if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
                           h->upd_copies, s) != hipSuccess)
@@ -998,10 +1037,10 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         }
         snprintf(buf, buflen,
                  "upd dt=%d RS=%dx%d waves=%dx%d frags=%dx%d TR=%d splits=%d rows/split=%d "
-                 "tiles=%dx%d grid=%d lds=%zu",
+                 "tiles=%dx%d grid=%d lds=%zu launches=%d",
                  h->uv.dtype, h->uv.r, h->uv.s, h->uv.wc, h->uv.wk, h->uv.fc, h->uv.fk, h->ua.TR,
                  h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt, h->upd_grid,
-                 h->upd_lds);
+                 h->upd_lds, h->upd_row_launches);
         return CONV_OK;
     }
     return CONV_EINVAL;

@@ -116,7 +116,13 @@ struct UpdArgs {
     const void *in;
     const void *dout;
     float *partial;  // [splits][Cb][R][S][Kp][v] fp32
-    int N, Cb, H, W, Kb, Kp, P, Q, R, S, stride, pad;
+    int N, Cb, H, W, Kb, Kp, P, Q, R, S, stride;
+    int pad;         // rows of zero padding above the image (may be negative: a launch that
+                     // serves one filter row r of a taller filter runs with pad_h - r)
+    int pad_w;       // columns of zero padding left of the image
+    // The launch computes taps [tap0, tap0 + R*S) of a filter with ntaps_all taps: the
+    // partial dW copies have the full filter's layout [Cb][ntaps_all][Kp][v].
+    int tap0, ntaps_all;
     int TR;          // linear output rows per staged step
     int rows_per_split;
     int splits;

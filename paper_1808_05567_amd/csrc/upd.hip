@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad;
-                iw = col - a.pad;
+                iw = col - a.pad_w;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             const u32x4 *ip = static_cast<const u32x4 *>(a.in) +
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
     }
 
     // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
-    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    const size_t copy = (size_t)a.Cb * a.ntaps_all * a.Kp * V;
     float *dst = a.partial + (size_t)split * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
                     if (cb >= a.Cb) continue;
                     f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
                                acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
-                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V) = v;
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * a.ntaps_all + a.tap0 + t) * a.Kp + k) * V) = v;
                 }
             }
 }
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                     const int lam = lam0 + row;
                     n = lam / a.Hs;
                     ih = lam - n * a.Hs - a.pad;
-                    iw = col - a.pad;
+                    iw = col - a.pad_w;
                     ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
                 }
                 ok = ok && (cb0 + pl) < a.Cb;
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
         }
     }
 
-    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    const size_t copy = (size_t)a.Cb * a.ntaps_all * a.Kp * V;
     float *dst = a.partial + (size_t)split * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                     if (cb >= a.Cb) continue;
                     f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
                                acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
-                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V +
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * a.ntaps_all + a.tap0 + t) * a.Kp + k) * V +
                                                4 * h) = v;
                 }
             }
@@ -577,6 +577,13 @@ static UpdEntry g_upd[] = {
     UPD_F32_ENTRY(1, 1, 2, 2, 4, 4, true),
     UPD_BF16_ENTRY(3, 3, 2, 2, 1, 2, 8, 8),
     UPD_BF16_ENTRY(1, 1, 2, 2, 2, 2, 8, 8),
+    // one filter row of a 1 x S, R x 1 or R x S filter per launch
+    UPD_F32_ENTRY(1, 3, 1, 1, 1, 4, false),
+    UPD_F32_ENTRY(1, 5, 1, 1, 1, 4, false),
+    UPD_F32_ENTRY(1, 7, 1, 1, 1, 4, false),
+    UPD_BF16_ENTRY(1, 3, 2, 2, 1, 2, 8, 8),
+    UPD_BF16_ENTRY(1, 5, 2, 2, 1, 2, 8, 8),
+    UPD_BF16_ENTRY(1, 7, 2, 2, 1, 2, 8, 8),
 };
 
 static UpdEntry *find_upd(const UpdVariant &v)

@@ -134,7 +134,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad;
-                iw = col - a.pad;
+                iw = col - a.pad_w;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;

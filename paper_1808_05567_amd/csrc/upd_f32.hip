@@ -83,7 +83,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
             const int lam = lam0 + row;
             const int n = fast_div(lam, inv_Hs);
             const int ih = lam - n * a.Hs - a.pad;
-            const int iw = col - a.pad;
+            const int iw = col - a.pad_w;
             const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
         };

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
         const int lam = lam0 + row;
         const int n = fast_div(lam, inv_Hs);
         const int ih = lam - mul24(n, a.Hs) - a.pad;
-        const int iw = col - a.pad;
+        const int iw = col - a.pad_w;
         const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
         return ok ? (unsigned)(mul24(mul24(n, a.H) + ih, a.W) + iw) * 16u : kOutOfRange;
     };

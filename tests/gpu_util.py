@@ -15,8 +15,9 @@ def rel_l2(got, ref):
 
 def make_inputs(shape, dtype, layer_id=0, seed=0):
     N, C, K, H, W, R, S, stride, pad = shape
-    P = (H + 2 * pad - R) // stride + 1
-    Q = (W + 2 * pad - S) // stride + 1
+    ph, pw = pad if isinstance(pad, (tuple, list)) else (pad, pad)
+    P = (H + 2 * ph - R) // stride + 1
+    Q = (W + 2 * pw - S) // stride + 1
     I = inputs.gen_input(N, C, H, W, layer_id, seed)
     Wt = inputs.gen_weights(K, C, R, S, layer_id, seed)
     dO = inputs.gen_outgrad(N, K, P, Q, layer_id, seed)

@@ -47,6 +47,26 @@ FEW_CHANNELS = [
     (2, 4, 72, 9, 9, 3, 3, 1, 1),
 ]
 
+# rectangular filters and padding given per axis (pad_h, pad_w): the factorised 7x7 and 3x3
+# filters and the 5x5 filter of Inception-style networks
+RECT = [
+    (2, 32, 48, 17, 17, 1, 7, 1, (0, 3)),
+    (2, 32, 48, 17, 17, 7, 1, 1, (3, 0)),
+    (3, 48, 40, 8, 8, 1, 3, 1, (0, 1)),
+    (3, 48, 40, 8, 8, 3, 1, 1, (1, 0)),
+    (2, 48, 64, 12, 12, 5, 5, 1, 2),
+    (2, 160, 192, 17, 17, 1, 7, 1, (0, 3)),   # ragged 128-row channel tiles, several channel steps
+    (2, 192, 160, 17, 17, 7, 1, 1, (3, 0)),
+    (2, 20, 24, 9, 11, 1, 7, 1, (0, 3)),      # odd numbers of channel blocks
+    (2, 20, 24, 11, 9, 7, 1, 1, (3, 0)),
+    (2, 16, 24, 10, 9, 3, 3, 1, (2, 0)),      # 3x3 with unequal pads (the dual pads are 0 and 2)
+    (2, 16, 24, 10, 9, 3, 3, 1, (0, 1)),
+    (2, 24, 16, 9, 11, 3, 3, 2, (1, 0)),      # ... strided: residue classes with per-axis pads
+    (2, 24, 32, 13, 13, 3, 3, 2, 0),          # unpadded stride-2 3x3 (grid-reduction layers)
+    (2, 12, 16, 9, 9, 1, 7, 1, 0),            # rectangular, unpadded: the output narrows
+    (2, 12, 16, 9, 9, 7, 1, 1, (0, 2)),       # padding along the short side only
+]
+
 
 def _layer(shape, dtype):
     return conv.ConvLayer(*shape, dtype=dtype)
@@ -66,6 +86,24 @@ def test_three_passes_match_oracle(shape, dtype):
         got = run_pass(L, "upd", I=I, dO=dO)
         # weight gradients are fp32 for both dtypes; bf16 products are exact in fp32
         assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+    finally:
+        L.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", RECT, ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
+def test_rectangular_filters_match_oracle(shape, dtype):
+    """1xS, Rx1 and 5x5 filters, padding per axis: forward, backward by data through the
+    flipped filter with the dual pads (R-1-pad_h, S-1-pad_w), weight update one filter
+    row per launch."""
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=30 + R + 2 * S)
+    L = _layer(shape, dtype)
+    try:
+        assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        assert rel_l2(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
     finally:
         L.close()
 
