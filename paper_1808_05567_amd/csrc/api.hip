@@ -55,6 +55,8 @@ struct conv_plan {
     int upd_copies = 0;    // partial dW copies the reduce kernel sums
     UpdVariant uv{};
     int upd_row_launches = 1;  // > 1: one launch of a 1 x S kernel per filter row
+    int upd_strips = 1;        // general kernels: strips of output columns, one launch each
+    int upd_strip_w = 0;       // ... their width (the last may be narrower)
     UpdArgs ua{};
     size_t upd_lds = 0;
     int upd_grid = 0;
@@ -365,56 +367,61 @@ void plan_upd(conv_plan *p)
     const bool bf16 = d.dtype == CONV_BF16;
     const bool square_pad = pad_h == pad_w;  // the filter-specific kernels take one pad
     p->upd_row_launches = 1;
+    p->upd_strips = 1;
     p->upd_c4 = false;
     if (d.C <= 4 && square_pad && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
-        // one input channel block: filter-row formulation, eight waves, two LDS buffers
-        const int NPO = 16;
-        const int Qp = (f.Q + 1) & ~1;
-        const int NP = d.N * f.P;
-        UpdArgs &a = p->ua;
-        memset(&a, 0, sizeof(a));
-        a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
-        a.tap0 = 0; a.ntaps_all = d.R * d.S;
-        int TR = std::min(NP, std::max(1, 256 / Qp));
-        for (;; --TR) {
-            if (TR < 1) return;
-            a.Hs = (f.P - 1) * d.stride + d.R;
-            // a lane reads up to 8 pixels (32 floats) past the pair's first pixel
-            a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * pad_w);
-            const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
-            a.LRW = LR * a.LW;
-            // whole wave-level loads of 64 positions; the dO plane pitch is 1 (mod 8) pixels
-            a.PLS_in = ceil_div(a.LRW, 64) * 64 + 8;
-            a.PLS_out = ceil_div(TR * Qp, 64) * 64 + 1;
-            p->upd_lds = 2 * ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
-            if (p->upd_lds <= (size_t)kMaxLds) break;
-        }
-        a.TR = TR;
-        a.n_ct = 1;
-        a.n_kt = ceil_div(f.Kp, 64);  // 64 output channels per workgroup
-        // (bf16 tensors: the staged band must fit the kernel's register staging)
-        if (bf16 && (a.PLS_in - 8 > 8 * 512 || 8 * TR * Qp > 4 * 512)) return;
-        // one workgroup per CU, one round
-        int splits = std::max(1, 256 / a.n_kt);
-        splits = std::max(splits, ceil_div(NP * f.Q, 1 << 17));  // chains of at most 2^15 pixels
-        int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
-        splits = ceil_div(NP, rps);
-        a.rows_per_split = rps;
-        a.splits = splits;
-        a.sampled = 0;
-        a.total = a.n_kt * splits;
-        a.per_xcd = ceil_div(a.total, 8);
-        if ((double)(d.N + 1) * std::max(a.Hs, std::max(d.H, f.P * f.Kb)) >= 8.0e6 ||
-            a.LRW >= (1 << 22) || 8 * TR * Qp >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
-            (double)d.N * f.Kp * f.P * f.Q * 4 >= 4.0e9)
-            return;
-        p->upd_grid = a.per_xcd * 8;
-        p->upd_copies = splits;
-        p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
-        p->upd_c4 = true;
-        p->upd_ok = true;
-        return;
+        // (a plan that does not fit leaves the layer to the general kernels)
+        auto plan_c4 = [&]() -> bool {
+            // one input channel block: filter-row formulation, eight waves, two LDS buffers
+            const int NPO = 16;
+            const int Qp = (f.Q + 1) & ~1;
+            const int NP = d.N * f.P;
+            UpdArgs &a = p->ua;
+            memset(&a, 0, sizeof(a));
+            a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+            a.tap0 = 0; a.ntaps_all = d.R * d.S;
+            int TR = std::min(NP, std::max(1, 256 / Qp));
+            for (;; --TR) {
+                if (TR < 1) return false;
+                a.Hs = (f.P - 1) * d.stride + d.R;
+                // a lane reads up to 8 pixels (32 floats) past the pair's first pixel
+                a.LW = std::max((Qp - 1) * d.stride + 8, d.W + 2 * pad_w);
+                const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
+                a.LRW = LR * a.LW;
+                // whole wave-level loads of 64 positions; the dO plane pitch is 1 (mod 8) pixels
+                a.PLS_in = ceil_div(a.LRW, 64) * 64 + 8;
+                a.PLS_out = ceil_div(TR * Qp, 64) * 64 + 1;
+                p->upd_lds = 2 * ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+                if (p->upd_lds <= (size_t)kMaxLds) break;
+            }
+            a.TR = TR;
+            a.n_ct = 1;
+            a.n_kt = ceil_div(f.Kp, 64);  // 64 output channels per workgroup
+            // (bf16 tensors: the staged band must fit the kernel's register staging)
+            if (bf16 && (a.PLS_in - 8 > 8 * 512 || 8 * TR * Qp > 4 * 512)) return false;
+            // one workgroup per CU, one round
+            int splits = std::max(1, 256 / a.n_kt);
+            splits = std::max(splits, ceil_div(NP * f.Q, 1 << 17));  // chains of at most 2^15 pixels
+            int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+            splits = ceil_div(NP, rps);
+            a.rows_per_split = rps;
+            a.splits = splits;
+            a.sampled = 0;
+            a.total = a.n_kt * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            if ((double)(d.N + 1) * std::max(a.Hs, std::max(d.H, f.P * f.Kb)) >= 8.0e6 ||
+                a.LRW >= (1 << 22) || 8 * TR * Qp >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
+                (double)d.N * f.Kp * f.P * f.Q * 4 >= 4.0e9)
+                return false;
+            p->upd_grid = a.per_xcd * 8;
+            p->upd_copies = splits;
+            p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+            p->upd_c4 = true;
+            p->upd_ok = true;
+            return true;
+        };
+        if (plan_c4()) return;
     }
     p->upd_flat = false;
     if (!bf16 && sampled) {
@@ -554,7 +561,7 @@ void plan_upd(conv_plan *p)
             a.LW = sampled ? RP : std::max(d.W + 2 * pad_w, RP + 4);
             int TR = std::min(NP, 64);
             for (;; --TR) {
-                if (TR < 1) return;
+                if (TR < 1) break;  // rows too wide for two bands in the LDS: the general kernel
                 const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
                 a.LRW = LR * a.LW;
                 a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
@@ -562,29 +569,31 @@ void plan_upd(conv_plan *p)
                 p->upd_lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
                 if (p->upd_lds <= (size_t)kMaxLds) break;
             }
-            a.TR = TR;
-            a.n_ct = ceil_div(f.Cb, NPI);
-            a.n_kt = ceil_div(f.Kb, NPO);
-            const int tiles = a.n_ct * a.n_kt;
-            // one workgroup per CU
-            int splits = std::max(1, (256 + tiles / 2) / tiles);
-            splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
-            int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
-            splits = ceil_div(NP, rps);
-            a.rows_per_split = rps;
-            a.splits = splits;
-            a.total = tiles * splits;
-            a.per_xcd = ceil_div(a.total, 8);
-            if ((double)(d.N + 1) * std::max(a.Hs, f.P) < 4.0e6 &&
-                (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 &&
-                (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
-                p->urv = rv;
-                p->upd_grid = a.per_xcd * 8;
-                p->upd_copies = splits * rv.wp;
-                p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
-                p->upd_rows = true;
-                p->upd_ok = true;
-                return;
+            if (TR >= 1) {
+                a.TR = TR;
+                a.n_ct = ceil_div(f.Cb, NPI);
+                a.n_kt = ceil_div(f.Kb, NPO);
+                const int tiles = a.n_ct * a.n_kt;
+                // one workgroup per CU
+                int splits = std::max(1, (256 + tiles / 2) / tiles);
+                splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
+                int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+                splits = ceil_div(NP, rps);
+                a.rows_per_split = rps;
+                a.splits = splits;
+                a.total = tiles * splits;
+                a.per_xcd = ceil_div(a.total, 8);
+                if ((double)(d.N + 1) * std::max(a.Hs, f.P) < 4.0e6 &&
+                    (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 &&
+                    (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
+                    p->urv = rv;
+                    p->upd_grid = a.per_xcd * 8;
+                    p->upd_copies = splits * rv.wp;
+                    p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+                    p->upd_rows = true;
+                    p->upd_ok = true;
+                    return;
+                }
             }
         }
     }
@@ -661,33 +670,45 @@ void plan_upd(conv_plan *p)
     // bf16 walks the band's pixels linearly in steps of 16.
     // (1x1 without padding: both bands are flat pixel lists, no row padding needed,
     // but a band must hold an even number of pixels)
-    const int Qp = (bf16 || sampled) ? f.Q : ((f.Q + 1) & ~1);
+    // A row wider than a band can hold is cut into strips of Qs output columns, one launch
+    // (and one set of partial copies) per strip.
+    int Qs = f.Q, Qp = 0, n_strips = 1;
     const int NP = d.N * f.P;
     // staged pixels a band may hold (see the staging maps of the two kernels)
     const int max_px_in = bf16 ? v.ppt_in * NT / NPI : NT / v.ppt_in;
     const int max_px_out = bf16 ? v.ppt_out * NT / NPO : NT / v.ppt_out;
     // fp32 tiles are kept below half of the LDS so that two workgroups share a CU
     const size_t lds_cap = bf16 ? (size_t)kMaxLds : (size_t)kMaxLds / 2;
-    int TR = std::min(NP, std::max(1, max_px_out / Qp));
-    int Hs = 0, LW = 0, LR = 0, npxO = 0;
-    for (;; --TR) {
-        if (TR < 1) return;
-        if (sampled) { Hs = f.P; LW = Qp; LR = TR; }
-        else {
-            Hs = (f.P - 1) * d.stride + kR;
-            LW = std::max((Qp - 1) * d.stride + d.S, d.W + 2 * pad_w);
-            LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, kR);
+    int TR = 0, Hs = 0, LW = 0, LR = 0, npxO = 0;
+    for (n_strips = 1; TR < 1; ++n_strips) {
+        if (n_strips > f.Q) return;
+        Qs = ceil_div(f.Q, n_strips);
+        if (ceil_div(f.Q, Qs) != n_strips) continue;
+        const int q_last = f.Q - (n_strips - 1) * Qs;  // width of the last strip
+        Qp = (bf16 || sampled) ? Qs : ((Qs + 1) & ~1);
+        for (TR = std::min(NP, std::max(1, max_px_out / Qp)); TR >= 1; --TR) {
+            if (sampled) { Hs = f.P; LW = Qp; LR = TR; }
+            else {
+                Hs = (f.P - 1) * d.stride + kR;
+                LW = (Qp - 1) * d.stride + d.S;
+                if (n_strips == 1) LW = std::max(LW, d.W + 2 * pad_w);
+                LR = max_band_rows(d.N, f.P, TR, Hs, d.stride, kR);
+            }
+            if (!bf16 && sampled && TR > 1 && ((TR * Qp) % 2 != 0 || (TR * q_last) % 2 != 0)) continue;
+            npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
+            const size_t lds_est = ((size_t)NPI * (LR * LW + 16) + (size_t)NPO * (npxO + 16)) * 16;
+            if (LR * LW <= max_px_in && npxO <= max_px_out && lds_est <= lds_cap) break;
         }
-        if (!bf16 && sampled && (TR * Qp) % 2 != 0 && TR > 1) continue;
-        npxO = bf16 ? ceil_div(TR * Qp, 16) * 16 : TR * Qp;
-        const size_t lds_est = ((size_t)NPI * (LR * LW + 16) + (size_t)NPO * (npxO + 16)) * 16;
-        if (LR * LW <= max_px_in && npxO <= max_px_out && lds_est <= lds_cap) break;
+        if (TR >= 1) break;
     }
+    p->upd_strips = n_strips;
+    p->upd_strip_w = Qs;
     UpdArgs &a = p->ua;
     memset(&a, 0, sizeof(a));
-    a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+    a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = Qs;
     a.R = kR; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
     a.tap0 = 0; a.ntaps_all = d.R * d.S;
+    a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
     a.TR = TR;
     a.n_ct = ceil_div(f.Cb, NPI);
     a.n_kt = ceil_div(f.Kb, NPO);
@@ -721,8 +742,8 @@ void plan_upd(conv_plan *p)
     p->upd_lds = ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
     if (p->upd_lds > (size_t)kMaxLds) return;
     p->upd_grid = a.per_xcd * 8;
-    p->upd_copies = splits;
-    p->upd_ws = (size_t)splits * f.dwt_bytes;
+    p->upd_copies = splits * n_strips;
+    p->upd_ws = (size_t)splits * n_strips * f.dwt_bytes;
     p->upd_ok = true;
 }
 
@@ -909,11 +930,24 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     else if (h->upd_bands)
         e = launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
     else
-        for (int r = 0; r < h->upd_row_launches && e == hipSuccess; ++r) {
-            // (one launch, or filter row r of a taller filter: its taps, its share of the padding)
-            a.pad = h->pad_h - r;
-            a.tap0 = r * h->d.S * (h->upd_row_launches > 1 ? 1 : 0);
-            e = launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+        for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
+            // strip st of the output columns; a narrower last strip of a flat (unpadded
+            // 1x1) band is its own row pitch
+            a.q0 = st * h->upd_strip_w;
+            a.Q = std::min(h->upd_strip_w, h->info.Q - a.q0);
+            a.copy0 = st * a.splits;
+            if (a.sampled) {
+                a.Qp = a.Q;
+                a.LW = a.Q;
+                a.LRW = a.TR * a.Q;
+            }
+            for (int r = 0; r < h->upd_row_launches && e == hipSuccess; ++r) {
+                // (one launch, or filter row r of a taller filter: its taps, its share of
+                // the padding)
+                a.pad = h->pad_h - r;
+                a.tap0 = r * h->d.S * (h->upd_row_launches > 1 ? 1 : 0);
+                e = launch_upd(h->uv, a, h->upd_lds, h->upd_grid, s);
+            }
         }
     if (e != hipSuccess) return CONV_ELAUNCH;
     if (launch_upd_reduce(a.partial, static_cast<float *>(dwt), h->info.dwt_bytes / sizeof(float),
@@ -1040,7 +1074,7 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
                  "tiles=%dx%d grid=%d lds=%zu launches=%d",
                  h->uv.dtype, h->uv.r, h->uv.s, h->uv.wc, h->uv.wk, h->uv.fc, h->uv.fk, h->ua.TR,
                  h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt, h->upd_grid,
-                 h->upd_lds, h->upd_row_launches);
+                 h->upd_lds, h->upd_row_launches * h->upd_strips);
         return CONV_OK;
     }
     return CONV_EINVAL;

@@ -123,6 +123,10 @@ struct UpdArgs {
     // The launch computes taps [tap0, tap0 + R*S) of a filter with ntaps_all taps: the
     // partial dW copies have the full filter's layout [Cb][ntaps_all][Kp][v].
     int tap0, ntaps_all;
+    // General kernels only: the launch serves the strip of Q output columns that starts at
+    // column q0 of rows Qpitch wide (image columns from q0*stride on), and writes partial
+    // copies copy0 .. copy0+splits-1.  One strip: q0 = 0, Qpitch = Q, copy0 = 0.
+    int q0, Qpitch, copy0;
     int TR;          // linear output rows per staged step
     int rows_per_split;
     int splits;

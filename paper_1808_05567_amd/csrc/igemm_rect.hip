@@ -33,6 +33,10 @@ static IgemmEntry g_rect[] = {
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 2, 5, 5, 3),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 2, 4, 1, 5, 5, 3),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 5, 5, 3),
+    // strided 3x3 over an image with a single channel block and rows as wide as the tile
+    // (the first layer of a 299 x 299 network): four staged positions per thread
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 3, 3, 4),
+    IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 3, 3, 4),
 };
 
 IgemmEntry *igemm_rect_entries(int *count)

@@ -68,8 +68,12 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
     const int rho_end = min(NP, rho_begin + a.rows_per_split);
     const int Qp = a.Qp;  // dO row pitch in the staged band
     const int npxO = a.TR * Qp;
+    // A flat (unpadded 1x1) band is walked in pixel pairs: one with an odd number of
+    // pixels is staged with one more, zero, pixel in both tensors.
+    const int npxO_st = a.sampled ? (npxO + 1) & ~1 : npxO;
+    const int lrw_st = a.sampled ? (a.LRW + 1) & ~1 : a.LRW;
     const int HW = a.H * a.W;
-    const int PQ = a.P * a.Q;
+    const int PQ = a.P * a.Qpitch;
     const int ls = a.sampled ? 1 : a.stride;
     const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
     const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P;
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
     auto fetch = [&](int rho0) {
         const int n0 = fast_div(rho0, inv_P);
         const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * a.stride;
-        if (pi < a.LRW) {
+        if (pi < lrw_st) {
             const int row = fast_div(pi, inv_LW);
             const int col = pi - row * a.LW;
             int n, ih, iw;
@@ -93,13 +97,13 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
                 const int rho = rho0 + row;
                 n = fast_div(rho, inv_P);
                 ih = (rho - n * a.P) * a.stride;
-                iw = col * a.stride;
-                ok = rho < rho_end && col < a.Q;
+                iw = (a.q0 + col) * a.stride;
+                ok = row < a.TR && rho < rho_end && col < a.Q;
             } else {
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad;
-                iw = col - a.pad_w;
+                iw = col + a.q0 * a.stride - a.pad_w;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             const u32x4 *ip = static_cast<const u32x4 *>(a.in) +
@@ -108,27 +112,27 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
             for (int j = 0; j < NPI / GI; ++j)
                 vi[j] = (ok && cb0 + gi + GI * j < a.Cb) ? ip[(size_t)j * GI * HW] : zero4;
         }
-        if (po < npxO) {
+        if (po < npxO_st) {
             const int trow = fast_div(po, inv_Qp);
             const int col = po - trow * Qp;
             const int rho = rho0 + trow;
             const int n = fast_div(rho, inv_P);
             const int oj = rho - n * a.P;
-            const bool ok = rho < rho_end && col < a.Q;
+            const bool ok = trow < a.TR && rho < rho_end && col < a.Q;
             const u32x4 *op = static_cast<const u32x4 *>(a.dout) +
-                              ((size_t)(n * a.Kb + kb0 + go) * a.P + oj) * a.Q + col;
+                              ((size_t)(n * a.Kb + kb0 + go) * a.P + oj) * a.Qpitch + a.q0 + col;
 #pragma unroll
             for (int j = 0; j < NPO / GO; ++j)
                 vo[j] = (ok && kb0 + go + GO * j < a.Kb) ? op[(size_t)j * GO * PQ] : zero4;
         }
     };
     auto commit = [&]() {
-        if (pi < a.LRW) {
+        if (pi < lrw_st) {
 #pragma unroll
             for (int j = 0; j < NPI / GI; ++j)
                 *reinterpret_cast<u32x4 *>(ldsI + ((size_t)(gi + GI * j) * a.PLS_in + pi) * V) = vi[j];
         }
-        if (po < npxO) {
+        if (po < npxO_st) {
 #pragma unroll
             for (int j = 0; j < NPO / GO; ++j)
                 *reinterpret_cast<u32x4 *>(ldsO + ((size_t)(go + GO * j) * a.PLS_out + po) * V) = vo[j];
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
 
     // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
     const size_t copy = (size_t)a.Cb * a.ntaps_all * a.Kp * V;
-    float *dst = a.partial + (size_t)split * copy;
+    float *dst = a.partial + (size_t)(a.copy0 + split) * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
 #pragma unroll
@@ -346,13 +350,13 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                     const int rho = rho0 + row;
                     n = rho / a.P;
                     ih = (rho - n * a.P) * a.stride;
-                    iw = col * a.stride;
+                    iw = (a.q0 + col) * a.stride;
                     ok = rho < rho_end && col < a.Q;
                 } else {
                     const int lam = lam0 + row;
                     n = lam / a.Hs;
                     ih = lam - n * a.Hs - a.pad;
-                    iw = col - a.pad_w;
+                    iw = col + a.q0 * a.stride - a.pad_w;
                     ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
                 }
                 ok = ok && (cb0 + pl) < a.Cb;
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                 if (trow < a.TR && rho < rho_end && (kb0 + pl) < a.Kb) {
                     const int n = rho / a.P;
                     const int oj = rho - n * a.P;
-                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Q + col];
+                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Qpitch + a.q0 + col];
                 }
             }
             oreg[i] = v;
@@ -495,7 +499,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
     }
 
     const size_t copy = (size_t)a.Cb * a.ntaps_all * a.Kp * V;
-    float *dst = a.partial + (size_t)split * copy;
+    float *dst = a.partial + (size_t)(a.copy0 + split) * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
 #pragma unroll

@@ -30,10 +30,28 @@ def _entries(rng, K, C, R, S, count):
     return np.concatenate([np.array(corners), e]).astype(np.int32)
 
 
+# Inception-v3 shapes (ids of inputs.INCEPTION_V3): the first layer (299 wide, stride 2,
+# unpadded), a 147-wide 3x3 (update in column strips), 5x5, unpadded stride-2 3x3, 1x7 / 7x1
+# at 160 and 192 channels, 1x3 / 3x1
+V3_CASES = [(1, conv.CONV_F32), (3, conv.CONV_F32), (13, conv.CONV_F32), (16, conv.CONV_F32),
+            (29, conv.CONV_F32), (30, conv.CONV_F32), (41, conv.CONV_F32), (42, conv.CONV_F32),
+            (2, conv.CONV_BF16), (13, conv.CONV_BF16), (25, conv.CONV_BF16), (26, conv.CONV_BF16),
+            (42, conv.CONV_BF16)]
+
+
 @pytest.mark.parametrize("lid,dtype", CASES,
                          ids=["L%d-%s" % (l, "bf16" if d else "f32") for l, d in CASES])
 def test_table1_layer_at_n256(lid, dtype):
-    l = inputs.layer(lid)
+    _layer_at_n256(inputs.layer(lid), lid, dtype)
+
+
+@pytest.mark.parametrize("lid,dtype", V3_CASES,
+                         ids=["V3L%d-%s" % (l, "bf16" if d else "f32") for l, d in V3_CASES])
+def test_inception_v3_layer_at_n256(lid, dtype):
+    _layer_at_n256(inputs.layer(lid, "inception_v3"), 100 + lid, dtype)
+
+
+def _layer_at_n256(l, lid, dtype):
     print("layer", lid, "dtype", dtype, flush=True)
     I = inputs.gen_input(N, l.C, l.H, l.W, lid)
     Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
@@ -53,7 +71,7 @@ def test_table1_layer_at_n256(lid, dtype):
         assert rel_l2(got[imgs], ref) <= TOL[dtype]
         assert np.isfinite(got).all()
         got = run_pass(L, "upd", I=I, dO=dO)
-        ent = _entries(rng, l.K, l.C, l.R, l.S, 256 if lid == 1 else 1024)
+        ent = _entries(rng, l.K, l.C, l.R, l.S, 256 if l.H > 200 else 1024)
         ref = oracle.upd_entries(I.astype(np.float64), dO.astype(np.float64), l.R, l.S,
                                  l.stride, l.pad, ent)
         assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5

@@ -36,6 +36,7 @@ SMALL = [
     (2, 100, 320, 7, 5, 1, 1, 1, 0),      # out x in, 128-channel narrow side, bands cross images
     (1, 512, 256, 6, 6, 1, 1, 2, 0),      # 256 x 256 tile, stride 2
     (2, 256, 36, 5, 5, 1, 1, 1, 0),       # narrow side below 64 channels, a single ragged band
+    (2, 16, 24, 3, 37, 1, 1, 1, 0),       # one odd row per flat band: staged with a zero pixel
 ]
 
 
@@ -65,6 +66,12 @@ RECT = [
     (2, 24, 32, 13, 13, 3, 3, 2, 0),          # unpadded stride-2 3x3 (grid-reduction layers)
     (2, 12, 16, 9, 9, 1, 7, 1, 0),            # rectangular, unpadded: the output narrows
     (2, 12, 16, 9, 9, 7, 1, 1, (0, 2)),       # padding along the short side only
+    # rows wider than one band of the general update kernels: strips of output columns
+    (1, 8, 16, 5, 150, 3, 3, 1, 1),
+    (1, 16, 24, 4, 75, 1, 1, 1, 0),           # flat bands, a narrower last strip
+    (1, 8, 8, 6, 140, 1, 7, 1, (0, 3)),
+    (1, 8, 16, 7, 141, 3, 3, 2, 0),
+    (2, 3, 32, 37, 301, 3, 3, 2, 0),          # first layer of a 299-wide network, widened
 ]
 
 
