@@ -37,7 +37,12 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--layers", default="4,8,13,18")
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "inception_v3"],
+                    help="layer table: ResNet-50 (Table I of the paper) or the distinct "
+                         "Inception-v3 shapes (second workload; --layers all)")
+    ap.add_argument("--layers", default=None,
+                    help="comma-separated layer ids of the workload, or 'all' "
+                         "(default: 4,8,13,18 for resnet50, all for inception_v3)")
     ap.add_argument("--batch", type=int, default=N_BATCH)
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -141,13 +146,13 @@ def algorithmic_bytes(l, N, es, which):
     return i + o + w * (4 if which == "upd" else es)
 
 
-def make_layers(ids, N, dtype_name):
+def make_layers(ids, N, dtype_name, workload="resnet50"):
     import torch
     from paper_1808_05567_amd import conv, inputs
     dt = conv.CONV_BF16 if dtype_name == "bf16" else conv.CONV_F32
     out = []
     for lid in ids:
-        l = inputs.layer(lid)
+        l = inputs.layer(lid, workload)
         L = conv.ConvLayer(N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dt)
         I = inputs.gen_input(N, l.C, l.H, l.W, lid)
         Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
@@ -177,7 +182,7 @@ def launch(L, which):
         conv.conv_upd(L.h, L.x_blk, L.dy_blk, L.dwt_blk, L.ws)
 
 
-def cpu_baseline(ids, n_cpu):
+def cpu_baseline(ids, n_cpu, workload="resnet50"):
     """The fp64 oracle, as it stands, on a bounded sample: the same layers and
     passes at a reduced minibatch (per-image cost does not depend on N)."""
     import numpy as np
@@ -186,7 +191,7 @@ def cpu_baseline(ids, n_cpu):
     flops = 0.0
     secs = 0.0
     for lid in ids:
-        l = inputs.layer(lid)
+        l = inputs.layer(lid, workload)
         I = inputs.gen_input(n_cpu, l.C, l.H, l.W, lid).astype(np.float64)
         Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid).astype(np.float64)
         dO = inputs.gen_outgrad(n_cpu, l.K, l.P, l.Q, lid).astype(np.float64)
@@ -254,10 +259,15 @@ def main():
     import torch
     from paper_1808_05567_amd import inputs
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    ids = [int(x) for x in args.layers.split(",")]
+    if args.layers is None:
+        args.layers = "4,8,13,18" if args.workload == "resnet50" else "all"
+    if args.layers == "all":
+        ids = [l.id for l in inputs.WORKLOADS[args.workload]]
+    else:
+        ids = [int(x) for x in args.layers.split(",")]
     N = args.batch
     es = 2 if args.dtype == "bf16" else 4
-    layers = make_layers(ids, N, args.dtype)
+    layers = make_layers(ids, N, args.dtype, args.workload)
     passes = ("fwd", "bwd", "upd")
 
     def step():
@@ -309,7 +319,8 @@ def main():
     # same workload (see profiles/); null when the workload differs or none exists.
     traffic = None
     tf_path = os.path.join(ROOT, "profiles", TRAFFIC_FILE[args.dtype])
-    if args.layers == "4,8,13,18" and N == N_BATCH and os.path.exists(tf_path):
+    if (args.workload == "resnet50" and args.layers == "4,8,13,18" and N == N_BATCH
+            and os.path.exists(tf_path)):
         try:
             ks = json.load(open(tf_path))["kernels"]
             ig = [(v["calls"], v["fetch_bytes"] + v["write_bytes"]) for k, v in ks.items()
@@ -326,12 +337,15 @@ def main():
                     for w in passes}}
 
     result = {
-        "metric": "conv TFLOPS per pass (fwd/bwd/upd) on ResNet-50 layers; % of MFMA peak",
+        "metric": "conv TFLOPS per pass (fwd/bwd/upd) on %s layers; %% of MFMA peak" % (
+            "ResNet-50" if args.workload == "resnet50" else "Inception-v3"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "ResNet-50 Table I layers %s, N=%d, %s, fwd+bwd_data+upd per layer, "
-                               "blocked tensors resident in HBM" % (args.layers, N, args.dtype),
+        "config": {"workload": "%s layers %s, N=%d, %s, fwd+bwd_data+upd per layer, "
+                               "blocked tensors resident in HBM" % (
+                                   "ResNet-50 Table I" if args.workload == "resnet50"
+                                   else "Inception-v3 (distinct shapes)", args.layers, N, args.dtype),
                    "pct_of_mfma_peak": round(100 * value / peak, 2)},
         "roofline": roofline,
     }
@@ -393,7 +407,8 @@ def main():
                              "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
             del nchw, nkpq
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        path = os.path.join(ROOT, "gpurun_out", "layers_%s.json" % args.dtype)
+        path = os.path.join(ROOT, "gpurun_out", "layers_%s%s.json" % (
+            "" if args.workload == "resnet50" else args.workload + "_", args.dtype))
         with open(path, "w") as f:
             json.dump(rows, f, indent=1)
         for r in rows:
@@ -404,7 +419,7 @@ def main():
     for _, L in layers:
         L.close()
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(ids, args.cpu_batch)
+        result["cpu_baseline"] = cpu_baseline(ids, args.cpu_batch, args.workload)
     print(json.dumps(result), flush=True)
 
 

@@ -651,19 +651,23 @@ void plan_upd(conv_plan *p)
     // General kernels.  3x3 and 1x1 in one launch; any other filter with S in {1, 3, 5, 7} as
     // one launch of the 1 x S kernel per filter row r (run with pad_h - r rows of padding,
     // writing taps [r*S, (r+1)*S) of the partial copies).
-    const int kR = (d.R == 3 && d.S == 3) ? 3 : 1;  // filter rows one launch serves
+    // filter rows one launch serves: all of them for 3x3 and the one-column filters
+    const bool whole = (d.R == 3 && d.S == 3) || (d.S == 1 && (d.R == 3 || d.R == 7));
+    const int kR = whole ? d.R : 1;
     UpdVariant v{};
-    if (kR == 3)
-        v = bf16 ? UpdVariant{CONV_BF16, 3, 3, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 3, 3, 2, 2, 1, 1, 1, 4};
-    else if (d.S == 1)
+    if (d.R == 1 && d.S == 1)
         v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8}
                  : UpdVariant{CONV_F32, 1, 1, 2, 2, f.Cp > 64 ? 2 : 1, f.Kp > 64 ? 2 : 1, 4, 4};
-    else if (d.S == 3 || d.S == 5 || d.S == 7)
-        v = bf16 ? UpdVariant{CONV_BF16, 1, d.S, 2, 2, 1, 2, 8, 8} : UpdVariant{CONV_F32, 1, d.S, 2, 2, 1, 1, 1, 4};
+    else if (whole || d.S == 1 || d.S == 3 || d.S == 5 || d.S == 7)
+        v = bf16 ? UpdVariant{CONV_BF16, kR, d.S, 2, 2, 1, 2, 8, 8}
+                 : UpdVariant{CONV_F32, kR, d.S, 2, 2, 1, 1, 1, 4};
     else
         return;
+    if (kR == 1 && d.S == 1 && d.R > 1)  // (other one-column filters: the 1x1 kernel per row)
+        v = bf16 ? UpdVariant{CONV_BF16, 1, 1, 2, 2, 2, 2, 8, 8}
+                 : UpdVariant{CONV_F32, 1, 1, 2, 2, f.Cp > 64 ? 2 : 1, f.Kp > 64 ? 2 : 1, 4, 4};
     if (!upd_variant_exists(v)) return;
-    p->upd_row_launches = kR == 3 ? 1 : d.R;
+    p->upd_row_launches = kR == d.R ? 1 : d.R;
     const int V = f.vlen;
     const int TC = v.wc * v.fc * 32, TK = v.wk * v.fk * 32, NPI = TC / V, NPO = TK / V, NT = 256;
     // fp32 pairs pixels along a row (row pitch rounded up to even, zero padded);

@@ -37,6 +37,10 @@ static IgemmEntry g_rect[] = {
     // (the first layer of a 299 x 299 network): four staged positions per thread
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 1, 3, 3, 4),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 1, 3, 3, 4),
+    // strided 3x3 of the grid-reduction modules: the input tile of a full pixel tile
+    // spans twice its rows and columns
+    IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 3, 3, 4),
+    IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 3, 3, 4),
 };
 
 IgemmEntry *igemm_rect_entries(int *count)

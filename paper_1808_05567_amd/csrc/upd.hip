@@ -588,6 +588,11 @@ static UpdEntry g_upd[] = {
     UPD_BF16_ENTRY(1, 3, 2, 2, 1, 2, 8, 8),
     UPD_BF16_ENTRY(1, 5, 2, 2, 1, 2, 8, 8),
     UPD_BF16_ENTRY(1, 7, 2, 2, 1, 2, 8, 8),
+    // tall one-column filters, all rows in one launch
+    UPD_F32_ENTRY(3, 1, 1, 1, 1, 4, false),
+    UPD_F32_ENTRY(7, 1, 1, 1, 1, 4, false),
+    UPD_BF16_ENTRY(3, 1, 2, 2, 1, 2, 8, 8),
+    UPD_BF16_ENTRY(7, 1, 2, 2, 1, 2, 8, 8),
 };
 
 static UpdEntry *find_upd(const UpdVariant &v)
