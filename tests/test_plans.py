@@ -50,6 +50,30 @@ def _check(info, plans):
 
 
 @pytest.mark.parametrize("dt", [conv.CONV_F32, conv.CONV_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 256])
+def test_inception_v3_plans_fit_the_machine(N, dt):
+    """Every shape of the second workload has all three passes (rectangular filters, per-axis
+    padding, unpadded stride 2, rows wider than an update band)."""
+    assert len(inputs.INCEPTION_V3) == 43
+    for l in inputs.INCEPTION_V3:
+        info, plans = _plans((N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad), dt)
+        _check(info, plans)
+        assert all(p is not None for p in plans.values()), (l.id, plans)
+        assert (info.P, info.Q) == (l.P, l.Q)
+
+
+def test_update_of_tall_filters_and_wide_rows():
+    def upd(shape, dt=conv.CONV_F32):
+        return _plans(shape, dt)[1][conv.PASS_UPD]
+    # 7x1 and 1x7: one launch; 5x5: one launch per filter row
+    assert "RS=7x1" in upd((4, 64, 64, 17, 17, 7, 1, 1, (3, 0))) and "launches=1" in upd((4, 64, 64, 17, 17, 7, 1, 1, (3, 0)))
+    assert "launches=1" in upd((4, 64, 64, 17, 17, 1, 7, 1, (0, 3)))
+    assert "RS=1x5" in upd((4, 48, 64, 35, 35, 5, 5, 1, 2)) and "launches=5" in upd((4, 48, 64, 35, 35, 5, 5, 1, 2))
+    # 147-wide rows: three strips of 49 output columns in fp32
+    assert "launches=3" in upd((2, 32, 64, 147, 147, 3, 3, 1, 1))
+
+
+@pytest.mark.parametrize("dt", [conv.CONV_F32, conv.CONV_BF16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("N", [1, 2, 256])
 def test_table1_plans_fit_the_machine(N, dt):
     for l in inputs.TABLE_I:
