@@ -446,7 +446,7 @@ void plan_upd(conv_plan *p)
             a.n_kt = a_is_in ? n_bt : n_at;
             const int tiles = n_at * n_bt;
             const int np = (int)npix;
-            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            int splits = std::max(1, 256 / tiles);
             splits = std::max(splits, ceil_div(np, 1 << 16));
             const int pps = ceil_div(ceil_div(np, splits), BP) * BP;
             splits = ceil_div(np, pps);
@@ -499,7 +499,7 @@ void plan_upd(conv_plan *p)
             a.n_kt = ceil_div(f.Kp, TK);
             const int tiles = a.n_ct * a.n_kt;
             const int np = d.N * f.P * f.Q;
-            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            int splits = std::max(1, 256 / tiles);
             splits = std::max(splits, ceil_div(np, 1 << 16));
             const int pps = ceil_div(ceil_div(np, splits), BP) * BP;
             splits = ceil_div(np, pps);
@@ -519,21 +519,24 @@ void plan_upd(conv_plan *p)
         }
     }
     p->upd_rows = false;
-    const bool rows_3x3 = d.R == 3 && d.S == 3 && d.stride == 1 && square_pad;
-    if (bf16 && (rows_3x3 || sampled)) {
+    // (this kernel takes the two pads separately)
+    const bool rows_rs = d.stride == 1 && !sampled &&
+                         ((d.R == 3 && d.S == 3) || (d.R == 1 && (d.S == 3 || d.S == 7)) ||
+                          (d.S == 1 && (d.R == 3 || d.R == 7)));
+    if (bf16 && (rows_rs || sampled)) {
         // bf16 row kernel: 8-pixel runs, filter-column shifts in registers.
         // 3x3: all nine taps in the wave (144 accumulators).  1x1: the layer is bound by
         // HBM, so take the channel tile that re-reads the least (input is read once per
         // output-channel tile, dO once per input-channel tile), then the smaller tile.
-        static const UpdRowsVariant k3x3[2] = {{3, 3, 2, 4, 1, 1, 1}, {3, 3, 2, 2, 2, 1, 1}};
         static const UpdRowsVariant k1x1[7] = {{1, 1, 2, 2, 2, 1, 1}, {1, 1, 2, 4, 1, 1, 1},
                                                {1, 1, 4, 2, 1, 1, 1}, {1, 1, 2, 4, 1, 1, 2},
                                                {1, 1, 4, 2, 1, 2, 1}, {1, 1, 2, 4, 1, 2, 2},
                                                {1, 1, 4, 2, 1, 2, 2}};
         UpdRowsVariant rv{};
         bool have = false;
-        if (rows_3x3) {
-            rv = f.Kp <= 64 ? k3x3[1] : k3x3[0];
+        if (rows_rs) {
+            // 64 x 128 channels, or 64 x 64 with two wave groups along the pixels
+            rv = f.Kp <= 64 ? UpdRowsVariant{d.R, d.S, 2, 2, 2, 1, 1} : UpdRowsVariant{d.R, d.S, 2, 4, 1, 1, 1};
             have = upd_rows_variant_exists(rv);
         } else {
             double best = 0;
@@ -554,28 +557,38 @@ void plan_upd(conv_plan *p)
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
             a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
             a.tap0 = 0; a.ntaps_all = d.R * d.S;
-            a.runs = ceil_div(f.Q, 8);
-            const int RP = a.runs * 8;
+            a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
             a.sampled = sampled ? 1 : 0;
             a.Hs = sampled ? f.P : f.P - 1 + d.R;
-            a.LW = sampled ? RP : std::max(d.W + 2 * pad_w, RP + 4);
-            int TR = std::min(NP, 64);
-            for (;; --TR) {
-                if (TR < 1) break;  // rows too wide for two bands in the LDS: the general kernel
-                const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
-                a.LRW = LR * a.LW;
-                a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
-                a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
-                p->upd_lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
-                if (p->upd_lds <= (size_t)kMaxLds) break;
+            // a lane reads a window of whole 4-pixel groups covering a run and its S-1 shifts
+            const int win = (8 + d.S - 1 + 3) / 4 * 4;
+            // Rows too wide for two bands in the LDS are cut into up to four strips of whole
+            // 8-pixel runs, one launch per strip; beyond that the general kernel takes over.
+            int TR = 0, Qs = f.Q;
+            for (int ns = 1; ns <= 4 && TR < 1; ++ns) {
+                Qs = ns == 1 ? f.Q : ceil_div(ceil_div(f.Q, ns), 8) * 8;
+                if (ns > 1 && (sampled || Qs * (ns - 1) >= f.Q)) continue;
+                a.runs = ceil_div(Qs, 8);
+                const int RP = a.runs * 8;
+                a.LW = sampled ? RP : std::max(ns == 1 ? d.W + 2 * pad_w : 0, RP + win - 8);
+                for (TR = std::min(NP, 64); TR >= 1; --TR) {
+                    const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
+                    a.LRW = LR * a.LW;
+                    a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
+                    a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
+                    p->upd_lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+                    if (p->upd_lds <= (size_t)kMaxLds) break;
+                }
             }
+            const int n_strips = ceil_div(f.Q, Qs);
+            a.Q = Qs;
             if (TR >= 1) {
                 a.TR = TR;
                 a.n_ct = ceil_div(f.Cb, NPI);
                 a.n_kt = ceil_div(f.Kb, NPO);
                 const int tiles = a.n_ct * a.n_kt;
                 // one workgroup per CU
-                int splits = std::max(1, (256 + tiles / 2) / tiles);
+                int splits = std::max(1, 256 / tiles);
                 splits = std::max(splits, ceil_div(NP * f.Q, 1 << 15));
                 int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
                 splits = ceil_div(NP, rps);
@@ -588,8 +601,10 @@ void plan_upd(conv_plan *p)
                     (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
                     p->urv = rv;
                     p->upd_grid = a.per_xcd * 8;
-                    p->upd_copies = splits * rv.wp;
+                    p->upd_copies = splits * rv.wp * n_strips;
                     p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+                    p->upd_strips = n_strips;
+                    p->upd_strip_w = Qs;
                     p->upd_rows = true;
                     p->upd_ok = true;
                     return;
@@ -610,27 +625,38 @@ void plan_upd(conv_plan *p)
         a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
         a.tap0 = 0; a.ntaps_all = d.R * d.S;
         a.Hs = (f.P - 1) * d.stride + d.R;
-        a.LW = std::max((f.Q - 1) * d.stride + d.S, d.W + 2 * pad_w);
-        int TR = std::min(NP, 64);
+        a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
         size_t lds = 0;
-        // (rows with an odd number of pixel pairs are shared out whole: even bands)
-        const bool by_rows = (f.Q % 2 == 0) && ((f.Q / 2) % 2 == 1);
-        for (;; --TR) {
-            if (TR < 1) break;
-            if (by_rows && TR > 1 && (TR & 1)) continue;
-            const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
-            a.LRW = LR * a.LW;
-            a.PLS_in = ceil_div(a.LRW, 64) * 64 + 1;
-            a.PLS_out = ceil_div(TR * f.Q + 1, 64) * 64 + 1;  // the band and one zero pixel
-            lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
-            if (lds <= (size_t)kMaxLds) break;
+        // Rows too wide for two bands in the LDS are cut into up to four strips of output
+        // columns, one launch per strip; beyond that the general kernel takes over.
+        int TR = 0, Qs = f.Q, n_strips = 1;
+        for (n_strips = 1; n_strips <= 4; ++n_strips) {
+            Qs = ceil_div(f.Q, n_strips);
+            if (ceil_div(f.Q, Qs) != n_strips) continue;
+            const int q_last = f.Q - (n_strips - 1) * Qs;
+            a.LW = (Qs - 1) * d.stride + d.S;
+            if (n_strips == 1) a.LW = std::max(a.LW, d.W + 2 * pad_w);
+            // (rows with an odd number of pixel pairs are shared out whole: even bands)
+            auto rows_whole = [](int q) { return (q % 2 == 0) && ((q / 2) % 2 == 1); };
+            const bool by_rows = rows_whole(Qs) || rows_whole(q_last);
+            for (TR = std::min(NP, 64); TR >= 1; --TR) {
+                if (by_rows && TR > 1 && (TR & 1)) continue;
+                const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
+                a.LRW = LR * a.LW;
+                a.PLS_in = ceil_div(a.LRW, 64) * 64 + 1;
+                a.PLS_out = ceil_div(TR * Qs + 1, 64) * 64 + 1;  // the band and one zero pixel
+                lds = 2 * ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+                if (lds <= (size_t)kMaxLds) break;
+            }
+            if (TR >= 1) break;
         }
+        a.Q = Qs;
         if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22)) {
             a.TR = TR;
             a.n_ct = ceil_div(f.Cb, NPI);
             a.n_kt = ceil_div(f.Kb, NPO);
             const int tiles = a.n_ct * a.n_kt;
-            int splits = std::max(1, (256 + tiles / 2) / tiles);
+            int splits = std::max(1, 256 / tiles);
             splits = std::max(splits, ceil_div(NP * f.Q, 1 << 16));  // chains of at most 2^15 pixels
             int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
             splits = ceil_div(NP, rps);
@@ -641,8 +667,10 @@ void plan_upd(conv_plan *p)
             a.per_xcd = ceil_div(a.total, 8);
             p->upd_lds = std::max(lds, xch);
             p->upd_grid = a.per_xcd * 8;
-            p->upd_copies = splits;
-            p->upd_ws = (size_t)splits * f.dwt_bytes;
+            p->upd_copies = splits * n_strips;
+            p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+            p->upd_strips = n_strips;
+            p->upd_strip_w = Qs;
             p->upd_bands = true;
             p->upd_ok = true;
             return;
@@ -930,9 +958,19 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     else if (h->upd_c4)
         e = launch_upd_c4(h->d.dtype, h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
     else if (h->upd_rows)
-        e = launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s);
+        for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
+            a.q0 = st * h->upd_strip_w;
+            a.Q = std::min(h->upd_strip_w, h->info.Q - a.q0);
+            a.copy0 = st * a.splits * h->urv.wp;
+            e = launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s);
+        }
     else if (h->upd_bands)
-        e = launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
+        for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
+            a.q0 = st * h->upd_strip_w;
+            a.Q = std::min(h->upd_strip_w, h->info.Q - a.q0);
+            a.copy0 = st * a.splits;
+            e = launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
+        }
     else
         for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
             // strip st of the output columns; a narrower last strip of a flat (unpadded
@@ -1059,18 +1097,18 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         if (h->upd_rows) {
             snprintf(buf, buflen,
                      "upd_rows dt=1 RS=%dx%d waves=%dx%dx%d frags=%dx%d TR=%d runs=%d splits=%d "
-                     "rows/split=%d tiles=%dx%d grid=%d lds=%zu",
+                     "rows/split=%d tiles=%dx%d grid=%d lds=%zu launches=%d",
                      h->d.R, h->d.S, h->urv.wc, h->urv.wk, h->urv.wp, h->urv.fc, h->urv.fk, h->ua.TR,
                      h->ua.runs, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt,
-                     h->upd_grid, h->upd_lds);
+                     h->upd_grid, h->upd_lds, h->upd_strips);
             return CONV_OK;
         }
         if (h->upd_bands) {
             snprintf(buf, buflen,
                      "upd_bands dt=0 RS=%dx%d waves=2x2x2 frags=1x1 TR=%d splits=%d rows/split=%d "
-                     "tiles=%dx%d grid=%d lds=%zu",
+                     "tiles=%dx%d grid=%d lds=%zu launches=%d",
                      h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct,
-                     h->ua.n_kt, h->upd_grid, h->upd_lds);
+                     h->ua.n_kt, h->upd_grid, h->upd_lds, h->upd_strips);
             return CONV_OK;
         }
         snprintf(buf, buflen,

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     // Two waves per SIMD need the accumulators to fit the 256 AGPRs outright:
     // above that the compiler shuttles tiles between register files every step.
     static_assert(NTAPS * FC * FK * 16 <= 256, "accumulators must fit the AGPRs");
-    static_assert(S <= 5, "window of three 4-pixel reads");
+    static_assert(S <= 9, "window of at most four 4-pixel reads");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int ibytes = NPI * a.PLS_in * 16;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     const int rho_end = min(NP, rho_begin + a.rows_per_split);
     const int RP = a.runs * 8;              // staged dO row pitch (pixels), zero padded beyond Q
     const int npxO = a.TR * RP + 8;         // ... plus one all-zero run for idle lane halves
-    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const int HW = a.H * a.W, PQ = a.P * a.Qpitch;
     const int gap = a.sampled ? 0 : a.Hs - a.P;  // staged rows between images (stride 1)
     const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
     const float inv_RP = 1.0f / (float)RP, inv_P = 1.0f / (float)a.P;
@@ -128,13 +128,13 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 const int rho = rho0 + row;
                 n = fast_div(rho, inv_P);
                 ih = (rho - n * a.P) * a.stride;
-                iw = col * a.stride;
+                iw = (a.q0 + col) * a.stride;
                 ok = rho < rho_end && col < a.Q;
             } else {
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad;
-                iw = col - a.pad_w;
+                iw = col + a.q0 - a.pad_w;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
             if (rho >= rho_end || col >= a.Q) return kOutOfRange;
             const int n = fast_div(rho, inv_P);
             const int oj = rho - n * a.P;
-            return (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
+            return (unsigned)((n * a.Kb * a.P + oj) * a.Qpitch + a.q0 + col) * 16u;
         };
         // (channel blocks beyond the tensor are out of range as a whole: zeros)
         auto load_in = [&](int pl, int p0, unsigned off) {
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 
     // ---- this (split, pixel wave)'s partial dW tile: [copy][cb][tap][k][c%8]
     const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
-    float *dst = a.partial + ((size_t)split * WP + wave_p) * copy;
+    float *dst = a.partial + ((size_t)a.copy0 + (size_t)split * WP + wave_p) * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
 #pragma unroll
@@ -323,6 +323,15 @@ struct UpdRowsEntry {
 static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(3, 3, 2, 4, 1, 1, 1),  // 64 x 128 channels, eight waves
     UPD_ROWS_ENTRY(3, 3, 2, 2, 2, 1, 1),  // 64 x 64 channels, two wave groups along pixels
+    // one-row and one-column filters (factorised 7x7 and 3x3), the same two tiles
+    UPD_ROWS_ENTRY(1, 7, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY(1, 7, 2, 2, 2, 1, 1),
+    UPD_ROWS_ENTRY(7, 1, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY(7, 1, 2, 2, 2, 1, 1),
+    UPD_ROWS_ENTRY(1, 3, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY(1, 3, 2, 2, 2, 1, 1),
+    UPD_ROWS_ENTRY(3, 1, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY(3, 1, 2, 2, 2, 1, 1),
     // 1x1 (input staged sampled): channel tiles TC x TK
     UPD_ROWS_ENTRY(1, 1, 2, 2, 2, 1, 1),  //  64 x  64
     UPD_ROWS_ENTRY(1, 1, 2, 4, 1, 1, 1),  //  64 x 128

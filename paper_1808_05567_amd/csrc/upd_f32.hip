@@ -61,7 +61,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
     const int rho_end = min(NP, rho_begin + a.rows_per_split);
     const int Qp = a.Q;          // the staged dO band is the plain pixel list ...
     const int npxO = a.TR * Qp + 1;  // ... followed by one zero
-    const int HW = a.H * a.W, PQ = a.P * a.Q;
+    const int HW = a.H * a.W, PQ = a.P * a.Qpitch;
     const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
     const float inv_Qp = 1.0f / (float)Qp, inv_P = 1.0f / (float)a.P, inv_Q = inv_Qp;
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, (size_t)a.N * a.Cb * HW * 16);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
             const int lam = lam0 + row;
             const int n = fast_div(lam, inv_Hs);
             const int ih = lam - n * a.Hs - a.pad;
-            const int iw = col - a.pad_w;
+            const int iw = col + a.q0 * a.stride - a.pad_w;
             const bool ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
         };
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
             if (rho >= rho_end || col >= a.Q) return kOutOfRange;
             const int n = fast_div(rho, inv_P);
             const int oj = rho - n * a.P;
-            return (unsigned)((n * a.Kb * a.P + oj) * a.Q + col) * 16u;
+            return (unsigned)((n * a.Kb * a.P + oj) * a.Qpitch + a.q0 + col) * 16u;
         };
         // The (64-position chunk, plane) loads, input band first, are shared out
         // in equal contiguous runs: a wave computes the source offsets of one
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
 
     // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
     const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
-    float *dst = a.partial + (size_t)split * copy;
+    float *dst = a.partial + (size_t)(a.copy0 + split) * copy;
     const int k = kb0 * V + k_lane;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)

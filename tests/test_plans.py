@@ -69,8 +69,9 @@ def test_update_of_tall_filters_and_wide_rows():
     assert "RS=7x1" in upd((4, 64, 64, 17, 17, 7, 1, 1, (3, 0))) and "launches=1" in upd((4, 64, 64, 17, 17, 7, 1, 1, (3, 0)))
     assert "launches=1" in upd((4, 64, 64, 17, 17, 1, 7, 1, (0, 3)))
     assert "RS=1x5" in upd((4, 48, 64, 35, 35, 5, 5, 1, 2)) and "launches=5" in upd((4, 48, 64, 35, 35, 5, 5, 1, 2))
-    # 147-wide rows: three strips of 49 output columns in fp32
+    # 147-wide rows: strips of output columns, one launch each
     assert "launches=3" in upd((2, 32, 64, 147, 147, 3, 3, 1, 1))
+    assert "launches=2" in upd((2, 32, 64, 147, 147, 3, 3, 1, 1), conv.CONV_BF16)
 
 
 @pytest.mark.parametrize("dt", [conv.CONV_F32, conv.CONV_BF16], ids=["f32", "bf16"])
