@@ -115,6 +115,50 @@ def test_rectangular_filters_match_oracle(shape, dtype):
         L.close()
 
 
+def _sweep_shapes():
+    rng = np.random.default_rng(5567)
+    out = []
+    filters = [(1, 7), (7, 1), (1, 3), (3, 1), (5, 5), (3, 3), (1, 1)]
+    while len(out) < 35:
+        R, S = filters[len(out) % len(filters)]
+        stride = int(rng.choice([1, 1, 2])) if R == S else 1
+        ph, pw = int(rng.integers(0, R // 2 + 1)), int(rng.integers(0, S // 2 + 1))
+        H = int(rng.integers(max(R, 3), 22))
+        W = int(rng.integers(max(S, 3), 90 if len(out) % 4 == 0 else 22))
+        C = int(rng.choice([3, 8, 20, 48, 72]))
+        K = int(rng.choice([8, 24, 40, 96]))
+        N = int(rng.integers(1, 4))
+        out.append((N, C, K, H, W, R, S, stride, (ph, pw)))
+    return out
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", _sweep_shapes(), ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
+def test_seeded_descriptor_sweep_matches_oracle(shape, dtype):
+    """Seeded descriptors over the filter shapes, strides and per-axis pads the library
+    accepts: every pass that has a plan matches the oracle (a pass without one reports
+    CONV_EUNSUPPORTED at its entry point and is skipped here)."""
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=77)
+    L = _layer(shape, dtype)
+    ran = 0
+    try:
+        for which, ref, tol in (
+                ("fwd", lambda: oracle.fwd(I, Wt, stride, pad), TOL[dtype]),
+                ("bwd", lambda: oracle.bwd_data(dO, Wt, H, W, stride, pad), TOL[dtype]),
+                ("upd", lambda: oracle.upd(I, dO, R, S, stride, pad), 1e-5)):
+            try:
+                got = run_pass(L, which, I=I, Wt=Wt, dO=dO)
+            except conv.ConvError as e:
+                assert e.status == conv.CONV_EUNSUPPORTED
+                continue
+            assert rel_l2(got, ref()) <= tol, which
+            ran += 1
+    finally:
+        L.close()
+    assert ran >= 2, "at most one pass of a sweep descriptor may lack a kernel"
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", FEW_CHANNELS, ids=lambda s: "x".join(map(str, s)))
 def test_few_channel_layers_match_oracle(shape, dtype):

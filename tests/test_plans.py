@@ -102,6 +102,27 @@ def test_seeded_descriptor_sweep_plans_fit_the_machine():
     assert planned > 1500  # the sweep is not vacuous: most passes have a kernel
 
 
+def test_seeded_rectangular_sweep_plans_fit_the_machine():
+    """Rectangular filters, padding per axis, images up to 300 wide (column strips)."""
+    rng = np.random.default_rng(1808055670)
+    planned = 0
+    for _ in range(300):
+        R, S = [(1, 7), (7, 1), (1, 3), (3, 1), (5, 5), (3, 3), (1, 5), (5, 1), (3, 7)][int(rng.integers(0, 9))]
+        stride = int(rng.choice([1, 1, 1, 2]))
+        ph, pw = int(rng.integers(0, R // 2 + 2)), int(rng.integers(0, S // 2 + 2))
+        H = int(rng.integers(R, 40))
+        W = int(rng.integers(S, 300 if rng.integers(0, 4) == 0 else 40))
+        C = int(rng.choice([3, 8, 32, 48, 160, 192, 384]))
+        K = int(rng.choice([8, 32, 64, 96, 160, 192, 448]))
+        N = int(rng.choice([1, 2, 32]))
+        for dt in (conv.CONV_F32, conv.CONV_BF16):
+            info, plans = _plans((N, C, K, H, W, R, S, stride, (ph, pw)), dt)
+            _check(info, plans)
+            assert (info.P, info.Q) == ((H + 2 * ph - R) // stride + 1, (W + 2 * pw - S) // stride + 1)
+            planned += sum(p is not None for p in plans.values())
+    assert planned > 1000
+
+
 def test_kernel_families_are_chosen_where_they_apply():
     # fp32 1x1 with 256 channels on one side: eight-wave kernel on the flat pixel list
     _, p = _plans((256, 256, 1024, 14, 14, 1, 1, 1, 0), conv.CONV_F32)
