@@ -45,6 +45,7 @@ struct conv_plan {
     // weight update
     bool upd_ok = false;
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
+    bool upd_c4_bf16 = false; // bf16, one input channel block: (tap, channel) rows on the bf16 MFMA
     bool upd_rows = false; // bf16 row kernel (stride 1)
     bool upd_bands = false; // fp32 eight-wave band kernel
     bool upd_flat_bf16 = false; // bf16 1x1 eight-wave kernel on the flat pixel list (variant: urv)
@@ -369,6 +370,62 @@ void plan_upd(conv_plan *p)
     p->upd_row_launches = 1;
     p->upd_strips = 1;
     p->upd_c4 = false;
+    p->upd_c4_bf16 = false;
+    if (bf16 && d.C <= 4 && upd_c4_bf16_exists(d.R, d.S)) {
+        // one input channel block, bf16: (tap, channel) rows on the bf16 MFMA, eight waves,
+        // two LDS buffers holding the bands as they sit in HBM
+        auto plan_c4_bf16 = [&]() -> bool {
+            const int NPO = 8;  // planes of 8 output channels
+            const int NP = d.N * f.P;
+            UpdArgs &a = p->ua;
+            memset(&a, 0, sizeof(a));
+            a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
+            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+            a.tap0 = 0; a.ntaps_all = d.R * d.S;
+            a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
+            a.runs = ceil_div(f.Q, 8);
+            const int RP = a.runs * 8;
+            a.Hs = (f.P - 1) * d.stride + d.R;
+            // a lane addresses up to 7 pixels past the first pixel of its run's last window
+            a.LW = std::max(d.W + 2 * pad_w, d.stride * (RP - 1) + 8);
+            int TR = std::min(NP, 16);
+            for (;; --TR) {
+                if (TR < 1) return false;
+                const int LR = max_band_rows(d.N, f.P, TR, a.Hs, d.stride, d.R);
+                a.LRW = LR * a.LW;
+                a.PLS_in = ceil_div(a.LRW, 64) * 64;
+                // (+4 pixels: the two planes a 16-lane transposing read touches start 64
+                // bytes apart in the 256-byte bank row)
+                a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
+                p->upd_lds = 2 * ((size_t)a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
+                if (p->upd_lds <= (size_t)kMaxLds) break;
+            }
+            p->upd_lds = std::max(p->upd_lds, (size_t)16 * 1024);  // the accumulator exchange
+            a.TR = TR;
+            a.n_ct = 1;
+            a.n_kt = ceil_div(f.Kp, 64);
+            int splits = std::max(1, 256 / a.n_kt);  // one workgroup per CU, one round
+            splits = std::max(splits, ceil_div(NP * f.Q, 1 << 17));
+            int rps = ceil_div(ceil_div(NP, splits), TR) * TR;
+            splits = ceil_div(NP, rps);
+            a.rows_per_split = rps;
+            a.splits = splits;
+            a.sampled = 0;
+            a.total = a.n_kt * splits;
+            a.per_xcd = ceil_div(a.total, 8);
+            if ((double)(d.N + 1) * std::max(a.Hs, std::max(d.H, f.P * f.Kb)) >= 4.0e6 ||
+                a.LRW >= (1 << 22) || TR * RP + 8 >= (1 << 22) || (double)d.N * d.H * d.W * 16 >= 4.0e9 ||
+                (double)d.N * f.Kp * f.P * f.Q * 2 >= 4.0e9)
+                return false;
+            p->upd_grid = a.per_xcd * 8;
+            p->upd_copies = splits;
+            p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
+            p->upd_c4_bf16 = true;
+            p->upd_ok = true;
+            return true;
+        };
+        if (plan_c4_bf16()) return;
+    }
     if (d.C <= 4 && square_pad && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
         // (a plan that does not fit leaves the layer to the general kernels)
         auto plan_c4 = [&]() -> bool {
@@ -955,6 +1012,8 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
         e = launch_upd_bf16_1x1(h->urv, a, h->upd_grid, s);
     else if (h->upd_flat)
         e = launch_upd_f32_1x1(h->upd_wb, h->upd_a_is_in, a, h->upd_grid, s);
+    else if (h->upd_c4_bf16)
+        e = launch_upd_c4_bf16(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
     else if (h->upd_c4)
         e = launch_upd_c4(h->d.dtype, h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
     else if (h->upd_rows)
@@ -1087,10 +1146,10 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
                      h->upd_lds);
             return CONV_OK;
         }
-        if (h->upd_c4) {
+        if (h->upd_c4 || h->upd_c4_bf16) {
             snprintf(buf, buflen,
-                     "upd_c4 dt=%d RS=%dx%d waves=2x4 TR=%d splits=%d rows/split=%d ktiles=%d grid=%d lds=%zu",
-                     (int)h->d.dtype, h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
+                     "upd_c4 dt=%d mfma=%s RS=%dx%d waves=2x4 TR=%d splits=%d rows/split=%d ktiles=%d grid=%d lds=%zu",
+                     (int)h->d.dtype, h->upd_c4_bf16 ? "bf16" : "f32", h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_kt,
                      h->upd_grid, h->upd_lds);
             return CONV_OK;
         }

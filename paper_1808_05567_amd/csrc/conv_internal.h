@@ -176,6 +176,10 @@ hipError_t launch_upd_f32_1x1(int wb, bool a_is_in, const UpdArgs &a, int grid, 
 // tensors widened on their way into LDS (then UpdArgs::Kb counts blocks of 8 channels)
 hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
                          hipStream_t stream);
+// bf16 tensors, at most 4 input channels: the same formulation on the bf16 MFMA
+bool upd_c4_bf16_exists(int r, int s);
+hipError_t launch_upd_c4_bf16(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+                              hipStream_t stream);
 hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
                              hipStream_t stream);
 

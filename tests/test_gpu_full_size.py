@@ -33,7 +33,7 @@ def _entries(rng, K, C, R, S, count):
 # Inception-v3 shapes (ids of inputs.INCEPTION_V3): the first layer (299 wide, stride 2,
 # unpadded), a 147-wide 3x3 (update in column strips), 5x5, unpadded stride-2 3x3, 1x7 / 7x1
 # at 160 and 192 channels, 1x3 / 3x1
-V3_CASES = [(1, conv.CONV_F32), (3, conv.CONV_F32), (13, conv.CONV_F32), (16, conv.CONV_F32),
+V3_CASES = [(1, conv.CONV_F32), (1, conv.CONV_BF16), (3, conv.CONV_F32), (13, conv.CONV_F32), (16, conv.CONV_F32),
             (29, conv.CONV_F32), (30, conv.CONV_F32), (41, conv.CONV_F32), (42, conv.CONV_F32),
             (2, conv.CONV_BF16), (13, conv.CONV_BF16), (25, conv.CONV_BF16), (26, conv.CONV_BF16),
             (42, conv.CONV_BF16)]
