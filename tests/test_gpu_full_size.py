@@ -80,6 +80,57 @@ def _layer_at_n256(l, lid, dtype):
         L.close()
 
 
+SEP_CASES = [(4, conv.CONV_F32), (18, conv.CONV_F32), (6, conv.CONV_F32), (1, conv.CONV_F32),
+             (13, conv.CONV_BF16), (2, conv.CONV_BF16), (1, conv.CONV_BF16)]
+
+
+@pytest.mark.parametrize("lid,dtype", SEP_CASES,
+                         ids=["L%d-%s" % (l, "bf16" if d else "f32") for l, d in SEP_CASES])
+def test_full_tensor_at_n256_separable_integers(lid, dtype):
+    """Every output of every image at N = 256, exactly.  With rank-1 weights
+    W[k,c,r,s] = b[k] a[c] g[r,s] the passes collapse to single-channel convolutions:
+        fwd:  O[n,k]  = b[k] * conv1(sum_c a[c] I[n,c], g)
+        bwd:  dI[n,c] = a[c] * conv1_bwd(sum_k b[k] dO[n,k], g)
+        upd:  I = a[c] u[n], dO = b[k] v[n]  =>  dW[k,c,r,s] = a[c] b[k] * conv1_upd(u, v)[r,s]
+    and the oracle computes the single-channel problems in full.  All values are small
+    integers, so every product and partial sum is exact in fp32 (|sum| < 2^24) whatever the
+    summation order: the result must match bit for bit (bf16 outputs: the exact value
+    rounded once to bf16).  Distinct a[c], b[k] catch channel permutations."""
+    l = inputs.layer(lid)
+    rng = np.random.default_rng(4242 + lid)
+    a = rng.choice([-2, -1, 1, 2], size=l.C).astype(np.float32)
+    b = rng.choice([-2, -1, 1, 2], size=l.K).astype(np.float32)
+    g = rng.integers(-1, 2, size=(l.R, l.S)).astype(np.float32)
+    Wt = b[:, None, None, None] * a[None, :, None, None] * g[None, None]
+    g1 = g[None, None].astype(np.float64)
+    out_round = inputs.round_to_bf16 if dtype == conv.CONV_BF16 else (lambda x: x)
+    L = conv.ConvLayer(N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dtype)
+    try:
+        I = rng.integers(-1, 2, size=(N, l.C, l.H, l.W)).astype(np.float32)
+        J = np.einsum("c,nchw->nhw", a.astype(np.float64), I)[:, None]
+        ref = b[None, :, None, None] * oracle.fwd(J, g1, l.stride, l.pad)
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+        assert np.array_equal(got, out_round(ref.astype(np.float32)))
+        del J, ref, got
+
+        dO = rng.integers(-1, 2, size=(N, l.K, l.P, l.Q)).astype(np.float32)
+        G = np.einsum("k,nkpq->npq", b.astype(np.float64), dO)[:, None]
+        ref = a[None, :, None, None] * oracle.bwd_data(G, g1, l.H, l.W, l.stride, l.pad)
+        got = run_pass(L, "bwd", dO=dO, Wt=Wt)
+        assert np.array_equal(got, out_round(ref.astype(np.float32)))
+        del G, ref, got, I, dO
+
+        u = rng.integers(-1, 2, size=(N, 1, l.H, l.W)).astype(np.float32)
+        v = rng.integers(-1, 2, size=(N, 1, l.P, l.Q)).astype(np.float32)
+        T = oracle.upd(u.astype(np.float64), v.astype(np.float64), l.R, l.S, l.stride, l.pad)[0, 0]
+        assert np.abs(T).max() * 4 < 2 ** 24
+        ref = b[:, None, None, None] * a[None, :, None, None] * T[None, None]
+        got = run_pass(L, "upd", I=a[None, :, None, None] * u, dO=b[None, :, None, None] * v)
+        assert np.array_equal(got, ref.astype(np.float32))
+    finally:
+        L.close()
+
+
 # (the 3-channel first layer is an fp32 workload only)
 N1_CASES = [(lid, dt) for lid in (4, 8, 13, 18, 1, 6, 20) for dt in (conv.CONV_F32, conv.CONV_BF16)
             if not (lid == 1 and dt == conv.CONV_BF16)]
