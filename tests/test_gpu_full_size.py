@@ -71,7 +71,7 @@ def _layer_at_n256(l, lid, dtype):
         assert rel_l2(got[imgs], ref) <= TOL[dtype]
         assert np.isfinite(got).all()
         got = run_pass(L, "upd", I=I, dO=dO)
-        ent = _entries(rng, l.K, l.C, l.R, l.S, 256 if l.H > 200 else 1024)
+        ent = _entries(rng, l.K, l.C, l.R, l.S, 512 if l.H > 200 else 2048)
         ref = oracle.upd_entries(I.astype(np.float64), dO.astype(np.float64), l.R, l.S,
                                  l.stride, l.pad, ent)
         assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5
