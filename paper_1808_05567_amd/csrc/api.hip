@@ -577,9 +577,11 @@ void plan_upd(conv_plan *p)
     }
     p->upd_rows = false;
     // (this kernel takes the two pads separately)
-    const bool rows_rs = d.stride == 1 && !sampled &&
-                         ((d.R == 3 && d.S == 3) || (d.R == 1 && (d.S == 3 || d.S == 7)) ||
-                          (d.S == 1 && (d.R == 3 || d.R == 7)));
+    const bool rows_strided = d.stride > 1 && d.R == 3 && d.S == 3;
+    const bool rows_rs = !sampled && (rows_strided ||
+                         (d.stride == 1 &&
+                          ((d.R == 3 && d.S == 3) || (d.R == 1 && (d.S == 3 || d.S == 7)) ||
+                           (d.S == 1 && (d.R == 3 || d.R == 7)))));
     if (bf16 && (rows_rs || sampled)) {
         // bf16 row kernel: 8-pixel runs, filter-column shifts in registers.
         // 3x3: all nine taps in the wave (144 accumulators).  1x1: the layer is bound by
@@ -593,7 +595,8 @@ void plan_upd(conv_plan *p)
         bool have = false;
         if (rows_rs) {
             // 64 x 128 channels, or 64 x 64 with two wave groups along the pixels
-            rv = f.Kp <= 64 ? UpdRowsVariant{d.R, d.S, 2, 2, 2, 1, 1} : UpdRowsVariant{d.R, d.S, 2, 4, 1, 1, 1};
+            rv = f.Kp <= 64 ? UpdRowsVariant{d.R, d.S, 2, 2, 2, 1, 1, 0} : UpdRowsVariant{d.R, d.S, 2, 4, 1, 1, 1, 0};
+            rv.strided = rows_strided ? 1 : 0;
             have = upd_rows_variant_exists(rv);
         } else {
             double best = 0;
@@ -616,7 +619,8 @@ void plan_upd(conv_plan *p)
             a.tap0 = 0; a.ntaps_all = d.R * d.S;
             a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
             a.sampled = sampled ? 1 : 0;
-            a.Hs = sampled ? f.P : f.P - 1 + d.R;
+            const int lst = rows_strided ? d.stride : 1;  // input pixels per output pixel in a band
+            a.Hs = sampled ? f.P : (f.P - 1) * lst + d.R;
             // a lane reads a window of whole 4-pixel groups covering a run and its S-1 shifts
             const int win = (8 + d.S - 1 + 3) / 4 * 4;
             // Rows too wide for two bands in the LDS are cut into up to four strips of whole
@@ -628,8 +632,9 @@ void plan_upd(conv_plan *p)
                 a.runs = ceil_div(Qs, 8);
                 const int RP = a.runs * 8;
                 a.LW = sampled ? RP : std::max(ns == 1 ? d.W + 2 * pad_w : 0, RP + win - 8);
+                if (rows_strided) a.LW = std::max(ns == 1 ? d.W + 2 * pad_w : 0, lst * (RP - 1) + d.S);
                 for (TR = std::min(NP, 64); TR >= 1; --TR) {
-                    const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, 1, d.R);
+                    const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, lst, d.R);
                     a.LRW = LR * a.LW;
                     a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
                     a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;

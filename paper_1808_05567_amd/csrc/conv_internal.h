@@ -153,6 +153,7 @@ struct UpdRowsVariant {
     int r, s;
     int wc, wk, wp;  // waves along input channels / output channels / pixels
     int fc, fk;      // 32x32 fragments per wave along input / output channels
+    int strided;     // 1: stride > 1 with a filter larger than 1x1 (an operand read per tap)
 };
 bool upd_rows_variant_exists(const UpdRowsVariant &v);
 hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds_bytes, int grid,

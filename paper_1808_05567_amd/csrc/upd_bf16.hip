@@ -47,7 +47,11 @@ static __device__ __forceinline__ u32x2 lds_read_tr16_b64(const unsigned char *p
     return __builtin_bit_cast(u32x2, v);
 }
 
-template <int R, int S, int WC, int WK, int WP, int FC, int FK>
+// STRIDED: filters larger than 1x1 with stride > 1.  Consecutive output pixels are then
+// `stride` input pixels apart, so a tap's operand is not a shifted window any more; the
+// transposing read takes a per-lane address, and the lanes of a group simply address
+// pixels stride*(q+j) + s: two reads per tap instead of a shared window per filter row.
+template <int R, int S, int WC, int WK, int WP, int FC, int FK, bool STRIDED = false>
 __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const UpdArgs a)
 {
     constexpr int V = 8;
@@ -58,6 +62,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     constexpr int NPI = TC / V;
     constexpr int NPO = TK / V;
     constexpr int WIN = (8 + S - 1 + 3) / 4;  // 4-pixel reads covering a run plus S-1 shifts
+    constexpr int WN = STRIDED ? 4 * S : 2 * WIN;  // operand dwords a lane holds per filter row
     static_assert(NT == 256 || NT == 512, "four or eight waves");
     // Two waves per SIMD need the accumulators to fit the 256 AGPRs outright:
     // above that the compiler shuttles tiles between register files every step.
@@ -98,6 +103,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     const int npxO = a.TR * RP + 8;         // ... plus one all-zero run for idle lane halves
     const int HW = a.H * a.W, PQ = a.P * a.Qpitch;
     const int gap = a.sampled ? 0 : a.Hs - a.P;  // staged rows between images (stride 1)
+    const int lst = STRIDED ? a.stride : 1;      // input pixels per output pixel in the staged band
     const float inv_LW = 1.0f / (float)a.LW, inv_Hs = 1.0f / (float)a.Hs;
     const float inv_RP = 1.0f / (float)RP, inv_P = 1.0f / (float)a.P;
     const float inv_runs = 1.0f / (float)a.runs;
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         unsigned char *ib = lds + buf * bufbytes;
         unsigned char *ob = ib + ibytes;
         const int n0 = fast_div(rho0, inv_P);
-        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P);
+        const int lam0 = n0 * a.Hs + (rho0 - n0 * a.P) * lst;
         // Positions are staged in whole wave-level loads (64 chunks); the plane pitch is
         // that count plus 4 pixels, so that the two planes a 16-lane transposing read
         // touches start 64 bytes apart in the 256-byte bank row.
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - n * a.Hs - a.pad;
-                iw = col + a.q0 - a.pad_w;
+                iw = col + a.q0 * lst - a.pad_w;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             return ok ? (unsigned)((n * a.Cb * a.H + ih) * a.W + iw) * 16u : kOutOfRange;
@@ -196,7 +202,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 #pragma unroll
     for (int i = 0; i < FC; ++i) {
         const int c = (wave_c * FC + i) * 32 + grp * 16 + (i16 & 3) * 4;
-        a_lane[i] = ((c / V) * a.PLS_in + (i16 >> 2)) * 16 + (c % V) * 2;
+        a_lane[i] = ((c / V) * a.PLS_in + lst * (i16 >> 2)) * 16 + (c % V) * 2;
     }
 #pragma unroll
     for (int j = 0; j < FK; ++j) {
@@ -224,18 +230,21 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         const int oj0 = rho0 - n0 * a.P;
         // Run pairs: lane half h takes run 2*t + h; waves along pixels interleave t.
         // (Two waves per SIMD: one wave's LDS latency hides behind the other's MFMAs.)
-        auto load_pair = [&](int t, unsigned (&w)[R][FC][2 * WIN], u32x4 (&bf)[FK]) {
+        auto load_pair = [&](int t, unsigned (&w)[R][FC][WN], u32x4 (&bf)[FK]) {
             const int q = 2 * t + h;
             const bool live = q < nruns;
             const int trow = fast_div(q, inv_runs);
             const int ri = q - trow * a.runs;
             int lrow = trow;
-            if (!a.sampled) {
+            if (STRIDED) {
+                const int dn = fast_div(oj0 + trow, inv_P);
+                lrow = dn * a.Hs + (oj0 + trow - dn * a.P - oj0) * lst;
+            } else if (!a.sampled) {
                 // staged row of output row (rho0 + trow), tap row 0
                 const int dn = fast_div(oj0 + trow, inv_P);
                 lrow = trow + dn * gap;
             }
-            const int ipix = live ? (lrow * a.LW + ri * 8) * 16 : 0;
+            const int ipix = live ? (lrow * a.LW + ri * 8 * lst) * 16 : 0;
             const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
 #pragma unroll
             for (int j = 0; j < FK; ++j) {
@@ -246,16 +255,33 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < FC; ++i)
+                for (int i = 0; i < FC; ++i) {
+                    if constexpr (STRIDED) {
 #pragma unroll
-                    for (int g = 0; g < WIN; ++g) {
-                        // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
-                        const u32x2 v = lds_read_tr16_b64(ib + a_lane[i] + ipix + (r * a.LW + 4 * g) * 16);
-                        w[r][i][2 * g] = v[0];
-                        w[r][i][2 * g + 1] = v[1];
+                        for (int sx = 0; sx < S; ++sx) {
+                            // the 8 output pixels of the run under tap (r, sx): input pixels
+                            // stride*j + sx of the window, four per read
+                            const unsigned char *p = ib + a_lane[i] + ipix + (r * a.LW + sx) * 16;
+                            const u32x2 lo = lds_read_tr16_b64(p);
+                            const u32x2 hi = lds_read_tr16_b64(p + lst * 4 * 16);
+                            w[r][i][4 * sx + 0] = lo[0];
+                            w[r][i][4 * sx + 1] = lo[1];
+                            w[r][i][4 * sx + 2] = hi[0];
+                            w[r][i][4 * sx + 3] = hi[1];
+                        }
+                    } else {
+#pragma unroll
+                        for (int g = 0; g < WIN; ++g) {
+                            // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
+                            const u32x2 v =
+                                lds_read_tr16_b64(ib + a_lane[i] + ipix + (r * a.LW + 4 * g) * 16);
+                            w[r][i][2 * g] = v[0];
+                            w[r][i][2 * g + 1] = v[1];
+                        }
                     }
+                }
         };
-        auto mma_pair = [&](const unsigned (&w)[R][FC][2 * WIN], const u32x4 (&bf)[FK]) {
+        auto mma_pair = [&](const unsigned (&w)[R][FC][WN], const u32x4 (&bf)[FK]) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -265,9 +291,13 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                         u32x4 af;
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
-                            const int lo = d + s / 2;
-                            af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][lo + 1], w[r][i][lo], 16)
-                                            : w[r][i][lo];
+                            if constexpr (STRIDED) {
+                                af[d] = w[r][i][4 * s + d];
+                            } else {
+                                const int lo = d + s / 2;
+                                af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][lo + 1], w[r][i][lo], 16)
+                                                : w[r][i][lo];
+                            }
                         }
 #pragma unroll
                         for (int j = 0; j < FK; ++j)
@@ -276,7 +306,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                                 acc[r * S + s][i][j], 0, 0, 0);
                     }
         };
-        unsigned w0[R][FC][2 * WIN];
+        unsigned w0[R][FC][WN];
         u32x4 b0[FK];
         for (int t = wave_p; 2 * t < nruns; t += WP) {
             load_pair(t, w0, b0);
@@ -320,6 +350,10 @@ struct UpdRowsEntry {
     {                                                                                    \
         {R, S, WC, WK, WP, FC, FK}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK>, 0    \
     }
+#define UPD_ROWS_ENTRY_STRIDED(R, S, WC, WK, WP, FC, FK)                                 \
+    {                                                                                    \
+        {R, S, WC, WK, WP, FC, FK, 1}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK, true>, 0 \
+    }
 static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(3, 3, 2, 4, 1, 1, 1),  // 64 x 128 channels, eight waves
     UPD_ROWS_ENTRY(3, 3, 2, 2, 2, 1, 1),  // 64 x 64 channels, two wave groups along pixels
@@ -332,6 +366,9 @@ static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(1, 3, 2, 2, 2, 1, 1),
     UPD_ROWS_ENTRY(3, 1, 2, 4, 1, 1, 1),
     UPD_ROWS_ENTRY(3, 1, 2, 2, 2, 1, 1),
+    // 3x3 with stride > 1 (per-tap strided operands)
+    UPD_ROWS_ENTRY_STRIDED(3, 3, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY_STRIDED(3, 3, 2, 2, 2, 1, 1),
     // 1x1 (input staged sampled): channel tiles TC x TK
     UPD_ROWS_ENTRY(1, 1, 2, 2, 2, 1, 1),  //  64 x  64
     UPD_ROWS_ENTRY(1, 1, 2, 4, 1, 1, 1),  //  64 x 128
@@ -346,7 +383,7 @@ static UpdRowsEntry *find_rows(const UpdRowsVariant &v)
 {
     for (auto &e : g_rows)
         if (e.v.r == v.r && e.v.s == v.s && e.v.wc == v.wc && e.v.wk == v.wk && e.v.wp == v.wp &&
-            e.v.fc == v.fc && e.v.fk == v.fk)
+            e.v.fc == v.fc && e.v.fk == v.fk && e.v.strided == v.strided)
             return &e;
     return nullptr;
 }
