@@ -578,10 +578,12 @@ void plan_upd(conv_plan *p)
     p->upd_rows = false;
     // (this kernel takes the two pads separately)
     const bool rows_strided = d.stride > 1 && d.R == 3 && d.S == 3;
-    const bool rows_rs = !sampled && (rows_strided ||
+    const bool rows_5x5 = d.stride == 1 && d.R == 5 && d.S == 5;  // one launch per filter row
+    const bool rows_rs = !sampled && (rows_strided || rows_5x5 ||
                          (d.stride == 1 &&
                           ((d.R == 3 && d.S == 3) || (d.R == 1 && (d.S == 3 || d.S == 7)) ||
                            (d.S == 1 && (d.R == 3 || d.R == 7)))));
+    const int rows_R = rows_5x5 ? 1 : d.R;  // filter rows a launch of the row kernel serves
     if (bf16 && (rows_rs || sampled)) {
         // bf16 row kernel: 8-pixel runs, filter-column shifts in registers.
         // 3x3: all nine taps in the wave (144 accumulators).  1x1: the layer is bound by
@@ -595,7 +597,7 @@ void plan_upd(conv_plan *p)
         bool have = false;
         if (rows_rs) {
             // 64 x 128 channels, or 64 x 64 with two wave groups along the pixels
-            rv = f.Kp <= 64 ? UpdRowsVariant{d.R, d.S, 2, 2, 2, 1, 1, 0} : UpdRowsVariant{d.R, d.S, 2, 4, 1, 1, 1, 0};
+            rv = f.Kp <= 64 ? UpdRowsVariant{rows_R, d.S, 2, 2, 2, 1, 1, 0} : UpdRowsVariant{rows_R, d.S, 2, 4, 1, 1, 1, 0};
             rv.strided = rows_strided ? 1 : 0;
             have = upd_rows_variant_exists(rv);
         } else {
@@ -615,12 +617,12 @@ void plan_upd(conv_plan *p)
             UpdArgs &a = p->ua;
             memset(&a, 0, sizeof(a));
             a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
-            a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
+            a.R = rows_R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
             a.tap0 = 0; a.ntaps_all = d.R * d.S;
             a.q0 = 0; a.Qpitch = f.Q; a.copy0 = 0;
             a.sampled = sampled ? 1 : 0;
             const int lst = rows_strided ? d.stride : 1;  // input pixels per output pixel in a band
-            a.Hs = sampled ? f.P : (f.P - 1) * lst + d.R;
+            a.Hs = sampled ? f.P : (f.P - 1) * lst + rows_R;
             // a lane reads a window of whole 4-pixel groups covering a run and its S-1 shifts
             const int win = (8 + d.S - 1 + 3) / 4 * 4;
             // Rows too wide for two bands in the LDS are cut into up to four strips of whole
@@ -634,7 +636,7 @@ void plan_upd(conv_plan *p)
                 a.LW = sampled ? RP : std::max(ns == 1 ? d.W + 2 * pad_w : 0, RP + win - 8);
                 if (rows_strided) a.LW = std::max(ns == 1 ? d.W + 2 * pad_w : 0, lst * (RP - 1) + d.S);
                 for (TR = std::min(NP, 64); TR >= 1; --TR) {
-                    const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, lst, d.R);
+                    const int LR = sampled ? TR : max_band_rows(d.N, f.P, TR, a.Hs, lst, rows_R);
                     a.LRW = LR * a.LW;
                     a.PLS_in = ceil_div(a.LRW, 64) * 64 + 4;
                     a.PLS_out = ceil_div(TR * RP + 8, 64) * 64 + 4;
@@ -667,6 +669,7 @@ void plan_upd(conv_plan *p)
                     p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
                     p->upd_strips = n_strips;
                     p->upd_strip_w = Qs;
+                    p->upd_row_launches = rows_R == d.R ? 1 : d.R;
                     p->upd_rows = true;
                     p->upd_ok = true;
                     return;
@@ -1026,7 +1029,13 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
             a.q0 = st * h->upd_strip_w;
             a.Q = std::min(h->upd_strip_w, h->info.Q - a.q0);
             a.copy0 = st * a.splits * h->urv.wp;
-            e = launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s);
+            for (int r = 0; r < h->upd_row_launches && e == hipSuccess; ++r) {
+                // (one launch, or filter row r of a taller filter: its taps, its share of
+                // the padding)
+                a.pad = h->pad_h - r;
+                a.tap0 = r * h->d.S * (h->upd_row_launches > 1 ? 1 : 0);
+                e = launch_upd_rows(h->urv, a, h->upd_lds, h->upd_grid, s);
+            }
         }
     else if (h->upd_bands)
         for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
@@ -1164,7 +1173,7 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
                      "rows/split=%d tiles=%dx%d grid=%d lds=%zu launches=%d",
                      h->d.R, h->d.S, h->urv.wc, h->urv.wk, h->urv.wp, h->urv.fc, h->urv.fk, h->ua.TR,
                      h->ua.runs, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct, h->ua.n_kt,
-                     h->upd_grid, h->upd_lds, h->upd_strips);
+                     h->upd_grid, h->upd_lds, h->upd_strips * h->upd_row_launches);
             return CONV_OK;
         }
         if (h->upd_bands) {

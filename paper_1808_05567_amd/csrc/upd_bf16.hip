@@ -317,7 +317,8 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     }
 
     // ---- this (split, pixel wave)'s partial dW tile: [copy][cb][tap][k][c%8]
-    const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
+    // (a launch may serve taps [tap0, tap0 + R*S) of a taller filter with ntaps_all taps)
+    const size_t copy = (size_t)a.Cb * a.ntaps_all * a.Kp * V;
     float *dst = a.partial + ((size_t)a.copy0 + (size_t)split * WP + wave_p) * copy;
 #pragma unroll
     for (int t = 0; t < NTAPS; ++t)
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                     if (cb >= a.Cb) continue;
                     f32x4 v = {acc[t][i][j][4 * vq + 0], acc[t][i][j][4 * vq + 1],
                                acc[t][i][j][4 * vq + 2], acc[t][i][j][4 * vq + 3]};
-                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * NTAPS + t) * a.Kp + k) * V +
+                    *reinterpret_cast<f32x4 *>(dst + (((size_t)cb * a.ntaps_all + a.tap0 + t) * a.Kp + k) * V +
                                                4 * h) = v;
                 }
             }
@@ -366,6 +367,9 @@ static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(1, 3, 2, 2, 2, 1, 1),
     UPD_ROWS_ENTRY(3, 1, 2, 4, 1, 1, 1),
     UPD_ROWS_ENTRY(3, 1, 2, 2, 2, 1, 1),
+    // one row of a 5x5 filter per launch
+    UPD_ROWS_ENTRY(1, 5, 2, 4, 1, 1, 1),
+    UPD_ROWS_ENTRY(1, 5, 2, 2, 2, 1, 1),
     // 3x3 with stride > 1 (per-tap strided operands)
     UPD_ROWS_ENTRY_STRIDED(3, 3, 2, 4, 1, 1, 1),
     UPD_ROWS_ENTRY_STRIDED(3, 3, 2, 2, 2, 1, 1),
