@@ -1,7 +1,8 @@
 """Benchmark of the convolution hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16]
-                    [--layers 4,8,13,18] [--table] [--no-cpu]
+                    [--workload resnet50|inception_v3] [--layers 4,8,13,18|all]
+                    [--table] [--table-dir DIR] [--no-cpu]
 
 A "step" is one pass of the whole hot path over one minibatch: forward,
 backward-by-data and weight update (partial + reduce) of every layer in the
@@ -10,9 +11,10 @@ workload is the configuration the headline metric is quoted on: the four
 ResNet-50 3x3 layers of Table I (ids 4, 8, 13, 18), fp32, N = 256, stride 1,
 pad 1, seeded synthetic inputs.  Prints ONE JSON line.
 
---table additionally times every requested layer/pass on its own and writes a
-per-layer table (TFLOP/s, % of MFMA peak, % of the layer's roofline ceiling)
-to gpurun_out/.
+--table additionally times every requested layer/pass on its own (in the cycling
+loop and repeated back to back) and writes a per-layer table (TFLOP/s, % of MFMA
+peak, % of the layer's roofline ceiling) as JSON into --table-dir and as text to
+stderr.
 """
 from __future__ import annotations
 
@@ -45,6 +47,8 @@ def parse():
                          "(default: 4,8,13,18 for resnet50, all for inception_v3)")
     ap.add_argument("--batch", type=int, default=N_BATCH)
     ap.add_argument("--table", action="store_true")
+    ap.add_argument("--table-dir", default=os.path.join(ROOT, "gpurun_out"),
+                    help="where --table writes layers_<workload>_<dtype>.json")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=128)
     ap.add_argument("--calib-copy", action="store_true",
@@ -425,8 +429,8 @@ def main():
                              "pct_mfma_peak": 0.0, "ceiling_tflops": 0.0, "pct_ceiling": 0.0,
                              "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
             del nchw, nkpq
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        path = os.path.join(ROOT, "gpurun_out", "layers_%s%s.json" % (
+        os.makedirs(args.table_dir, exist_ok=True)
+        path = os.path.join(args.table_dir, "layers_%s%s.json" % (
             "" if args.workload == "resnet50" else args.workload + "_", args.dtype))
         with open(path, "w") as f:
             json.dump(rows, f, indent=1)
