@@ -678,7 +678,8 @@ void plan_upd(conv_plan *p)
         }
     }
     p->upd_bands = false;
-    if (!bf16 && !sampled && d.stride == 1 && square_pad && upd_f32_bands_exists(d.R, d.S)) {
+    // (this kernel takes the two pads separately)
+    if (!bf16 && !sampled && d.stride == 1 && upd_f32_bands_exists(d.R, d.S)) {
         // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
         // bands; the pixel range is split so that one round of workgroups fills the chip.
         const int NPI = 16, NPO = 16;

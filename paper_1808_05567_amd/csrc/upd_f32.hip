@@ -26,7 +26,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <int R, int S, bool ODDQ>  // unit stride
 __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
 {
-    static_assert(S == 3, "the register hand-over between pixel pairs assumes three filter columns");
     constexpr int V = 4;
     constexpr int NT = 512, NW = NT / 64;
     constexpr int NTAPS = R * S;
@@ -191,31 +190,33 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
                 const int oj = rho - n * a.P;
                 const float *pi = ldsI + a_lane + ((n * a.Hs + oj - lam0) * a.LW + col_first + h) * V;
                 const float *po = ldsO + b_lane + (trow * a.Q + col_first + h) * V;
-                float a0[R], an[R][S - 1], bn;
+                // (the window of the next pair starts two columns further: its first S-2
+                // values are this pair's last S-2, only the other two are read)
+                constexpr int KEEP = S > 2 ? S - 2 : 0;
+                float an[R][S], bn;
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    a0[r] = pi[(r * a.LW) * V];
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int s = 1; s < S; ++s) an[r][s - 1] = pi[(r * a.LW + s) * V];
-                }
+                    for (int s = 0; s < S; ++s) an[r][s] = pi[(r * a.LW + s) * V];
                 bn = po[0];
 #pragma unroll 2
                 for (int c = 0; c < ncol; c += 2) {
                     float av[R][S];
                     const float bv = bn;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        av[r][0] = a0[r];
-#pragma unroll
-                        for (int s = 1; s < S; ++s) av[r][s] = an[r][s - 1];
-                        a0[r] = av[r][S - 1];  // column c+2 of this row's window (S == 3)
-                    }
-                    // next pair (clamped at the end of the run: a harmless re-read)
-                    const int cn = min(c + 2, ncol - 2);
-#pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int s = 1; s < S; ++s) an[r][s - 1] = pi[(r * a.LW + cn + s) * V];
+                        for (int s = 0; s < S; ++s) av[r][s] = an[r][s];
+                    // next pair (clamped at the end of the run: a harmless re-read, the
+                    // values are not used)
+                    const int cn = min(c + 2, ncol - 2);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+#pragma unroll
+                        for (int s = 0; s < KEEP; ++s) an[r][s] = av[r][s + 2];
+#pragma unroll
+                        for (int s = KEEP; s < S; ++s) an[r][s] = pi[(r * a.LW + cn + s) * V];
+                    }
                     bn = po[cn * V];
 #pragma unroll
                     for (int r = 0; r < R; ++r)
@@ -272,7 +273,11 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
         }
 }
 
-bool upd_f32_bands_exists(int r, int s) { return r == 3 && s == 3; }
+bool upd_f32_bands_exists(int r, int s)
+{
+    // (not 7x1: its bands hold a single output row and the four-wave kernel measured faster)
+    return (r == 3 && s == 3) || (r == 1 && (s == 3 || s == 7)) || (s == 1 && r == 3);
+}
 
 // LDS bytes the in-workgroup exchange of the two pixel groups needs
 size_t upd_f32_bands_exchange_bytes(int r, int s) { return (size_t)4 * r * s * 4 * 64 * 16; }
@@ -283,10 +288,20 @@ hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
     const int odd = a.Q & 1;
-    if (r == 3 && s == 3) fn = odd ? upd_f32_bands_kernel<3, 3, true> : upd_f32_bands_kernel<3, 3, false>;
+    int slot = -1;
+#define BANDS_CASE(IDX, RR, SS)                                                                 \
+    if (r == RR && s == SS) {                                                                   \
+        fn = odd ? upd_f32_bands_kernel<RR, SS, true> : upd_f32_bands_kernel<RR, SS, false>;    \
+        slot = IDX;                                                                             \
+    }
+    BANDS_CASE(0, 3, 3)
+    BANDS_CASE(1, 1, 7)
+    BANDS_CASE(2, 1, 3)
+    BANDS_CASE(3, 3, 1)
+#undef BANDS_CASE
     if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attrs[2] = {0, 0};
-    size_t &attr = attrs[odd];
+    static size_t attrs[4][2] = {};
+    size_t &attr = attrs[slot][odd];
     if (lds_bytes > attr) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                              hipFuncAttributeMaxDynamicSharedMemorySize,

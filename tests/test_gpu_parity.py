@@ -262,11 +262,13 @@ FUSED = [
     (5, 128, 128, 28, 28, 3, 3, 1, 1),    # many tiles: operators in the convolution's store
     (3, 64, 256, 56, 56, 1, 1, 1, 0),
     (2, 20, 24, 8, 8, 3, 3, 1, 1),        # padded channel slots stay zero
+    (2, 48, 72, 17, 17, 1, 7, 1, (0, 3)),  # rectangular filter, padding along one axis
+    (2, 32, 40, 13, 13, 3, 3, 2, 0),       # unpadded stride 2
 ]
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("shape", FUSED, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shape", FUSED, ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
 def test_fused_forward_matches_oracle(shape, dtype):
     """Section II-G / Algorithm 4: bias, residual and ReLU applied before the result is stored."""
     import torch
