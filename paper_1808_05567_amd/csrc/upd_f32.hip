@@ -138,7 +138,13 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
     __syncthreads();
     int buf = 0;
     for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, buf ^= 1) {
-        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, buf ^ 1);
+        // The two pixel groups of a channel pair are the two waves of one SIMD.  With even
+        // rows group 0 issues its share of the next band's loads before its pixels, group 1
+        // between the two halves of its pixels: while one wave computes addresses and
+        // issues loads the other has MFMAs to issue (2-3 % at 56 and 28 pixels per row; the
+        // odd-row path lost 5 % to a split loop and issues all loads up front).
+        const bool more = rho0 + a.TR < rho_end;
+        if (more && (ODDQ || wave_p == 0)) fetch(rho0 + a.TR, buf ^ 1);
         const float *ldsI = reinterpret_cast<const float *>(lds + buf * bufbytes);
         const float *ldsO = reinterpret_cast<const float *>(lds + buf * bufbytes + ibytes);
 
@@ -176,63 +182,80 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
         } else {
             // Even rows: pairs stay inside a row.  Each group walks a contiguous
             // run of pairs (half a row if the row has an even number of pairs,
-            // else alternate rows), so with unit stride the input value of the
-            // last filter column is the next pair's first-column value and is
-            // kept in a register; the other operands of the next pair are read
-            // before this pair's MFMAs issue.
+            // else alternate rows), so with unit stride the input values of the
+            // last filter columns are the next pair's first ones and are kept in
+            // registers; the other operands of the next pair are read before this
+            // pair's MFMAs issue.
             const bool halves = ((a.Q >> 1) & 1) == 0;
             const int row_first = halves ? 0 : wave_p, row_step = halves ? 1 : 2;
             const int ncol = halves ? (a.Q >> 1) : a.Q;  // pixels of a row this group takes
             const int col_first = halves ? wave_p * ncol : 0;
-            for (int trow = row_first; trow < rows; trow += row_step) {
-                const int rho = rho0 + trow;
-                const int n = fast_div(rho, inv_P);
-                const int oj = rho - n * a.P;
-                const float *pi = ldsI + a_lane + ((n * a.Hs + oj - lam0) * a.LW + col_first + h) * V;
-                const float *po = ldsO + b_lane + (trow * a.Q + col_first + h) * V;
-                // (the window of the next pair starts two columns further: its first S-2
-                // values are this pair's last S-2, only the other two are read)
-                constexpr int KEEP = S > 2 ? S - 2 : 0;
-                float an[R][S], bn;
+            const int nrow = rows > row_first ? (rows - row_first + row_step - 1) / row_step : 0;
+            // rows [r0, r1) of this group's rows, columns [c0, c1) of its run (c0, c1 even)
+            auto walk = [&](int r0, int r1, int c0, int c1) {
+                if (c1 <= c0) return;
+                for (int ri = r0; ri < r1; ++ri) {
+                    const int trow = row_first + ri * row_step;
+                    const int rho = rho0 + trow;
+                    const int n = fast_div(rho, inv_P);
+                    const int oj = rho - n * a.P;
+                    const float *pi = ldsI + a_lane + ((n * a.Hs + oj - lam0) * a.LW + col_first + h) * V;
+                    const float *po = ldsO + b_lane + (trow * a.Q + col_first + h) * V;
+                    // (the window of the next pair starts two columns further: its first S-2
+                    // values are this pair's last S-2, only the other two are read)
+                    constexpr int KEEP = S > 2 ? S - 2 : 0;
+                    float an[R][S], bn;
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+                    for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int s = 0; s < S; ++s) an[r][s] = pi[(r * a.LW + s) * V];
-                bn = po[0];
+                        for (int s = 0; s < S; ++s) an[r][s] = pi[(r * a.LW + c0 + s) * V];
+                    bn = po[c0 * V];
 #pragma unroll 2
-                for (int c = 0; c < ncol; c += 2) {
-                    float av[R][S];
-                    const float bv = bn;
+                    for (int c = c0; c < c1; c += 2) {
+                        float av[R][S];
+                        const float bv = bn;
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
+                        for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int s = 0; s < S; ++s) av[r][s] = an[r][s];
-                    // next pair (clamped at the end of the run: a harmless re-read, the
-                    // values are not used)
-                    const int cn = min(c + 2, ncol - 2);
+                            for (int s = 0; s < S; ++s) av[r][s] = an[r][s];
+                        // next pair (clamped at the end of the run: a harmless re-read, the
+                        // values are not used)
+                        const int cn = min(c + 2, c1 - 2);
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
+                        for (int r = 0; r < R; ++r) {
 #pragma unroll
-                        for (int s = 0; s < KEEP; ++s) an[r][s] = av[r][s + 2];
+                            for (int s = 0; s < KEEP; ++s) an[r][s] = av[r][s + 2];
 #pragma unroll
-                        for (int s = KEEP; s < S; ++s) an[r][s] = pi[(r * a.LW + cn + s) * V];
+                            for (int s = KEEP; s < S; ++s) an[r][s] = pi[(r * a.LW + cn + s) * V];
+                        }
+                        bn = po[cn * V];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int s = 0; s < S; ++s)
+                                acc[r * S + s] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                    av[r][s], bv, acc[r * S + s], 0, 0, 0);
+                        // issue order: each of the next pair's reads behind an MFMA of this pair
+#pragma unroll
+                        for (int k = 0; k < R * S; ++k) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    bn = po[cn * V];
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int s = 0; s < S; ++s)
-                            acc[r * S + s] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                av[r][s], bv, acc[r * S + s], 0, 0, 0);
-                    // issue order: each of the next pair's reads behind an MFMA of this pair
-#pragma unroll
-                    for (int k = 0; k < R * S; ++k) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+            };
+            // the halves of this group's pixels: rows where it has several, else columns
+            // (one copy of the loop: the two halves are two trips of an outer loop)
+            const bool by_rows = nrow >= 2;
+            const int rm = by_rows ? nrow >> 1 : nrow, cm = by_rows ? ncol : (ncol >> 1) & ~1;
+#pragma nounroll
+            for (int part = 0; part < 2; ++part) {
+                if (part == 1 && more && wave_p == 1) fetch(rho0 + a.TR, buf ^ 1);
+                const int r0 = part == 0 ? 0 : (by_rows ? rm : 0), r1 = part == 0 ? rm : nrow;
+                const int c0 = part == 0 ? 0 : (by_rows ? 0 : cm), c1 = part == 0 ? cm : ncol;
+                walk(r0, r1, c0, c1);
             }
         }
         wait_all_memory();
