@@ -115,14 +115,23 @@ conv_status_t conv_fwd(conv_handle_t h, const void *in, const void *wt, void *ou
 /* Forward pass with fused operators (Section II-G, Algorithm 4: APPLY(L(), O
  * sub-tensor) once the sub-tensor's reduction is complete -- here while it is
  * still in registers):
- *     out[n,k,oj,oi] = L( conv[n,k,oj,oi] + bias[k] + residual[n,k,oj,oi] )
+ *     out[n,k,oj,oi] = L( scale[k] * conv[n,k,oj,oi] + bias[k] + residual[n,k,oj,oi] )
  * with L(x) = max(x, 0) if relu != 0, else the identity; the sum and L are
- * evaluated in fp32 before the one rounding to the output type.
+ * evaluated in fp32 before the one rounding to the output type.  scale and bias
+ * together are a normalisation layer applied with given statistics (the
+ * "Normalization" and "Bias" layers Section II-G names), residual + relu the
+ * element-wise tail of a residual block.
+ * scale: device, fp32, Kp entries, or NULL (= 1).
  * bias: device, fp32, Kp entries (entries of padded channels must be 0), or NULL.
  * residual: device, blocked O layout and the tensors' dtype, or NULL; it may
  * alias out (each element is read before it is written, by the same lane).
- * Everything else as conv_fwd; with bias == residual == NULL and relu == 0 the
- * two calls give identical results. */
+ * Everything else as conv_fwd; with scale == bias == residual == NULL and
+ * relu == 0 the two calls give identical results. */
+conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *wt, void *out,
+                                  const float *scale, const float *bias, const void *residual,
+                                  int32_t relu, void *ws, void *stream);
+
+/* The same without the scale (scale[k] = 1). */
 conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, void *out,
                              const float *bias, const void *residual, int32_t relu, void *ws,
                              void *stream);

@@ -106,12 +106,17 @@ def fwd(I, Wt, stride=1, pad=0):
     return O
 
 
-def fwd_fused(I, Wt, stride=1, pad=0, bias=None, residual=None, relu=False):
-    """Algorithm 4 (Section II-G) with L() = bias add, residual add, ReLU, applied to each
-    output element once its reduction is complete:
-        O = L(conv(I, Wt) + bias[k] + residual[n,k,oj,oi]),  L = max(., 0) if relu.
+def fwd_fused(I, Wt, stride=1, pad=0, bias=None, residual=None, relu=False, scale=None):
+    """Algorithm 4 (Section II-G) with L() = per-channel scale (a normalisation layer applied
+    with given statistics), bias add, residual add, ReLU, applied to each output element
+    once its reduction is complete:
+        O = L(scale[k] * conv(I, Wt) + bias[k] + residual[n,k,oj,oi]),  L = max(., 0) if relu.
     Written out with numpy on top of ``fwd``; all in float64."""
     O = fwd(I, Wt, stride, pad)
+    if scale is not None:
+        g = np.asarray(scale, dtype=np.float64)
+        for k in range(O.shape[1]):
+            O[:, k, :, :] *= g[k]
     if bias is not None:
         b = np.asarray(bias, dtype=np.float64)
         for k in range(O.shape[1]):

@@ -20,7 +20,7 @@ CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5
 
 EXPORTS = (
     "conv_create", "conv_create_rect", "conv_destroy", "conv_query", "conv_status_str",
-    "conv_fwd", "conv_fwd_fused", "conv_bwd_data", "conv_upd",
+    "conv_fwd", "conv_fwd_fused", "conv_fwd_fused_norm", "conv_bwd_data", "conv_upd",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
@@ -76,6 +76,7 @@ def load():
     for name in ("conv_fwd", "conv_bwd_data", "conv_upd"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp]
     lib.conv_fwd_fused.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
+    lib.conv_fwd_fused_norm.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
     for name in ("conv_pack_in", "conv_pack_out", "conv_pack_wt", "conv_unpack_in",
                  "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp]
@@ -155,6 +156,13 @@ def conv_fwd(h, inp, wt, out, ws=None, stream=None):
 def conv_fwd_fused(h, inp, wt, out, bias=None, residual=None, relu=False, ws=None, stream=None):
     _check(load().conv_fwd_fused(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(bias), _ptr(residual),
                                  1 if relu else 0, _ptr(ws), _stream(stream)), "conv_fwd_fused")
+
+
+def conv_fwd_fused_norm(h, inp, wt, out, scale=None, bias=None, residual=None, relu=False, ws=None,
+                        stream=None):
+    _check(load().conv_fwd_fused_norm(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(scale), _ptr(bias),
+                                      _ptr(residual), 1 if relu else 0, _ptr(ws), _stream(stream)),
+           "conv_fwd_fused_norm")
 
 
 def conv_bwd_data(h, dout, wt, din, ws, stream=None):
@@ -244,8 +252,12 @@ class ConvLayer:
     def fwd(self):
         conv_fwd(self.h, self.in_blk, self.wt_blk, self.out_blk, self.ws)
 
-    def fwd_fused(self, bias=None, residual=None, relu=False):
-        """bias: fp32 device tensor of Kp entries; residual: blocked tensor like out_blk."""
+    def fwd_fused(self, bias=None, residual=None, relu=False, scale=None):
+        """scale, bias: fp32 device tensors of Kp entries; residual: blocked tensor like out_blk."""
+        if scale is not None:
+            conv_fwd_fused_norm(self.h, self.in_blk, self.wt_blk, self.out_blk, scale, bias, residual,
+                                relu, self.ws)
+            return
         conv_fwd_fused(self.h, self.in_blk, self.wt_blk, self.out_blk, bias, residual, relu, self.ws)
 
     def bwd_data(self):

@@ -142,7 +142,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
     a.shuffle = 0; a.out_kb = Kp / V;
     a.ksplit = 1;
-    a.bias = nullptr; a.resid = nullptr; a.relu = 0;
+    a.scale = nullptr; a.bias = nullptr; a.resid = nullptr; a.relu = 0;
     a.TR = TR; a.TQ = TQ;
     a.n_qt = ceil_div(Q, TQ);
     a.n_mt = ceil_div(N * P, TR);
@@ -943,9 +943,16 @@ conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, vo
                              const float *bias, const void *residual, int32_t relu, void *ws,
                              void *stream)
 {
+    return conv_fwd_fused_norm(h, in, wt, out, nullptr, bias, residual, relu, ws, stream);
+}
+
+conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *wt, void *out,
+                                  const float *scale, const float *bias, const void *residual,
+                                  int32_t relu, void *ws, void *stream)
+{
     if (!h || !in || !wt || !out) return CONV_EINVAL;
     if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws) || !aligned16(bias) ||
-        !aligned16(residual))
+        !aligned16(residual) || !aligned16(scale))
         return CONV_EINVAL;
     if (!h->fwd.ok) return CONV_EUNSUPPORTED;
     IgemmArgs a = h->fwd.a;
@@ -955,14 +962,15 @@ conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, vo
     a.wt = wt;
     a.out = split ? ws : out;
     // a split reduction applies the operators where the partial results are summed
+    a.scale = split ? nullptr : scale;
     a.bias = split ? nullptr : bias;
     a.resid = split ? nullptr : residual;
     a.relu = split ? 0 : (relu != 0);
     hipError_t e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
     if (e == hipSuccess && split)
         e = launch_split_reduce(h->d.dtype, static_cast<const float *>(ws), out,
-                                (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit, bias,
-                                residual, relu != 0, h->info.P * h->info.Q, h->info.Kb,
+                                (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit, scale,
+                                bias, residual, relu != 0, h->info.P * h->info.Q, h->info.Kb,
                                 (hipStream_t)stream);
     return e == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }

@@ -59,6 +59,7 @@ struct IgemmArgs {
     int ksplit;    // number of splits (1: none, the result is written directly)
     int st_per;    // reduction steps per split
     // Operators fused into the store of the result (forward pass only)
+    const float *scale; // per output channel row, Kp entries, multiplies the result, or null
     const float *bias;  // per output channel row, Kp entries, or null
     const void *resid;  // tensor of the output's layout and type added to the result, or null
     int relu;           // clamp at zero after the additions
@@ -79,11 +80,11 @@ hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_by
                         int grid, hipStream_t stream);
 bool igemm_variant_exists(const IgemmVariant &v);
 // out[e] = sum over copies j (ascending) of partial[j][e], converted to the tensor's type
-// Fused operators (null / 0: none): bias[channel], residual (output layout), ReLU;
-// pq = pixels per image, kb = channel blocks, for the channel of an element.
+// Fused operators (null / 0: none): scale[channel], bias[channel], residual (output
+// layout), ReLU; pq = pixels per image, kb = channel blocks, for the channel of an element.
 hipError_t launch_split_reduce(int dtype, const float *partial, void *out, size_t n_elems, int copies,
-                               const float *bias, const void *resid, int relu, int pq, int kb,
-                               hipStream_t stream);
+                               const float *scale, const float *bias, const void *resid, int relu,
+                               int pq, int kb, hipStream_t stream);
 
 // Weight transform for backward by data:  dst[kb][r'][s'][c][k%v] (tap-flipped,
 // channel roles swapped, optionally a stride-decimated sub-filter).

@@ -107,6 +107,7 @@ bool igemm_variant_exists(const IgemmVariant &v) { return find_igemm(v) != nullp
 template <bool BF16>
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ partial,
                                                            void *out, size_t n4, int copies,
+                                                           const float *__restrict__ scale,
                                                            const float *__restrict__ bias,
                                                            const void *resid, int relu, int pq, int kb)
 {
@@ -122,6 +123,13 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
         s[2] += v[2];
         s[3] += v[3];
     }
+    // element e of [n][kb][pixel][V]: channel = block * V + e % V
+    const size_t e0 = idx * 4;
+    const int ch0 = (int)((e0 / ((size_t)pq * V)) % (size_t)kb) * V + (int)(e0 % V);
+    if (scale) {
+        const f32x4 g = *reinterpret_cast<const f32x4 *>(scale + ch0);
+        s[0] *= g[0]; s[1] *= g[1]; s[2] *= g[2]; s[3] *= g[3];
+    }
     if (resid) {
         if (BF16) {
             const u32x2 r = reinterpret_cast<const u32x2 *>(resid)[idx];
@@ -135,10 +143,7 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
         }
     }
     if (bias) {
-        // element e of [n][kb][pixel][V]: channel = block * V + e % V
-        const size_t e = idx * 4;
-        const int blk = (int)((e / ((size_t)pq * V)) % (size_t)kb);
-        const f32x4 b = *reinterpret_cast<const f32x4 *>(bias + blk * V + (int)(e % V));
+        const f32x4 b = *reinterpret_cast<const f32x4 *>(bias + ch0);
         s[0] += b[0]; s[1] += b[1]; s[2] += b[2]; s[3] += b[3];
     }
     if (relu) {
@@ -154,17 +159,17 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restri
 }
 
 hipError_t launch_split_reduce(int dtype, const float *partial, void *out, size_t n_elems, int copies,
-                               const float *bias, const void *resid, int relu, int pq, int kb,
-                               hipStream_t stream)
+                               const float *scale, const float *bias, const void *resid, int relu,
+                               int pq, int kb, hipStream_t stream)
 {
     const size_t n4 = n_elems / 4;
     const unsigned grid = (unsigned)((n4 + 255) / 256);
     if (dtype == CONV_BF16)
         hipLaunchKernelGGL(split_reduce_kernel<true>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
-                           copies, bias, resid, relu, pq, kb);
+                           copies, scale, bias, resid, relu, pq, kb);
     else
         hipLaunchKernelGGL(split_reduce_kernel<false>, dim3(grid), dim3(256), 0, stream, partial, out, n4,
-                           copies, bias, resid, relu, pq, kb);
+                           copies, scale, bias, resid, relu, pq, kb);
     return hipGetLastError();
 }
 

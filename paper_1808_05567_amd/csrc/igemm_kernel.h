@@ -408,8 +408,8 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
         return;
     }
     const rsrc_t ro = make_rsrc(a.out, 0, out_bytes);
-    if (a.bias != nullptr || a.resid != nullptr || a.relu != 0) {
-        // L() of Algorithm 4 on the finished accumulators: bias, residual, ReLU (forward
+    if (a.scale != nullptr || a.bias != nullptr || a.resid != nullptr || a.relu != 0) {
+        // L() of Algorithm 4 on the finished accumulators: scale, bias, residual, ReLU (forward
         // pass: plain store geometry).  The residual values of a row group are all
         // requested before the first of them is used, and before any store of the group
         // (the residual may be the output buffer itself).
@@ -425,6 +425,11 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
                 if (a.bias && rows_live) {
                     const f32x4 b = *reinterpret_cast<const f32x4 *>(a.bias + krow0 + 4 * h);
                     b4[0] = b[0]; b4[1] = b[1]; b4[2] = b[2]; b4[3] = b[3];
+                }
+                float s4[4] = {1.f, 1.f, 1.f, 1.f};
+                if (a.scale && rows_live) {
+                    const f32x4 g = *reinterpret_cast<const f32x4 *>(a.scale + krow0 + 4 * h);
+                    s4[0] = g[0]; s4[1] = g[1]; s4[2] = g[2]; s4[3] = g[3];
                 }
                 const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
                 const unsigned lane_off = (V == 4) ? (unsigned)h * (unsigned)oplane : (unsigned)h * 8u;
@@ -446,7 +451,7 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
                     float o4[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        o4[t] = acc[i][j][4 * vq + t] + r4[j][t] + b4[t];
+                        o4[t] = acc[i][j][4 * vq + t] * s4[t] + r4[j][t] + b4[t];
                         if (a.relu) o4[t] = fmaxf(o4[t], 0.0f);
                     }
                     E_::store4(ro, live ? obyte[j] + lane_off : kOutOfRange, skip, o4[0], o4[1], o4[2],

@@ -286,19 +286,23 @@ def test_fused_forward_matches_oracle(shape, dtype):
         info = conv.conv_query(L.h)
         bias_dev = torch.zeros(info.Kp, dtype=torch.float32, device="cuda")
         bias_dev[:K] = torch.from_numpy(bias)
+        scale = rng.uniform(0.5, 1.5, size=K).astype(np.float32) * rng.choice([-1.0, 1.0], size=K).astype(np.float32)
+        scale_dev = torch.ones(info.Kp, dtype=torch.float32, device="cuda")
+        scale_dev[:K] = torch.from_numpy(scale)
         L.set_outgrad(res)                 # blocked tensor of the output's shape ...
         res_blk = L.out_blk.clone()        # ... used as the residual
         L.set_input(I)
         L.set_weights(Wt)
         for kw in (dict(bias=bias_dev), dict(residual=res_blk, relu=True),
-                   dict(bias=bias_dev, residual=res_blk, relu=True)):
+                   dict(bias=bias_dev, residual=res_blk, relu=True), dict(scale=scale_dev),
+                   dict(scale=scale_dev, bias=bias_dev, residual=res_blk, relu=True)):
             L.out_blk.fill_(float("nan"))
             L.fwd_fused(**kw)
             torch.cuda.synchronize()
             got = L.get_output().float().cpu().numpy()
             ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias if "bias" in kw else None,
                                    residual=res if "residual" in kw else None,
-                                   relu=kw.get("relu", False))
+                                   relu=kw.get("relu", False), scale=scale if "scale" in kw else None)
             assert rel_l2(got, ref) <= TOL[dtype], kw.keys()
             if kw.get("relu"):
                 assert got.min() >= 0.0

@@ -324,6 +324,13 @@ def test_fused_forward_reduces_to_its_parts():
     only_b = oracle.fwd_fused(I, Wt, 1, 1, bias=b)
     for k in range(K):
         assert np.allclose(only_b[:, k] - plain[:, k], b[k], rtol=0, atol=1e-12)
+    # the per-channel scale is a rescaling of the filters of channel k (the convolution is
+    # linear in them): scale folded into the weights gives the same result
+    g = rng.uniform(0.5, 2.0, size=K) * np.array([1, -1, 1, -1])
+    scaled = oracle.fwd_fused(I, Wt, 1, 1, scale=g)
+    assert np.allclose(scaled, oracle.fwd(I, Wt * g[:, None, None, None], 1, 1), rtol=1e-13, atol=1e-13)
+    allops = oracle.fwd_fused(I, Wt, 1, 1, scale=g, bias=b, residual=res, relu=True)
+    assert np.allclose(allops, np.maximum(scaled + b[None, :, None, None] + res, 0.0), rtol=0, atol=1e-13)
 
 
 # ---------------------------------------------------------------- per-axis padding
