@@ -202,7 +202,7 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
             if (cd.fk == 2 && dtype != CONV_BF16) continue;
             const int TK = cd.wk * cd.fk * 32;
             if (TK > 64 && Kp <= TK / 2) continue;
-            if (TK == 32 && Kp > 32) continue;
+            if (TK == 32 && Kp > 96) continue;  // (three 32-row tiles at most: 80 rows waste less so)
             IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
                                     ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, cd.fm, caps[ci]);
             if (!c.ok) continue;
