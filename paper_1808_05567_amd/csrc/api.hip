@@ -47,6 +47,7 @@ struct conv_plan {
     bool upd_c4 = false;   // few-channel formulation (one input channel block)
     bool upd_c4_bf16 = false; // bf16, one input channel block: (tap, channel) rows on the bf16 MFMA
     bool upd_rows = false; // bf16 row kernel (stride 1)
+    int upd_bands_layout = 0;  // fp32 band kernel: 0 = 2x2 channel waves x 2 pixel groups, 1 = 1x2x4, 2 = 1x1x8
     bool upd_bands = false; // fp32 eight-wave band kernel
     bool upd_flat_bf16 = false; // bf16 1x1 eight-wave kernel on the flat pixel list (variant: urv)
     bool upd_flat = false;  // fp32 1x1 eight-wave kernel on the flat pixel list
@@ -682,9 +683,11 @@ void plan_upd(conv_plan *p)
     if (!bf16 && !sampled && d.stride == 1 && upd_f32_bands_exists(d.R, d.S)) {
         // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
         // bands; the pixel range is split so that one round of workgroups fills the chip.
-        const int NPI = 16, NPO = 16;
+        // Layers with at most 32 channels on the input side (and on both) take 32 x 64
+        // (32 x 32) blocks with four (eight) pixel groups where every strip has odd rows.
+        const int want = f.Cp <= 32 ? (f.Kp <= 32 ? 2 : 1) : 0;
+        int layout = upd_f32_bands_layout_exists(d.R, d.S, want, true) ? want : 0;
         const int NP = d.N * f.P;
-        const size_t xch = upd_f32_bands_exchange_bytes(d.R, d.S);
         UpdArgs &a = p->ua;
         memset(&a, 0, sizeof(a));
         a.N = d.N; a.Cb = f.Cb; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
@@ -695,11 +698,19 @@ void plan_upd(conv_plan *p)
         size_t lds = 0;
         // Rows too wide for two bands in the LDS are cut into up to four strips of output
         // columns, one launch per strip; beyond that the general kernel takes over.
-        int TR = 0, Qs = f.Q, n_strips = 1;
+        int TR = 0, Qs = f.Q, n_strips = 1, NPI = 16, NPO = 16;
+        for (int attempt = 0; attempt < 2 && TR < 1; ++attempt) {
+        if (attempt == 1) {
+            if (layout == 0) break;
+            layout = 0;  // no odd strips: the 64 x 64 layout
+        }
+        NPI = layout == 0 ? 16 : 8;
+        NPO = layout == 2 ? 8 : 16;
         for (n_strips = 1; n_strips <= 4; ++n_strips) {
             Qs = ceil_div(f.Q, n_strips);
             if (ceil_div(f.Q, Qs) != n_strips) continue;
             const int q_last = f.Q - (n_strips - 1) * Qs;
+            if (layout != 0 && ((Qs & 1) == 0 || (q_last & 1) == 0)) continue;
             a.LW = (Qs - 1) * d.stride + d.S;
             if (n_strips == 1) a.LW = std::max(a.LW, d.W + 2 * pad_w);
             // (rows with an odd number of pixel pairs are shared out whole: even bands)
@@ -716,6 +727,8 @@ void plan_upd(conv_plan *p)
             }
             if (TR >= 1) break;
         }
+        }
+        const size_t xch = upd_f32_bands_exchange_bytes(d.R, d.S, layout);
         a.Q = Qs;
         if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22)) {
             a.TR = TR;
@@ -737,6 +750,7 @@ void plan_upd(conv_plan *p)
             p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
             p->upd_strips = n_strips;
             p->upd_strip_w = Qs;
+            p->upd_bands_layout = layout;
             p->upd_bands = true;
             p->upd_ok = true;
             return;
@@ -1051,7 +1065,7 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
             a.q0 = st * h->upd_strip_w;
             a.Q = std::min(h->upd_strip_w, h->info.Q - a.q0);
             a.copy0 = st * a.splits;
-            e = launch_upd_f32_bands(h->d.R, h->d.S, a, h->upd_lds, h->upd_grid, s);
+            e = launch_upd_f32_bands(h->d.R, h->d.S, h->upd_bands_layout, a, h->upd_lds, h->upd_grid, s);
         }
     else
         for (int st = 0; st < h->upd_strips && e == hipSuccess; ++st) {
@@ -1187,9 +1201,11 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         }
         if (h->upd_bands) {
             snprintf(buf, buflen,
-                     "upd_bands dt=0 RS=%dx%d waves=2x2x2 frags=1x1 TR=%d splits=%d rows/split=%d "
+                     "upd_bands dt=0 RS=%dx%d waves=%s frags=1x1 TR=%d splits=%d rows/split=%d "
                      "tiles=%dx%d grid=%d lds=%zu launches=%d",
-                     h->d.R, h->d.S, h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct,
+                     h->d.R, h->d.S,
+                     h->upd_bands_layout == 0 ? "2x2x2" : h->upd_bands_layout == 1 ? "1x2x4" : "1x1x8",
+                     h->ua.TR, h->ua.splits, h->ua.rows_per_split, h->ua.n_ct,
                      h->ua.n_kt, h->upd_grid, h->upd_lds, h->upd_strips);
             return CONV_OK;
         }

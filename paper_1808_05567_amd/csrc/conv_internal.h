@@ -161,8 +161,10 @@ hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds
                            hipStream_t stream);
 // fp32, filters larger than 1x1: eight waves, double-buffered bands
 bool upd_f32_bands_exists(int r, int s);
-size_t upd_f32_bands_exchange_bytes(int r, int s);
-hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+// layout: 0 = 2 x 2 channel waves x 2 pixel groups, 1 = 1 x 2 x 4, 2 = 1 x 1 x 8
+bool upd_f32_bands_layout_exists(int r, int s, int layout, bool odd_rows);
+size_t upd_f32_bands_exchange_bytes(int r, int s, int layout);
+hipError_t launch_upd_f32_bands(int r, int s, int layout, const UpdArgs &a, size_t lds_bytes, int grid,
                                 hipStream_t stream);
 // bf16, 1x1 without padding: eight waves on the flat pixel list, bands of 64 pixels
 // (UpdArgs::rows_per_split = pixels per split, a multiple of 64)

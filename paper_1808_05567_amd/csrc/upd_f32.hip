@@ -23,13 +23,19 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ODDQ: rows of an odd number of pixels
-template <int R, int S, bool ODDQ>  // unit stride
+// WCC x WCK: waves along input / output channels (32 each); the other 8 / (WCC*WCK) wave
+// groups share the pixels.  2 x 2 (a 64 x 64 block of dW, two pixel groups) is the
+// workhorse; 1 x 2 and 1 x 1 serve layers with at most 32 channels on a side, where three
+// quarters of a 64 x 64 block would be padding (odd rows only).
+template <int R, int S, bool ODDQ, int WCC = 2, int WCK = 2>  // unit stride
 __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
 {
     constexpr int V = 4;
     constexpr int NT = 512, NW = NT / 64;
     constexpr int NTAPS = R * S;
-    constexpr int NPI = 16, NPO = 16;  // staged planes: 64 input and 64 output channels
+    constexpr int G = NW / (WCC * WCK);         // pixel groups
+    constexpr int NPI = WCC * 8, NPO = WCK * 8;  // staged planes of 4 input / output channels
+    static_assert(G == 2 || ODDQ, "more than two pixel groups: the odd-row path only");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int ibytes = NPI * a.PLS_in * 16;
@@ -41,9 +47,9 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same, known to be uniform
     const int h = lane >> 5;
     const int l32 = lane & 31;
-    const int wave_c = wave & 1;
-    const int wave_k = (wave >> 1) & 1;
-    const int wave_p = wave >> 2;
+    const int wave_c = wave % WCC;
+    const int wave_k = (wave / WCC) % WCK;
+    const int wave_p = wave / (WCC * WCK);
 
     const int bid = blockIdx.x;
     const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
@@ -100,25 +106,29 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
         // in equal contiguous runs: a wave computes the source offsets of one
         // chunk (rarely two) and issues its planes.
         const int nch_in = cov_in >> 6, nch_out = cov_out >> 6;
-        const int total = (nch_in + nch_out) * 16;  // NPI == NPO == 16
+        const int n_in = nch_in * NPI;
+        const int total = n_in + nch_out * NPO;
         const int share = (total + NW - 1) / NW;
         const int first = wave_u * share, last = min(total, first + share);
         int cur = -1;
         unsigned off = kOutOfRange;
         for (int e = first; e < last; ++e) {
-            const int ch = e >> 4, pl = e & 15;
-            if (ch != cur) {
-                cur = ch;
-                off = ch < nch_in ? in_off(ch * 64 + lane) : out_off((ch - nch_in) * 64 + lane);
+            const bool is_in = e < n_in;
+            const int u = is_in ? e : e - n_in;
+            const int ch = is_in ? u / NPI : u / NPO, pl = is_in ? u % NPI : u % NPO;
+            const int key = is_in ? ch : nch_in + ch;
+            if (key != cur) {
+                cur = key;
+                off = is_in ? in_off(ch * 64 + lane) : out_off(ch * 64 + lane);
             }
-            if (ch < nch_in)
+            if (is_in)
                 load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
                                (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
                                ib + (pl * a.PLS_in + ch * 64) * 16);
             else
                 load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                                (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
-                               ob + (pl * a.PLS_out + (ch - nch_in) * 64) * 16);
+                               ob + (pl * a.PLS_out + ch * 64) * 16);
         }
     };
 
@@ -160,7 +170,7 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
             const int npx = rows * a.Q;
             const int npairs = (npx + 1) >> 1;
 #pragma unroll 2
-            for (int pr = wave_p; pr < npairs; pr += 2) {
+            for (int pr = wave_p; pr < npairs; pr += G) {
                 const int p = 2 * pr + h;
                 const int pin = p < npx ? p : 0;
                 const int trow = fast_div(pin, inv_Q);
@@ -262,10 +272,41 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
         __syncthreads();
     }
 
-    // ---- the second pixel group hands its sums to the first through LDS
+    // ---- the other pixel groups hand their sums to the first through LDS
     // (all staged bands have been consumed: the last barrier is behind us)
-    f32x4 *xch = reinterpret_cast<f32x4 *>(lds) + (size_t)(wave & 3) * NTAPS * 4 * 64 + lane;
-    if (wave_p == 1) {
+    f32x4 *xch = reinterpret_cast<f32x4 *>(lds) + (size_t)(wave % (WCC * WCK)) * NTAPS * 4 * 64 + lane;
+    if constexpr (G > 2) {
+        // group after group in a fixed order; the first group adds each in turn
+#pragma unroll 1
+        for (int g = 1; g < G; ++g) {
+            if (wave_p == g) {
+#pragma unroll
+                for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const f32x4 v = {acc[t][4 * vq + 0], acc[t][4 * vq + 1], acc[t][4 * vq + 2],
+                                         acc[t][4 * vq + 3]};
+                        xch[(t * 4 + vq) * 64] = v;
+                    }
+            }
+            __syncthreads();
+            if (wave_p == 0 && g < G - 1) {
+#pragma unroll
+                for (int t = 0; t < NTAPS; ++t)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const f32x4 v = xch[(t * 4 + vq) * 64];
+                        acc[t][4 * vq + 0] += v[0];
+                        acc[t][4 * vq + 1] += v[1];
+                        acc[t][4 * vq + 2] += v[2];
+                        acc[t][4 * vq + 3] += v[3];
+                    }
+            }
+            if (g < G - 1) __syncthreads();
+        }
+        // (the last group's sums are still in the exchange buffer: added at the store below)
+        if (wave_p != 0) return;
+    } else if (wave_p == 1) {
 #pragma unroll
         for (int t = 0; t < NTAPS; ++t)
 #pragma unroll
@@ -275,8 +316,10 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
                 xch[(t * 4 + vq) * 64] = v;
             }
     }
-    __syncthreads();
-    if (wave_p == 1) return;
+    if constexpr (G == 2) {
+        __syncthreads();
+        if (wave_p == 1) return;
+    }
 
     // ---- write this split's partial dW tile: [split][cb][tap][k][c%V]
     const size_t copy = (size_t)a.Cb * NTAPS * a.Kp * V;
@@ -302,16 +345,44 @@ bool upd_f32_bands_exists(int r, int s)
     return (r == 3 && s == 3) || (r == 1 && (s == 3 || s == 7)) || (s == 1 && r == 3);
 }
 
-// LDS bytes the in-workgroup exchange of the two pixel groups needs
-size_t upd_f32_bands_exchange_bytes(int r, int s) { return (size_t)4 * r * s * 4 * 64 * 16; }
+// Wave layouts: 0 = 2 x 2 channel waves (64 x 64 block of dW) x 2 pixel groups,
+// 1 = 1 x 2 (32 x 64) x 4, 2 = 1 x 1 (32 x 32) x 8; layouts 1 and 2: 3x3, odd rows.
+bool upd_f32_bands_layout_exists(int r, int s, int layout, bool odd_rows)
+{
+    if (layout == 0) return upd_f32_bands_exists(r, s);
+    return (layout == 1 || layout == 2) && r == 3 && s == 3 && odd_rows;
+}
 
-hipError_t launch_upd_f32_bands(int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
+// LDS bytes the in-workgroup exchange of the pixel groups needs: one buffer of all the
+// taps' accumulators per channel-wave pair
+size_t upd_f32_bands_exchange_bytes(int r, int s, int layout)
+{
+    const int pairs = layout == 0 ? 4 : layout == 1 ? 2 : 1;
+    return (size_t)pairs * r * s * 4 * 64 * 16;
+}
+
+hipError_t launch_upd_f32_bands(int r, int s, int layout, const UpdArgs &a, size_t lds_bytes, int grid,
                                 hipStream_t stream)
 {
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
     const int odd = a.Q & 1;
     int slot = -1;
+    if (layout != 0) {
+        if (!upd_f32_bands_layout_exists(r, s, layout, odd != 0)) return hipErrorInvalidDeviceFunction;
+        fn = layout == 1 ? upd_f32_bands_kernel<3, 3, true, 1, 2> : upd_f32_bands_kernel<3, 3, true, 1, 1>;
+        static size_t attr2[2] = {0, 0};
+        size_t &at = attr2[layout - 1];
+        if (lds_bytes > at) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 (int)lds_bytes);
+            if (err != hipSuccess) return err;
+            at = lds_bytes;
+        }
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
+        return hipGetLastError();
+    }
 #define BANDS_CASE(IDX, RR, SS)                                                                 \
     if (r == RR && s == SS) {                                                                   \
         fn = odd ? upd_f32_bands_kernel<RR, SS, true> : upd_f32_bands_kernel<RR, SS, false>;    \

@@ -37,6 +37,11 @@ SMALL = [
     (1, 512, 256, 6, 6, 1, 1, 2, 0),      # 256 x 256 tile, stride 2
     (2, 256, 36, 5, 5, 1, 1, 1, 0),       # narrow side below 64 channels, a single ragged band
     (2, 16, 24, 3, 37, 1, 1, 1, 0),       # one odd row per flat band: staged with a zero pixel
+    # at most 32 channels on a side, odd rows (fp32 update: 32 x 64 and 32 x 32 blocks of dW,
+    # four and eight pixel groups)
+    (2, 32, 64, 9, 9, 3, 3, 1, 1),
+    (3, 32, 32, 11, 15, 3, 3, 1, 1),
+    (1, 8, 16, 5, 147, 3, 3, 1, 1),       # ... in strips of 49 columns
 ]
 
 
