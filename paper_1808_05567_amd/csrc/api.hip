@@ -684,8 +684,9 @@ void plan_upd(conv_plan *p)
         // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
         // bands; the pixel range is split so that one round of workgroups fills the chip.
         // Layers with at most 32 channels on the input side (and on both) take 32 x 64
-        // (32 x 32) blocks with four (eight) pixel groups where every strip has odd rows.
-        const int want = f.Cp <= 32 ? (f.Kp <= 32 ? 2 : 1) : 0;
+        // (32 x 32) blocks of dW with four (eight) pixel groups where every strip has odd rows.
+        // (65 to 96 input channels: three 32-channel blocks waste less than two of 64)
+        const int want = f.Cp <= 32 ? (f.Kp <= 32 ? 2 : 1) : (f.Cp > 64 && f.Cp <= 96 ? 1 : 0);
         int layout = upd_f32_bands_layout_exists(d.R, d.S, want, true) ? want : 0;
         const int NP = d.N * f.P;
         UpdArgs &a = p->ua;
