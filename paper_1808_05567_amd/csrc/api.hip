@@ -93,7 +93,11 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
 {
     IgemmPlan pl;
     const int V = vlen_of(dtype);
-    const bool sampled = (R == 1 && S == 1 && pad_h == 0 && pad_w == 0);
+    // (1x1, no padding: only the pixels that are read are staged -- valid where every output
+    // pixel has its input pixel; a residue class of a strided backward pass can be one row or
+    // column larger than its input, which then needs the zero rows of the padded row space)
+    const bool sampled = (R == 1 && S == 1 && pad_h == 0 && pad_w == 0 && (P - 1) * stride < H &&
+                          (Q - 1) * stride < W);
 
     int npl;
     if (R == 1 && S == 1)

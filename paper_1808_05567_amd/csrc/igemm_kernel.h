@@ -45,6 +45,15 @@ struct Elem<CONV_F32> {
         u32x4 v = {__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2),
                    __float_as_uint(x3)};
         __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, uniform_off, 0);
+        // A 16-byte buffer store reads its data registers over several cycles.  The compiler
+        // guards a VALU write to them right behind the store only where the store has no
+        // scalar offset; with one (as here) it places the write directly behind the store,
+        // and on gfx950 the first data register of the last lanes of each 16-lane group was
+        // then stored with the new value (seen as sporadic wrong partial results).  Two
+        // wait states pinned behind the store close the window.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 1");
+        __builtin_amdgcn_sched_barrier(0);
     }
 };
 

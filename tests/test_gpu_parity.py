@@ -77,6 +77,15 @@ RECT = [
     (1, 8, 8, 6, 140, 1, 7, 1, (0, 3)),
     (1, 8, 16, 7, 141, 3, 3, 2, 0),
     (2, 3, 32, 37, 301, 3, 3, 2, 0),          # first layer of a 299-wide network, widened
+    # unpadded stride 2 on an even extent: a residue class of the backward pass is one
+    # row / column larger than dO (its 1x1 sub-filter must not take the sampled staging)
+    (2, 20, 16, 32, 22, 3, 3, 2, 0),
+    (3, 264, 48, 8, 14, 3, 3, 2, (0, 1)),
+    (2, 48, 256, 29, 10, 3, 3, 2, (1, 0)),
+    # forward reduction split over workgroups with one channel block per step: fp32 partial
+    # results through 16-byte buffer stores (wait states behind the store)
+    (1, 264, 256, 23, 39, 1, 1, 1, 0),
+    (4, 130, 256, 11, 134, 1, 3, 1, 0),
 ]
 
 
