@@ -143,6 +143,23 @@ def _sweep_shapes():
         K = int(rng.choice([8, 24, 40, 96]))
         N = int(rng.integers(1, 4))
         out.append((N, C, K, H, W, R, S, stride, (ph, pw)))
+    # a second batch with wider channel counts and images (long reductions at small N: split
+    # forward reductions; wide rows: column strips; 7x7)
+    filters = filters + [(7, 7), (3, 3), (1, 1)]
+    while len(out) < 70:
+        R, S = filters[int(rng.integers(0, len(filters)))]
+        stride = int(rng.choice([1, 1, 2])) if R == S else 1
+        ph, pw = int(rng.integers(0, R // 2 + 1)), int(rng.integers(0, S // 2 + 1))
+        H = int(rng.integers(max(R, 3), 40))
+        W = int(rng.integers(max(S, 3), 160 if len(out) % 3 == 0 else 40))
+        C = int(rng.choice([3, 4, 8, 20, 32, 48, 72, 80, 96, 130, 264]))
+        if R == 7 and S == 7:
+            C = 3 + int(C % 2)  # (7x7 kernels exist for first layers only)
+        K = int(rng.choice([8, 24, 32, 40, 64, 96, 136, 256]))
+        N = int(rng.integers(1, 5))
+        if N * C * H * W > 3e6 or N * K * H * W > 3e6:
+            N = 1
+        out.append((N, C, K, H, W, R, S, stride, (ph, pw)))
     return out
 
 
