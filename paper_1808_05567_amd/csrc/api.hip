@@ -684,7 +684,8 @@ void plan_upd(conv_plan *p)
     }
     p->upd_bands = false;
     // (this kernel takes the two pads separately)
-    if (!bf16 && !sampled && d.stride == 1 && upd_f32_bands_exists(d.R, d.S)) {
+    // (stride > 1: its odd-row path only, which addresses every pixel on its own)
+    if (!bf16 && !sampled && upd_f32_bands_exists(d.R, d.S)) {
         // fp32 band kernel: 64 x 64 channel tile, one workgroup per CU, the LDS holds two
         // bands; the pixel range is split so that one round of workgroups fills the chip.
         // Layers with at most 32 channels on the input side (and on both) take 32 x 64
@@ -715,7 +716,7 @@ void plan_upd(conv_plan *p)
             Qs = ceil_div(f.Q, n_strips);
             if (ceil_div(f.Q, Qs) != n_strips) continue;
             const int q_last = f.Q - (n_strips - 1) * Qs;
-            if (layout != 0 && ((Qs & 1) == 0 || (q_last & 1) == 0)) continue;
+            if ((layout != 0 || d.stride > 1) && ((Qs & 1) == 0 || (q_last & 1) == 0)) continue;
             a.LW = (Qs - 1) * d.stride + d.S;
             if (n_strips == 1) a.LW = std::max(a.LW, d.W + 2 * pad_w);
             // (rows with an odd number of pixel pairs are shared out whole: even bands)
@@ -733,6 +734,8 @@ void plan_upd(conv_plan *p)
             if (TR >= 1) break;
         }
         }
+        // (strided: bands of a single output row lose to the four-wave kernel)
+        if (d.stride > 1 && TR < 2) TR = 0;
         const size_t xch = upd_f32_bands_exchange_bytes(d.R, d.S, layout);
         a.Q = Qs;
         if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22)) {
