@@ -45,6 +45,13 @@ def build_lib(verbose: bool = True) -> str:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
+    # every symbol must resolve (a kernel instantiation the host pass dropped would only
+    # show up when the library is loaded): load it in a child process before installing it
+    r = subprocess.run([sys.executable, "-c", "import ctypes, sys; ctypes.CDLL(sys.argv[1])", tmp],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        os.unlink(tmp)
+        raise RuntimeError("the built library does not load:\n" + r.stderr)
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB)
