@@ -288,6 +288,34 @@ def test_upd_is_bitwise_deterministic():
         L.close()
 
 
+REPEAT = [
+    (1, 264, 256, 23, 39, 1, 1, 1, 0),    # split forward reduction, 16-byte partial stores
+    (4, 130, 256, 11, 134, 1, 3, 1, 0),
+    (16, 64, 64, 28, 28, 3, 3, 1, 1),
+    (8, 256, 128, 14, 14, 1, 1, 2, 0),
+    (4, 32, 64, 35, 35, 3, 3, 1, 1),      # four pixel groups folded through LDS
+    (2, 3, 64, 64, 64, 7, 7, 2, 3),
+    (4, 96, 96, 17, 17, 7, 1, 1, (3, 0)),
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", REPEAT, ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
+def test_every_pass_repeats_bit_for_bit(shape, dtype):
+    """No result may depend on timing: fixed-order reductions everywhere, and no store whose
+    data a later instruction can overtake.  Four runs of each pass give identical bits."""
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=9)
+    L = _layer(shape, dtype)
+    try:
+        for which in ("fwd", "bwd", "upd"):
+            first = run_pass(L, which, I=I, Wt=Wt, dO=dO)
+            assert np.isfinite(first).all(), which
+            for _ in range(3):
+                assert np.array_equal(first, run_pass(L, which, I=I, Wt=Wt, dO=dO)), which
+    finally:
+        L.close()
+
+
 FUSED = [
     (2, 64, 64, 14, 14, 3, 3, 1, 1),      # reduction split over workgroups: operators in the reduce
     (5, 128, 128, 28, 28, 3, 3, 1, 1),    # many tiles: operators in the convolution's store
