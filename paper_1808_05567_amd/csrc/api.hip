@@ -362,20 +362,13 @@ void plan_bwd(conv_plan *p)
     p->bwd_ws = off;
 }
 
-void plan_upd(conv_plan *p)
+// Weight update, bf16, at most 4 input channels: (tap, channel) rows on the bf16 MFMA.
+bool plan_upd_c4_bf16(conv_plan *p)
 {
     const conv_desc_t &d = p->d;
     const conv_info_t &f = p->info;
-    p->upd_ok = false;
-    p->upd_ws = 0;
     const int pad_h = p->pad_h, pad_w = p->pad_w;
-    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
     const bool bf16 = d.dtype == CONV_BF16;
-    const bool square_pad = pad_h == pad_w;  // the filter-specific kernels take one pad
-    p->upd_row_launches = 1;
-    p->upd_strips = 1;
-    p->upd_c4 = false;
-    p->upd_c4_bf16 = false;
     if (bf16 && d.C <= 4 && upd_c4_bf16_exists(d.R, d.S)) {
         // one input channel block, bf16: (tap, channel) rows on the bf16 MFMA, eight waves,
         // two LDS buffers holding the bands as they sit in HBM
@@ -429,8 +422,19 @@ void plan_upd(conv_plan *p)
             p->upd_ok = true;
             return true;
         };
-        if (plan_c4_bf16()) return;
+        if (plan_c4_bf16()) return true;
     }
+    return false;
+}
+
+// Weight update, at most 4 input channels, fp32 MFMA (fp32 tensors, or bf16 widened into LDS).
+bool plan_upd_c4(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool bf16 = d.dtype == CONV_BF16;
+    const bool square_pad = pad_h == pad_w;  // the filter-specific kernels take one pad
     if (d.C <= 4 && square_pad && ((d.R == 7 && d.S == 7) || (d.R == 3 && d.S == 3))) {
         // (a plan that does not fit leaves the layer to the general kernels)
         auto plan_c4 = [&]() -> bool {
@@ -483,9 +487,19 @@ void plan_upd(conv_plan *p)
             p->upd_ok = true;
             return true;
         };
-        if (plan_c4()) return;
+        if (plan_c4()) return true;
     }
-    p->upd_flat = false;
+    return false;
+}
+
+// Weight update, fp32 1x1 without padding: flat pixel list, eight waves.
+bool plan_upd_flat_f32(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
+    const bool bf16 = d.dtype == CONV_BF16;
     if (!bf16 && sampled) {
         // fp32 1x1: 256 channels of the wider tensor x up to 256 of the other per workgroup,
         // the pixel list split so that one round of workgroups fills the chip
@@ -526,10 +540,20 @@ void plan_upd(conv_plan *p)
             p->upd_flat = true;
             (void)wp;
             p->upd_ok = true;
-            return;
+            return true;
         }
     }
-    p->upd_flat_bf16 = false;
+    return false;
+}
+
+// Weight update, bf16 1x1 without padding: flat pixel list.
+bool plan_upd_flat_bf16(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
+    const bool bf16 = d.dtype == CONV_BF16;
     if (bf16 && sampled && (double)d.N * f.P * f.Q < 4.0e6 &&
         (double)(d.N + 1) * std::max(f.Cb, f.Kb) < 8.0e6 && (double)d.H * d.W < 8.0e6 &&
         (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 && (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
@@ -577,10 +601,20 @@ void plan_upd(conv_plan *p)
             p->upd_ws = (size_t)p->upd_copies * f.dwt_bytes;
             p->upd_flat_bf16 = true;
             p->upd_ok = true;
-            return;
+            return true;
         }
     }
-    p->upd_rows = false;
+    return false;
+}
+
+// Weight update, bf16 row kernel (8-pixel runs).
+bool plan_upd_rows(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
+    const bool bf16 = d.dtype == CONV_BF16;
     // (this kernel takes the two pads separately)
     const bool rows_strided = d.stride > 1 && d.R == 3 && d.S == 3;
     const bool rows_5x5 = d.stride == 1 && d.R == 5 && d.S == 5;  // one launch per filter row
@@ -677,12 +711,22 @@ void plan_upd(conv_plan *p)
                     p->upd_row_launches = rows_R == d.R ? 1 : d.R;
                     p->upd_rows = true;
                     p->upd_ok = true;
-                    return;
+                    return true;
                 }
             }
         }
     }
-    p->upd_bands = false;
+    return false;
+}
+
+// Weight update, fp32 band kernel.
+bool plan_upd_bands(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
+    const bool bf16 = d.dtype == CONV_BF16;
     // (this kernel takes the two pads separately)
     // (stride > 1: its odd-row path only, which addresses every pixel on its own)
     if (!bf16 && !sampled && upd_f32_bands_exists(d.R, d.S)) {
@@ -761,9 +805,20 @@ void plan_upd(conv_plan *p)
             p->upd_bands_layout = layout;
             p->upd_bands = true;
             p->upd_ok = true;
-            return;
+            return true;
         }
     }
+    return false;
+}
+
+// Weight update, general four-wave kernels (any remaining filter the kernels cover).
+void plan_upd_general(conv_plan *p)
+{
+    const conv_desc_t &d = p->d;
+    const conv_info_t &f = p->info;
+    const int pad_h = p->pad_h, pad_w = p->pad_w;
+    const bool sampled = (d.R == 1 && d.S == 1 && pad_h == 0 && pad_w == 0);
+    const bool bf16 = d.dtype == CONV_BF16;
     // General kernels.  3x3 and 1x1 in one launch; any other filter with S in {1, 3, 5, 7} as
     // one launch of the 1 x S kernel per filter row r (run with pad_h - r rows of padding,
     // writing taps [r*S, (r+1)*S) of the partial copies).
@@ -865,6 +920,25 @@ void plan_upd(conv_plan *p)
     p->upd_copies = splits * n_strips;
     p->upd_ws = (size_t)splits * n_strips * f.dwt_bytes;
     p->upd_ok = true;
+}
+
+void plan_upd(conv_plan *p)
+{
+    p->upd_ok = false;
+    p->upd_ws = 0;
+    p->upd_row_launches = 1;
+    p->upd_strips = 1;
+    p->upd_c4 = false;
+    p->upd_c4_bf16 = false;
+    p->upd_flat = false;
+    p->upd_flat_bf16 = false;
+    p->upd_rows = false;
+    p->upd_bands = false;
+    // the kernels written for a family of layers first, each declining what it does not fit
+    if (plan_upd_c4_bf16(p) || plan_upd_c4(p) || plan_upd_flat_f32(p) || plan_upd_flat_bf16(p) ||
+        plan_upd_rows(p) || plan_upd_bands(p))
+        return;
+    plan_upd_general(p);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
