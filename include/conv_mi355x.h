@@ -58,7 +58,7 @@ typedef enum {
     CONV_OK = 0,
     CONV_EINVAL = 1,       /* NULL pointer, non-positive extent, negative pad,
                               empty output, unknown dtype, misaligned pointer  */
-    CONV_EUNSUPPORTED = 2, /* valid problem the kernels cannot run             */
+    CONV_EUNSUPPORTED = 2, /* valid problem beyond the kernels' launch limits  */
     CONV_EWORKSPACE = 3,   /* workspace required but ws == NULL                */
     CONV_ELAUNCH = 4       /* the HIP runtime refused a launch                 */
 } conv_status_t;
@@ -95,8 +95,13 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
  * the same reading of padding applied to each axis on its own.  It serves the 1xS and
  * Rx1 filters of Inception-style layers, which pad along their long side only (the paper
  * reports averages over such a topology next to ResNet-50, Section III).  Everything else
- * is as for conv_create: CONV_EINVAL for a negative pad or an empty output; a pass whose
- * filter shape no kernel serves returns CONV_EUNSUPPORTED when it is called. */
+ * is as for conv_create: CONV_EINVAL for a negative pad or an empty output.
+ * Every accepted descriptor has all three passes.  Filters the tiled MFMA kernels are
+ * instantiated for (1x1, 3x3, 5x5, 1x3, 3x1, 1x7, 7x1, and 7x7 where a staged tile fits
+ * the LDS) run on those; any other filter, stride or row width runs the plain loop nests of
+ * Algorithms 1, 5 and 8, one result element per thread, at a small fraction of that rate
+ * (conv_describe names the kernel: "direct ...").  CONV_EUNSUPPORTED is left for tensors
+ * beyond the launch limits (more than 2^39 elements). */
 conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
                                conv_handle_t *out);
 conv_status_t conv_destroy(conv_handle_t h);

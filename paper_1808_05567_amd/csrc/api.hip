@@ -63,6 +63,9 @@ struct conv_plan {
     size_t upd_lds = 0;
     int upd_grid = 0;
     size_t upd_ws = 0;
+    // passes no tiled kernel fits run on the untiled direct kernels (no workspace)
+    bool fwd_direct = false, bwd_direct = false, upd_direct = false;
+    DirectArgs da{};
 };
 
 namespace {
@@ -1015,7 +1018,23 @@ conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t p
     }
     plan_bwd(p);
     plan_upd(p);
-    f.upd_splits = p->upd_ok ? p->upd_copies : 0;
+    // A pass without a tiled plan falls to the direct kernels (any filter, stride and pad).
+    if (direct_fits(d.dtype, d.N, f.Cb, f.Kb, d.H, d.W, f.P, f.Q, d.R, d.S)) {
+        p->fwd_direct = !p->fwd.ok;
+        p->bwd_direct = p->bwd_mode == 0;
+        p->upd_direct = !p->upd_ok;
+        DirectArgs &a = p->da;
+        a = DirectArgs{};
+        a.N = d.N; a.Cb = f.Cb; a.Kb = f.Kb; a.H = d.H; a.W = d.W; a.P = f.P; a.Q = f.Q;
+        a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad_h = pad_h; a.pad_w = pad_w;
+        if (p->fwd_direct) p->fwd_ws = 0;
+        if (p->bwd_direct) p->bwd_ws = 0;
+        if (p->upd_direct) {
+            p->upd_ws = 0;
+            p->upd_copies = 1;  // dW is written once, by the kernel itself
+        }
+    }
+    f.upd_splits = (p->upd_ok || p->upd_direct) ? p->upd_copies : 0;
     f.workspace_bytes = std::max(std::max(p->bwd_ws, p->upd_ws), p->fwd_ws);
     *out = p;
     return CONV_OK;
@@ -1050,6 +1069,17 @@ conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *w
     if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws) || !aligned16(bias) ||
         !aligned16(residual) || !aligned16(scale))
         return CONV_EINVAL;
+    if (h->fwd_direct) {
+        DirectArgs a = h->da;
+        a.x = in;
+        a.wt = wt;
+        a.y = out;
+        a.scale = scale;
+        a.bias = bias;
+        a.resid = residual;
+        a.relu = relu != 0;
+        return launch_direct_fwd(h->d.dtype, a, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+    }
     if (!h->fwd.ok) return CONV_EUNSUPPORTED;
     IgemmArgs a = h->fwd.a;
     const bool split = a.ksplit > 1;
@@ -1082,6 +1112,13 @@ conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, v
 {
     if (!h || !dout || !wt || !din) return CONV_EINVAL;
     if (!aligned16(dout) || !aligned16(wt) || !aligned16(din) || !aligned16(ws)) return CONV_EINVAL;
+    if (h->bwd_direct) {
+        DirectArgs a = h->da;
+        a.x = dout;
+        a.wt = wt;
+        a.y = din;
+        return launch_direct_bwd(h->d.dtype, a, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+    }
     if (h->bwd_mode == 0) return CONV_EUNSUPPORTED;
     if (!ws) return CONV_EWORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -1113,6 +1150,13 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
 {
     if (!h || !in || !dout || !dwt) return CONV_EINVAL;
     if (!aligned16(in) || !aligned16(dout) || !aligned16(dwt) || !aligned16(ws)) return CONV_EINVAL;
+    if (h->upd_direct) {
+        DirectArgs a = h->da;
+        a.x = in;
+        a.wt = dout;
+        a.y = dwt;
+        return launch_direct_upd(h->d.dtype, a, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+    }
     if (!h->upd_ok) return CONV_EUNSUPPORTED;
     if (!ws) return CONV_EWORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -1234,6 +1278,16 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
 {
     if (!h || !buf || buflen == 0) return CONV_EINVAL;
     buf[0] = 0;
+    if ((pass == 0 && h->fwd_direct) || (pass == 1 && h->bwd_direct) || (pass == 2 && h->upd_direct)) {
+        const DirectArgs &a = h->da;
+        const int V = h->info.vlen;
+        const size_t grid = pass == 0   ? ((size_t)a.N * a.Kb * a.P * a.Q * V + 255) / 256
+                            : pass == 1 ? ((size_t)a.N * a.Cb * a.H * a.W * V + 255) / 256
+                                        : (size_t)a.Cb * a.R * a.S * a.Kb;
+        snprintf(buf, buflen, "direct dt=%d RS=%dx%d stride=%d threads=256 grid=%zu lds=%d launches=1",
+                 (int)h->d.dtype, a.R, a.S, a.stride, grid, pass == 2 ? 4 * V * V * 4 : 0);
+        return CONV_OK;
+    }
     if (pass == 0 || pass == 1) {
         const IgemmPlan *p = pass == 0 ? &h->fwd : &h->bwd[0].p;
         if (pass == 1 && h->bwd_mode == 0) return CONV_EUNSUPPORTED;

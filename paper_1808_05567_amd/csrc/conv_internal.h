@@ -187,6 +187,26 @@ hipError_t launch_upd_c4_bf16(int r, int s, const UpdArgs &a, size_t lds_bytes, 
 hipError_t launch_upd_reduce(const float *partial, float *dwt, size_t n_elems, int splits,
                              hipStream_t stream);
 
+// Untiled direct kernels for descriptors outside the tiled kernels' reach: any filter,
+// stride and per-axis pad.  x / wt / y are (input, weights, output) for the forward pass,
+// (dO, weights, dI) for backward by data and (input, dO, fp32 dW) for the update.
+struct DirectArgs {
+    const void *x;
+    const void *wt;
+    void *y;
+    int N, Cb, Kb, H, W, P, Q, R, S, stride, pad_h, pad_w;
+    // forward only: operators applied to the result (null / 0: none)
+    const float *scale;
+    const float *bias;
+    const void *resid;
+    int relu;
+};
+// whether the grids of the three passes fit the launch limits
+bool direct_fits(int dtype, int N, int Cb, int Kb, int H, int W, int P, int Q, int R, int S);
+hipError_t launch_direct_fwd(int dtype, const DirectArgs &a, hipStream_t stream);
+hipError_t launch_direct_bwd(int dtype, const DirectArgs &a, hipStream_t stream);
+hipError_t launch_direct_upd(int dtype, const DirectArgs &a, hipStream_t stream);
+
 // Layout conversion (pure permutations).
 hipError_t launch_pack_act(int dtype, const void *nchw, void *blk, int N, int C, int H, int W,
                            hipStream_t stream);

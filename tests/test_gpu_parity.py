@@ -42,6 +42,7 @@ SMALL = [
     (2, 32, 64, 9, 9, 3, 3, 1, 1),
     (3, 32, 32, 11, 15, 3, 3, 1, 1),
     (1, 8, 16, 5, 147, 3, 3, 1, 1),       # ... in strips of 49 columns
+    (3, 40, 72, 10, 13, 7, 7, 2, 3),      # 7x7 stride 2 over many channels (fp32 forward: direct kernel)
 ]
 
 
@@ -88,9 +89,45 @@ RECT = [
     (4, 130, 256, 11, 134, 1, 3, 1, 0),
 ]
 
+# descriptors outside the tiled kernels' tables: these run (in at least one pass) on the
+# untiled direct kernels, which take any filter, stride and per-axis pad
+DIRECT = [
+    (2, 64, 32, 12, 12, 7, 7, 1, 3),          # 7x7 over many channels
+    (2, 20, 24, 9, 11, 1, 5, 1, (0, 2)),
+    (2, 24, 16, 11, 9, 5, 1, 2, (2, 0)),
+    (2, 8, 16, 10, 10, 2, 2, 2, 0),           # non-overlapping 2x2 windows
+    (2, 12, 20, 9, 9, 4, 4, 1, 1),            # even filter
+    (1, 12, 8, 9, 8, 4, 3, 3, (1, 2)),        # stride 3, unequal pads
+    (1, 16, 16, 8, 120, 7, 1, 1, (3, 0)),     # tall filter over rows wider than a staged tile
+    (2, 8, 8, 6, 6, 6, 6, 1, 0),              # filter as large as the image: one output pixel
+    (300, 8, 8, 5, 5, 2, 2, 1, 1),            # more pixels than one pass of the update's 256 threads
+]
+
 
 def _layer(shape, dtype):
     return conv.ConvLayer(*shape, dtype=dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", DIRECT, ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
+def test_direct_kernels_match_oracle(shape, dtype):
+    """Algorithms 1, 5 and 8 as plain loop nests over the blocked layouts, for descriptors no
+    tiled kernel fits: every pass has a kernel and matches the oracle."""
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, dO = make_inputs(shape, dtype, layer_id=41)
+    L = _layer(shape, dtype)
+    try:
+        kinds = [conv.conv_describe(L.h, w).split()[0] for w in
+                 (conv.PASS_FWD, conv.PASS_BWD_DATA, conv.PASS_UPD)]
+        assert "direct" in kinds, kinds
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+        assert rel_l2(got, oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        got = run_pass(L, "bwd", dO=dO, Wt=Wt)
+        assert rel_l2(got, oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        got = run_pass(L, "upd", I=I, dO=dO)
+        assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+    finally:
+        L.close()
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -167,8 +204,7 @@ def _sweep_shapes():
 @pytest.mark.parametrize("shape", _sweep_shapes(), ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
 def test_seeded_descriptor_sweep_matches_oracle(shape, dtype):
     """Seeded descriptors over the filter shapes, strides and per-axis pads the library
-    accepts: every pass that has a plan matches the oracle (a pass without one reports
-    CONV_EUNSUPPORTED at its entry point and is skipped here)."""
+    accepts: every pass matches the oracle, on a tiled kernel or on the direct one."""
     N, C, K, H, W, R, S, stride, pad = shape
     I, Wt, dO = make_inputs(shape, dtype, layer_id=77)
     L = _layer(shape, dtype)
@@ -178,16 +214,12 @@ def test_seeded_descriptor_sweep_matches_oracle(shape, dtype):
                 ("fwd", lambda: oracle.fwd(I, Wt, stride, pad), TOL[dtype]),
                 ("bwd", lambda: oracle.bwd_data(dO, Wt, H, W, stride, pad), TOL[dtype]),
                 ("upd", lambda: oracle.upd(I, dO, R, S, stride, pad), 1e-5)):
-            try:
-                got = run_pass(L, which, I=I, Wt=Wt, dO=dO)
-            except conv.ConvError as e:
-                assert e.status == conv.CONV_EUNSUPPORTED
-                continue
+            got = run_pass(L, which, I=I, Wt=Wt, dO=dO)
             assert rel_l2(got, ref()) <= tol, which
             ran += 1
     finally:
         L.close()
-    assert ran >= 2, "at most one pass of a sweep descriptor may lack a kernel"
+    assert ran == 3
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -225,8 +257,9 @@ def test_first_layer_backward_bf16(shape):
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", [(3, 32, 48, 14, 14, 3, 3, 1, 1), (2, 64, 32, 12, 12, 1, 1, 2, 0),
-                                   (2, 288, 96, 10, 10, 1, 1, 2, 0)],
-                         ids=["3x3", "1x1s2", "1x1s2wide"])
+                                   (2, 288, 96, 10, 10, 1, 1, 2, 0), (2, 8, 8, 6, 6, 6, 6, 1, 0),
+                                   (2, 12, 20, 9, 9, 4, 4, 2, 1)],
+                         ids=["3x3", "1x1s2", "1x1s2wide", "6x6direct", "4x4s2direct"])
 def test_integer_inputs_are_exact(shape, dtype):
     """Small integers: every product and partial sum is exact in fp32 (and the
     values are exact in bf16), so any summation order gives the oracle's bits."""
@@ -296,6 +329,8 @@ REPEAT = [
     (4, 32, 64, 35, 35, 3, 3, 1, 1),      # four pixel groups folded through LDS
     (2, 3, 64, 64, 64, 7, 7, 2, 3),
     (4, 96, 96, 17, 17, 7, 1, 1, (3, 0)),
+    (300, 8, 8, 5, 5, 2, 2, 1, 1),        # the untiled direct kernels: update ...
+    (8, 20, 24, 9, 11, 1, 5, 1, (0, 2)),  # ... forward and backward
 ]
 
 
@@ -323,6 +358,7 @@ FUSED = [
     (2, 20, 24, 8, 8, 3, 3, 1, 1),        # padded channel slots stay zero
     (2, 48, 72, 17, 17, 1, 7, 1, (0, 3)),  # rectangular filter, padding along one axis
     (2, 32, 40, 13, 13, 3, 3, 2, 0),       # unpadded stride 2
+    (2, 20, 24, 9, 11, 1, 5, 1, (0, 2)),   # a filter only the direct kernel serves
 ]
 
 
