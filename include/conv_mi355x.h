@@ -104,6 +104,17 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
  * beyond the launch limits (more than 2^39 elements). */
 conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
                                conv_handle_t *out);
+/* As conv_create_rect, with the minibatch run in chunks of at most max_images images
+ * (>= 1; CONV_EINVAL otherwise): every pass launches its kernels once per chunk on that
+ * chunk's slice of the tensors (images are independent in Algorithms 1 and 6; Algorithm 8
+ * sums over them, so conv_upd writes one dW per chunk into the workspace and adds them in
+ * chunk order: still one fixed order).  The tensors, their layouts and every entry point
+ * stay the same; conv_query reports the workspace the chunked plan needs.  It bounds the
+ * workspace of large minibatches.  conv_create and conv_create_rect choose chunks by
+ * themselves in one case only: tensors of 4 GB or more, which the tiled kernels' 32-bit
+ * byte offsets do not reach in one launch. */
+conv_status_t conv_create_chunked(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
+                                  int32_t max_images, conv_handle_t *out);
 conv_status_t conv_destroy(conv_handle_t h);
 conv_status_t conv_query(conv_handle_t h, conv_info_t *info);
 const char *conv_status_str(conv_status_t s);

@@ -19,7 +19,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_UPD = 0, 1, 2
 CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5)
 
 EXPORTS = (
-    "conv_create", "conv_create_rect", "conv_destroy", "conv_query", "conv_status_str",
+    "conv_create", "conv_create_rect", "conv_create_chunked", "conv_destroy", "conv_query", "conv_status_str",
     "conv_fwd", "conv_fwd_fused", "conv_fwd_fused_norm", "conv_bwd_data", "conv_upd",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
@@ -69,6 +69,8 @@ def load():
     lib.conv_create.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(vp)]
     lib.conv_create_rect.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_int32, ctypes.c_int32,
                                      ctypes.POINTER(vp)]
+    lib.conv_create_chunked.argtypes = [ctypes.POINTER(ConvDesc), ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.POINTER(vp)]
     lib.conv_destroy.argtypes = [vp]
     lib.conv_query.argtypes = [vp, ctypes.POINTER(ConvInfo)]
     lib.conv_status_str.argtypes = [ctypes.c_int]
@@ -130,6 +132,16 @@ def conv_create_rect(N, C, K, H, W, R, S, stride, pad_h, pad_w, dtype=CONV_F32):
     h = ctypes.c_void_p()
     _check(load().conv_create_rect(ctypes.byref(d), int(pad_h), int(pad_w), ctypes.byref(h)),
            "conv_create_rect")
+    return h
+
+
+def conv_create_chunked(N, C, K, H, W, R, S, stride, pad, max_images, dtype=CONV_F32):
+    """The minibatch in chunks of at most ``max_images`` images per launch."""
+    ph, pw = pad if isinstance(pad, (tuple, list)) else (pad, pad)
+    d = ConvDesc(N, C, K, H, W, R, S, stride, 0, dtype)
+    h = ctypes.c_void_p()
+    _check(load().conv_create_chunked(ctypes.byref(d), int(ph), int(pw), int(max_images),
+                                      ctypes.byref(h)), "conv_create_chunked")
     return h
 
 
@@ -197,14 +209,18 @@ class ConvLayer:
     NCHW / KCRS; all computation and all layout conversion is done by the
     library's kernels."""
 
-    def __init__(self, N, C, K, H, W, R, S, stride, pad, dtype=CONV_F32, device="cuda:0"):
+    def __init__(self, N, C, K, H, W, R, S, stride, pad, dtype=CONV_F32, device="cuda:0",
+                 max_images=None):
         import torch
         self.torch = torch
         self.shape = (N, C, K, H, W, R, S, stride, pad)
         self.dtype = dtype
         self.tdtype = torch.bfloat16 if dtype == CONV_BF16 else torch.float32
         self.device = torch.device(device)
-        self.h = conv_create(N, C, K, H, W, R, S, stride, pad, dtype)
+        if max_images is None:
+            self.h = conv_create(N, C, K, H, W, R, S, stride, pad, dtype)
+        else:
+            self.h = conv_create_chunked(N, C, K, H, W, R, S, stride, pad, max_images, dtype)
         self.info = conv_query(self.h)
         es = 2 if dtype == CONV_BF16 else 4
         i = self.info

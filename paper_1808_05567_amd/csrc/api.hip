@@ -66,6 +66,18 @@ struct conv_plan {
     // passes no tiled kernel fits run on the untiled direct kernels (no workspace)
     bool fwd_direct = false, bwd_direct = false, upd_direct = false;
     DirectArgs da{};
+    // The minibatch in chunks of chunk_n images (the last chunk has the rest), each a plan of
+    // its own run on its slice of the tensors: for tensors beyond the tiled kernels' 32-bit
+    // byte offsets, or on request.  n_chunks == 0: none.
+    int n_chunks = 0, chunk_n = 0;
+    conv_plan *chunk = nullptr, *tail = nullptr;  // owned; tail: the last chunk if it is smaller
+    bool fwd_chunked = false, bwd_chunked = false, upd_chunked = false;
+    size_t chunk_ws = 0;  // the chunks' own workspace; the per-chunk dW results follow it
+    ~conv_plan()
+    {
+        delete chunk;
+        delete tail;
+    }
 };
 
 namespace {
@@ -785,7 +797,9 @@ bool plan_upd_bands(conv_plan *p)
         if (d.stride > 1 && TR < 2) TR = 0;
         const size_t xch = upd_f32_bands_exchange_bytes(d.R, d.S, layout);
         a.Q = Qs;
-        if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22)) {
+        // (the band kernel addresses both tensors with 32-bit byte offsets)
+        if (TR >= 1 && (double)(d.N + 1) * a.Hs < 4.0e6 && a.LRW < (1 << 22) &&
+            (double)f.in_bytes < 4.0e9 && (double)f.out_bytes < 4.0e9) {
             a.TR = TR;
             a.n_ct = ceil_div(f.Cb, NPI);
             a.n_kt = ceil_div(f.Kb, NPO);
@@ -919,6 +933,8 @@ void plan_upd_general(conv_plan *p)
     p->uv = v;
     p->upd_lds = ((size_t)NPI * a.PLS_in + (size_t)NPO * a.PLS_out) * 16;
     if (p->upd_lds > (size_t)kMaxLds) return;
+    // the kernels divide linear row indices through a float reciprocal, exact below 2^22
+    if ((double)(d.N + 1) * std::max(a.Hs, f.P) >= 4.0e6) return;
     p->upd_grid = a.per_xcd * 8;
     p->upd_copies = splits * n_strips;
     p->upd_ws = (size_t)splits * n_strips * f.dwt_bytes;
@@ -968,7 +984,29 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out)
     return conv_create_rect(desc, desc->pad, desc->pad, out);
 }
 
+namespace {
+bool all_tiled(const conv_plan *q) { return q->fwd.ok && q->bwd_mode != 0 && q->upd_ok; }
+conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w, int32_t max_images,
+                          conv_handle_t *out);
+}  // namespace
+
 conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w, conv_handle_t *out)
+{
+    return create_plan(desc, pad_h, pad_w, 0, out);
+}
+
+conv_status_t conv_create_chunked(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
+                                  int32_t max_images, conv_handle_t *out)
+{
+    if (max_images < 1) return CONV_EINVAL;
+    return create_plan(desc, pad_h, pad_w, max_images, out);
+}
+
+namespace {
+// max_images: > 0: no launch covers more images; 0: chunks only where the tensors need them;
+// < 0: never (the plan of a chunk)
+conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w, int32_t max_images,
+                          conv_handle_t *out)
 {
     if (!desc || !out) return CONV_EINVAL;
     *out = nullptr;
@@ -1036,9 +1074,59 @@ conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t p
     }
     f.upd_splits = (p->upd_ok || p->upd_direct) ? p->upd_copies : 0;
     f.workspace_bytes = std::max(std::max(p->bwd_ws, p->upd_ws), p->fwd_ws);
+
+    // Chunks of the minibatch.  On request: every pass.  Otherwise only for tensors of 4 GB
+    // and more, which the tiled kernels' 32-bit byte offsets do not reach, or minibatches
+    // whose linear row indices pass the kernels' exact-division range: the fewest equal
+    // chunks whose plans are all tiled, for the passes that would else run untiled.
+    int nc = 0;
+    const bool forced = max_images > 0;
+    if (forced) {
+        if (max_images < d.N) nc = max_images;
+    } else if (max_images == 0 && d.N >= 2 && !all_tiled(p) &&
+               ((double)std::max(f.in_bytes, f.out_bytes) >= 4.0e9 ||
+                (double)(d.N + 1) * std::max(d.H + 2 * pad_h, f.P) * std::max(f.Cb, f.Kb) >= 4.0e6)) {
+        for (int k = 2; k <= 64 && k <= d.N && nc == 0; ++k) {
+            conv_desc_t dd = d;
+            dd.N = ceil_div(d.N, k);
+            conv_handle_t q = nullptr;
+            if (create_plan(&dd, pad_h, pad_w, -1, &q) != CONV_OK) break;
+            if (all_tiled(q)) nc = dd.N;
+            delete q;
+        }
+    }
+    if (nc > 0) {
+        conv_desc_t dd = d;
+        dd.N = nc;
+        const int n_chunks = ceil_div(d.N, nc), rest = d.N - (n_chunks - 1) * nc;
+        conv_status_t st = create_plan(&dd, pad_h, pad_w, -1, &p->chunk);
+        if (st == CONV_OK && rest != nc) {
+            dd.N = rest;
+            st = create_plan(&dd, pad_h, pad_w, -1, &p->tail);
+        }
+        if (st != CONV_OK) {
+            delete p;
+            return st;
+        }
+        p->n_chunks = n_chunks;
+        p->chunk_n = nc;
+        p->fwd_chunked = forced || !p->fwd.ok;
+        p->bwd_chunked = forced || p->bwd_mode == 0;
+        p->upd_chunked = forced || !p->upd_ok;
+        if (p->fwd_chunked) p->fwd_direct = false, p->fwd_ws = 0;
+        if (p->bwd_chunked) p->bwd_direct = false, p->bwd_ws = 0;
+        if (p->upd_chunked) p->upd_direct = false, p->upd_ws = 0;
+        const size_t sub = std::max(p->chunk->info.workspace_bytes,
+                                    p->tail ? p->tail->info.workspace_bytes : (size_t)0);
+        p->chunk_ws = (sub + 255) / 256 * 256;
+        const size_t need = p->chunk_ws + (p->upd_chunked ? (size_t)n_chunks * f.dwt_bytes : 0);
+        if (p->upd_chunked) f.upd_splits = n_chunks;  // one dW per chunk, summed in chunk order
+        f.workspace_bytes = std::max(f.workspace_bytes, need);
+    }
     *out = p;
     return CONV_OK;
 }
+}  // namespace
 
 conv_status_t conv_destroy(conv_handle_t h)
 {
@@ -1069,6 +1157,19 @@ conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *w
     if (!aligned16(in) || !aligned16(wt) || !aligned16(out) || !aligned16(ws) || !aligned16(bias) ||
         !aligned16(residual) || !aligned16(scale))
         return CONV_EINVAL;
+    if (h->fwd_chunked) {
+        const size_t in_img = h->info.in_bytes / h->d.N, out_img = h->info.out_bytes / h->d.N;
+        for (int c = 0; c < h->n_chunks; ++c) {
+            conv_plan *q = (c == h->n_chunks - 1 && h->tail) ? h->tail : h->chunk;
+            const size_t n0 = (size_t)c * h->chunk_n;
+            const conv_status_t st = conv_fwd_fused_norm(
+                q, static_cast<const char *>(in) + n0 * in_img, wt, static_cast<char *>(out) + n0 * out_img,
+                scale, bias, residual ? static_cast<const char *>(residual) + n0 * out_img : nullptr, relu,
+                ws, stream);
+            if (st != CONV_OK) return st;
+        }
+        return CONV_OK;
+    }
     if (h->fwd_direct) {
         DirectArgs a = h->da;
         a.x = in;
@@ -1112,6 +1213,18 @@ conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, v
 {
     if (!h || !dout || !wt || !din) return CONV_EINVAL;
     if (!aligned16(dout) || !aligned16(wt) || !aligned16(din) || !aligned16(ws)) return CONV_EINVAL;
+    if (h->bwd_chunked) {
+        const size_t in_img = h->info.in_bytes / h->d.N, out_img = h->info.out_bytes / h->d.N;
+        for (int c = 0; c < h->n_chunks; ++c) {
+            conv_plan *q = (c == h->n_chunks - 1 && h->tail) ? h->tail : h->chunk;
+            const size_t n0 = (size_t)c * h->chunk_n;
+            const conv_status_t st =
+                conv_bwd_data(q, static_cast<const char *>(dout) + n0 * out_img, wt,
+                              static_cast<char *>(din) + n0 * in_img, ws, stream);
+            if (st != CONV_OK) return st;
+        }
+        return CONV_OK;
+    }
     if (h->bwd_direct) {
         DirectArgs a = h->da;
         a.x = dout;
@@ -1150,6 +1263,27 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
 {
     if (!h || !in || !dout || !dwt) return CONV_EINVAL;
     if (!aligned16(in) || !aligned16(dout) || !aligned16(dwt) || !aligned16(ws)) return CONV_EINVAL;
+    if (h->upd_chunked) {
+        // dW of chunk c goes to slot c behind the chunks' own workspace; the slots are then
+        // summed in chunk order
+        if (!ws) return CONV_EWORKSPACE;
+        const size_t in_img = h->info.in_bytes / h->d.N, out_img = h->info.out_bytes / h->d.N;
+        char *slots = static_cast<char *>(ws) + h->chunk_ws;
+        for (int c = 0; c < h->n_chunks; ++c) {
+            conv_plan *q = (c == h->n_chunks - 1 && h->tail) ? h->tail : h->chunk;
+            const size_t n0 = (size_t)c * h->chunk_n;
+            const conv_status_t st =
+                conv_upd(q, static_cast<const char *>(in) + n0 * in_img,
+                         static_cast<const char *>(dout) + n0 * out_img,
+                         slots + (size_t)c * h->info.dwt_bytes, ws, stream);
+            if (st != CONV_OK) return st;
+        }
+        if (launch_upd_reduce(reinterpret_cast<const float *>(slots), static_cast<float *>(dwt),
+                              h->info.dwt_bytes / sizeof(float), h->n_chunks,
+                              (hipStream_t)stream) != hipSuccess)
+            return CONV_ELAUNCH;
+        return CONV_OK;
+    }
     if (h->upd_direct) {
         DirectArgs a = h->da;
         a.x = in;
@@ -1278,6 +1412,11 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
 {
     if (!h || !buf || buflen == 0) return CONV_EINVAL;
     buf[0] = 0;
+    if ((pass == 0 && h->fwd_chunked) || (pass == 1 && h->bwd_chunked) || (pass == 2 && h->upd_chunked)) {
+        const int n = snprintf(buf, buflen, "chunks=%d images=%d: ", h->n_chunks, h->chunk_n);
+        if (n < 0 || (size_t)n >= buflen) return CONV_EINVAL;
+        return conv_describe(h->chunk, pass, buf + n, buflen - n);
+    }
     if ((pass == 0 && h->fwd_direct) || (pass == 1 && h->bwd_direct) || (pass == 2 && h->upd_direct)) {
         const DirectArgs &a = h->da;
         const int V = h->info.vlen;

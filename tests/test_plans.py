@@ -155,3 +155,46 @@ def test_kernel_families_are_chosen_where_they_apply():
     # small minibatch, long reduction: the forward reduction is split
     _, p = _plans((1, 512, 512, 7, 7, 3, 3, 1, 1), conv.CONV_F32)
     assert _field(p[conv.PASS_FWD], "ksplit") > 1
+
+
+def _describe_all(h):
+    return [conv.conv_describe(h, w) for w in (conv.PASS_FWD, conv.PASS_BWD_DATA, conv.PASS_UPD)]
+
+
+def test_minibatch_chunks_on_request():
+    shape = (10, 64, 64, 14, 14, 3, 3, 1, 1)
+    h = conv.conv_create_chunked(*shape, 4)
+    try:
+        info = conv.conv_query(h)
+        assert all(t.startswith("chunks=3 images=4: ") for t in _describe_all(h))
+        # one dW per chunk behind the chunks' own workspace
+        assert info.upd_splits == 3 and info.workspace_bytes >= 3 * info.dwt_bytes
+    finally:
+        conv.conv_destroy(h)
+    # a bound the minibatch already meets changes nothing
+    h, g = conv.conv_create_chunked(*shape, 10), conv.conv_create(*shape)
+    try:
+        assert _describe_all(h) == _describe_all(g)
+    finally:
+        conv.conv_destroy(h)
+        conv.conv_destroy(g)
+    with pytest.raises(conv.ConvError) as e:
+        conv.conv_create_chunked(*shape, 0)
+    assert e.value.status == conv.CONV_EINVAL
+
+
+@pytest.mark.parametrize("dt", [conv.CONV_F32, conv.CONV_BF16], ids=["f32", "bf16"])
+def test_tensors_beyond_32bit_offsets_run_in_chunks_on_tiled_kernels(dt):
+    """4 GB and more in one tensor, or more linear rows than the kernels' exact divisions
+    reach: the planner splits the minibatch so that every pass keeps its tiled kernel."""
+    for shape in ((1024 if dt == conv.CONV_BF16 else 512, 64, 64, 224, 224, 3, 3, 1, 1),
+                  (8192 if dt == conv.CONV_BF16 else 4096, 64, 256, 56, 56, 1, 1, 1, 0),
+                  (300000, 8, 8, 14, 14, 3, 3, 1, 1)):
+        info, plans = _plans(shape, dt)
+        _check(info, plans)
+        assert all(_tiled(p) for p in plans.values()), (shape, plans)
+        assert plans[conv.PASS_FWD].startswith("chunks=") and plans[conv.PASS_BWD_DATA].startswith("chunks=")
+    # the benchmark's own sizes are never chunked
+    for l in inputs.TABLE_I:
+        _, plans = _plans((256, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad), dt)
+        assert not any(p.startswith("chunks=") for p in plans.values())
