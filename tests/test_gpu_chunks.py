@@ -93,35 +93,36 @@ def test_chunked_update_repeats_bit_for_bit():
         L.close()
 
 
-def test_output_tensor_beyond_4gb_runs_in_chunks():
-    """An output tensor of 4.5 GB (fp32): forward and backward run as two chunks of 176
-    images on the tiled kernels, the update in one piece on a kernel with 64-bit addressing.
-    The oracle computes every output of the first and last image and of the two images either
-    side of the chunk boundary, and a seeded subset of dW entries (each a full N*P*Q-long dot
-    product, summed over the two halves of the minibatch to bound the fp64 copies)."""
+def _sampled_parity(shape, dtype, seed, chunked):
+    """All three passes of a large problem: the oracle computes every output of the first and
+    last image and of the two images in the middle (either side of a chunk boundary where there
+    is one), and a seeded subset of dW entries, each a full N*P*Q-long dot product (summed over
+    the two halves of the minibatch to bound the fp64 copies)."""
     import torch
-    shape = (352, 8, 64, 224, 224, 3, 3, 1, 1)
     N, C, K, H, W, R, S, stride, pad = shape
-    print("shape", shape, flush=True)
-    I = inputs.gen_input(N, C, H, W, 37)
-    Wt = inputs.gen_weights(K, C, R, S, 37)
-    dO = inputs.gen_outgrad(N, K, H, W, 37)
-    L = conv.ConvLayer(*shape, dtype=conv.CONV_F32)
+    print("shape", shape, "dtype", dtype, flush=True)
+    L = conv.ConvLayer(*shape, dtype=dtype)
     try:
-        assert L.info.out_bytes > 2 ** 32
-        assert conv.conv_describe(L.h, conv.PASS_FWD).startswith("chunks=2 images=176: igemm")
-        assert conv.conv_describe(L.h, conv.PASS_BWD_DATA).startswith("chunks=2 images=176: igemm")
-        imgs = [0, 175, 176, 351]
+        P, Q = L.info.P, L.info.Q
+        for which in (conv.PASS_FWD, conv.PASS_BWD_DATA):
+            assert conv.conv_describe(L.h, which).startswith("chunks=2 ") == chunked
+            assert " igemm " in " " + conv.conv_describe(L.h, which)
+        I = inputs.gen_input(N, C, H, W, seed)
+        Wt = inputs.gen_weights(K, C, R, S, seed)
+        dO = inputs.gen_outgrad(N, K, P, Q, seed)
+        if dtype == conv.CONV_BF16:
+            I, Wt, dO = (inputs.round_to_bf16(x) for x in (I, Wt, dO))
+        imgs = [0, N // 2 - 1, N // 2, N - 1]
         L.set_input(I)
         L.set_weights(Wt)
         L.out_blk.fill_(float("nan"))
         L.fwd()
         out = L.get_output()
         torch.cuda.synchronize()
-        got = out[imgs].cpu().numpy()
+        got = out[imgs].float().cpu().numpy()
         assert bool(torch.isfinite(out).all())
         del out
-        assert rel_l2(got, oracle.fwd(I[imgs], Wt, stride, pad)) <= 1e-5
+        assert rel_l2(got, oracle.fwd(I[imgs], Wt, stride, pad)) <= TOL[dtype]
         print("fwd done", flush=True)
 
         L.set_outgrad(dO)
@@ -129,10 +130,10 @@ def test_output_tensor_beyond_4gb_runs_in_chunks():
         L.bwd_data()
         din = L.get_input()
         torch.cuda.synchronize()
-        got = din[imgs].cpu().numpy()
+        got = din[imgs].float().cpu().numpy()
         assert bool(torch.isfinite(din).all())
         del din
-        assert rel_l2(got, oracle.bwd_data(dO[imgs], Wt, H, W, stride, pad)) <= 1e-5
+        assert rel_l2(got, oracle.bwd_data(dO[imgs], Wt, H, W, stride, pad)) <= TOL[dtype]
         print("bwd done", flush=True)
 
         L.set_input(I)   # (the backward pass wrote dI over the blocked input)
@@ -141,12 +142,27 @@ def test_output_tensor_beyond_4gb_runs_in_chunks():
         torch.cuda.synchronize()
         got = L.get_dweights().cpu().numpy()
         assert np.isfinite(got).all()
-        rng = np.random.default_rng(37)
+        rng = np.random.default_rng(seed)
         ent = np.stack([rng.integers(0, K, 24), rng.integers(0, C, 24), rng.integers(0, R, 24),
                         rng.integers(0, S, 24)], axis=1).astype(np.int32)
         ent = np.concatenate([np.array([[0, 0, 0, 0], [K - 1, C - 1, R - 1, S - 1]], dtype=np.int32), ent])
         ref = sum(oracle.upd_entries(I[a:b], dO[a:b], R, S, stride, pad, ent)
-                  for a, b in ((0, 176), (176, 352)))
+                  for a, b in ((0, N // 2), (N // 2, N)))
         assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5
     finally:
         L.close()
+
+
+def test_output_tensor_beyond_4gb_runs_in_chunks():
+    """An output tensor of 4.5 GB (fp32): forward and backward run as two chunks of 176
+    images on the tiled kernels, the update in one piece on a kernel with 64-bit addressing."""
+    shape = (352, 8, 64, 224, 224, 3, 3, 1, 1)
+    _sampled_parity(shape, conv.CONV_F32, 37, chunked=True)
+
+
+@pytest.mark.parametrize("shape", [(4000, 64, 64, 56, 56, 3, 3, 1, 1), (1200, 256, 64, 56, 56, 1, 1, 1, 0)],
+                         ids=["3x3-3.2GB", "1x1-3.9GB"])
+def test_tensors_between_2gb_and_4gb_in_one_launch(shape):
+    """Byte offsets past 2^31 (a signed 32-bit offset would wrap) in single launches of the
+    forward / backward kernel and of the fp32 band and flat update kernels."""
+    _sampled_parity(shape, conv.CONV_F32, 41, chunked=False)
