@@ -89,15 +89,19 @@ const int kMaxLds = 160 * 1024;
 // band of TR consecutive linear output rows touches with an R-tall filter.
 int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
 {
-    const int NP = N * P;
-    int best = 0;
-    for (int rho0 = 0; rho0 < NP; rho0 += TR) {
-        const int rho1 = std::min(NP, rho0 + TR) - 1;
-        const int lam0 = (rho0 / P) * Hs + (rho0 % P) * stride;
-        const int lam1 = (rho1 / P) * Hs + (rho1 % P) * stride + R - 1;
+    // A band's extent depends on the row it starts at within its image, rho0 % P, and those
+    // repeat after at most P bands: the first P bands hold the maximum (the last band of the
+    // row space can only be shorter than an earlier one of the same phase).
+    const long long NP = (long long)N * P;
+    const long long bands = std::min<long long>((NP + TR - 1) / TR, P);
+    long long best = 0;
+    for (long long b = 0; b < bands; ++b) {
+        const long long rho0 = b * TR, rho1 = std::min(NP, rho0 + TR) - 1;
+        const long long lam0 = (rho0 / P) * Hs + (rho0 % P) * stride;
+        const long long lam1 = (rho1 / P) * Hs + (rho1 % P) * stride + R - 1;
         best = std::max(best, lam1 - lam0 + 1);
     }
-    return best;
+    return (int)std::min<long long>(best, 1 << 30);
 }
 
 // One candidate plan of the implicit-GEMM kernel: `wk` waves along channels,
@@ -954,10 +958,17 @@ void plan_upd(conv_plan *p)
     p->upd_rows = false;
     p->upd_bands = false;
     // the kernels written for a family of layers first, each declining what it does not fit
-    if (plan_upd_c4_bf16(p) || plan_upd_c4(p) || plan_upd_flat_f32(p) || plan_upd_flat_bf16(p) ||
-        plan_upd_rows(p) || plan_upd_bands(p))
-        return;
-    plan_upd_general(p);
+    if (!(plan_upd_c4_bf16(p) || plan_upd_c4(p) || plan_upd_flat_f32(p) || plan_upd_flat_bf16(p) ||
+          plan_upd_rows(p) || plan_upd_bands(p)))
+        plan_upd_general(p);
+    // Partial copies that dwarf the tensors themselves (very wide rows cut into many strips,
+    // under a filter with thousands of channels): no tiled plan; the direct kernel needs no
+    // workspace.
+    const double cap = std::max(2.0 * ((double)p->info.in_bytes + (double)p->info.out_bytes), 8.0e9);
+    if (p->upd_ok && (double)p->upd_ws > cap) {
+        p->upd_ok = false;
+        p->upd_ws = 0;
+    }
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -1086,7 +1097,13 @@ conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
     } else if (max_images == 0 && d.N >= 2 && !all_tiled(p) &&
                ((double)std::max(f.in_bytes, f.out_bytes) >= 4.0e9 ||
                 (double)(d.N + 1) * std::max(d.H + 2 * pad_h, f.P) * std::max(f.Cb, f.Kb) >= 4.0e6)) {
-        for (int k = 2; k <= 64 && k <= d.N && nc == 0; ++k) {
+        // (if one image alone has no tiled plan, no chunk has)
+        conv_desc_t d1 = d;
+        d1.N = 1;
+        conv_handle_t q1 = nullptr;
+        const bool any = create_plan(&d1, pad_h, pad_w, -1, &q1) == CONV_OK && all_tiled(q1);
+        delete q1;
+        for (int k = 2; any && k <= 64 && k <= d.N && nc == 0; ++k) {
             conv_desc_t dd = d;
             dd.N = ceil_div(d.N, k);
             conv_handle_t q = nullptr;

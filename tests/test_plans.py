@@ -198,3 +198,19 @@ def test_tensors_beyond_32bit_offsets_run_in_chunks_on_tiled_kernels(dt):
     for l in inputs.TABLE_I:
         _, plans = _plans((256, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad), dt)
         assert not any(p.startswith("chunks=") for p in plans.values())
+
+
+def test_extreme_descriptors_plan_quickly_and_within_bounds():
+    """Very tall images, millions of images, thousands of channels under a large filter:
+    planning time must not grow with N*P, and the update's partial copies must not dwarf
+    the tensors (such plans are left to the direct kernel, which needs no workspace)."""
+    import time
+    for shape, dt in (((77948, 3, 4, 16060, 9, 7, 7, 3, (2, 5)), conv.CONV_F32),
+                      ((2000000, 8, 8, 9, 9, 3, 3, 1, 1), conv.CONV_BF16),
+                      ((2, 5585, 5431, 330, 2214, 7, 7, 3, (6, 1)), conv.CONV_F32),
+                      ((19, 5746, 6495, 325, 972, 7, 1, 1, (6, 0)), conv.CONV_F32)):
+        t0 = time.time()
+        info, plans = _plans(shape, dt)
+        assert time.time() - t0 < 20.0, shape
+        _check(info, plans)
+        assert info.workspace_bytes <= max(2 * (info.in_bytes + info.out_bytes), 8e9) + 64 * info.dwt_bytes
