@@ -45,6 +45,17 @@ static IgemmEntry g_rect[] = {
     // backward passes): 32 rows x 896 pixels per workgroup
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 3, 3, 5),
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 3, 3, 3),
+    // (six rows of a 147-wide image fill the pixel slots; a band that crosses two images
+    // spans ten input rows)
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 3, 3, 6),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 2, 3, 3, 6),
+    // ... with a single input channel block under stride 2 (the 3-channel first layer of a
+    // 299 x 299 network: six 149-pixel output rows fill the 896 pixel slots, their input tile
+    // is 13 rows of 299), and the 2x2 residue classes of that layer's backward pass
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 1, 3, 3, 16),
+    IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 1, 3, 3, 16),
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 2, 2, 4),
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 2, 2, 5),
 };
 
 IgemmEntry *igemm_rect_entries(int *count)
