@@ -41,6 +41,7 @@ static IgemmEntry g_rect[] = {
     // spans twice its rows and columns
     IGEMM_ENTRY(CONV_F32, 4, 1, 1, 7, 2, 3, 3, 4),
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 3, 3, 4),
+    IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 4),
     // 3x3 results with at most 32 channel rows (the 32-channel stem layers and their
     // backward passes): 32 rows x 896 pixels per workgroup
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 3, 3, 5),
