@@ -36,7 +36,9 @@ def _entries(rng, K, C, R, S, count):
 V3_CASES = [(1, conv.CONV_F32), (1, conv.CONV_BF16), (3, conv.CONV_F32), (13, conv.CONV_F32), (16, conv.CONV_F32),
             (29, conv.CONV_F32), (30, conv.CONV_F32), (41, conv.CONV_F32), (42, conv.CONV_F32),
             (2, conv.CONV_BF16), (13, conv.CONV_BF16), (25, conv.CONV_BF16), (26, conv.CONV_BF16),
-            (42, conv.CONV_BF16)]
+            (42, conv.CONV_BF16),
+            # 32-row tiles of the 32-channel stem, 128-row tiles of a 17-pixel-wide grid reduction
+            (2, conv.CONV_F32), (16, conv.CONV_BF16)]
 
 
 @pytest.mark.parametrize("lid,dtype", CASES,
