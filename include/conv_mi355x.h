@@ -58,8 +58,9 @@ typedef enum {
     CONV_OK = 0,
     CONV_EINVAL = 1,       /* NULL pointer, non-positive extent, negative pad,
                               empty output, unknown dtype, misaligned pointer  */
-    CONV_EUNSUPPORTED = 2, /* valid problem beyond the kernels' launch limits  */
-    CONV_EWORKSPACE = 3,   /* workspace required but ws == NULL                */
+    CONV_EUNSUPPORTED = 2, /* valid problem beyond the library's size limits   */
+    CONV_EWORKSPACE = 3,   /* workspace required but ws == NULL, or (the _ws
+                              entry points) smaller than the pass needs        */
     CONV_ELAUNCH = 4       /* the HIP runtime refused a launch                 */
 } conv_status_t;
 
@@ -86,8 +87,18 @@ typedef struct {
 
 typedef struct conv_plan *conv_handle_t;
 
-/* Host only: validate the descriptor and plan tile shapes, grids and the
- * weight-update split (everything the paper does once per layer at set-up). */
+/* Host only: validate the descriptor and plan every pass -- kernel variant, tile
+ * shape, grid, LDS size, the split of the weight update -- once per layer.  This is
+ * the role of the paper's set-up: the dryrun phase of the kernel streams
+ * (Section II-H), which walks the loops once to record what each thread will
+ * run, and the division of the work items over the threads (Section II-F); the
+ * pass entry points below are the replay phase and only launch.
+ * Errors: CONV_EINVAL for a NULL pointer, an extent < 1, a negative pad, an
+ * unknown dtype, or an empty output (H + 2 pad < R or W + 2 pad < S);
+ * CONV_EUNSUPPORTED beyond the size limits: N, C, K, H, W <= 2^24; R, S, stride,
+ * pad <= 2^16; at most 2^39 elements per activation tensor and 2^31 - 1 per
+ * weight tensor (channels rounded up to the block).  On success *out owns a
+ * host-side plan (no device memory) until conv_destroy. */
 conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
 /* As conv_create, with one pad per axis (desc->pad is ignored):
  *     ij = stride*oj - pad_h + r,  ii = stride*oi - pad_w + s,
@@ -99,9 +110,9 @@ conv_status_t conv_create(const conv_desc_t *desc, conv_handle_t *out);
  * Every accepted descriptor has all three passes.  Filters the tiled MFMA kernels are
  * instantiated for (1x1, 3x3, 5x5, 1x3, 3x1, 1x7, 7x1, and 7x7 where a staged tile fits
  * the LDS) run on those; any other filter, stride or row width runs the plain loop nests of
- * Algorithms 1, 5 and 8, one result element per thread, at a small fraction of that rate
- * (conv_describe names the kernel: "direct ...").  CONV_EUNSUPPORTED is left for tensors
- * beyond the launch limits (more than 2^39 elements). */
+ * Algorithms 1, 6 and 8, one result element per thread, at a small fraction of that rate
+ * (conv_describe names the kernel: "direct ...").  CONV_EUNSUPPORTED is left for the size
+ * limits listed at conv_create. */
 conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
                                conv_handle_t *out);
 /* As conv_create_rect, with the minibatch run in chunks of at most max_images images
@@ -115,9 +126,22 @@ conv_status_t conv_create_rect(const conv_desc_t *desc, int32_t pad_h, int32_t p
  * byte offsets do not reach in one launch. */
 conv_status_t conv_create_chunked(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
                                   int32_t max_images, conv_handle_t *out);
+/* Free the host-side plan (the end of the set-up's lifetime, Section II-H; no device
+ * memory is involved).  CONV_EINVAL for NULL. */
 conv_status_t conv_destroy(conv_handle_t h);
+/* Output extent (P, Q as defined above), channel blocking (the VLEN blocking of
+ * Section II-B) and the byte sizes of the blocked tensors and of the workspace.
+ * CONV_EINVAL for a NULL argument. */
 conv_status_t conv_query(conv_handle_t h, conv_info_t *info);
+/* Static text for a status code; never NULL. */
 const char *conv_status_str(conv_status_t s);
+
+/* Workspace.  conv_fwd, conv_bwd_data and conv_upd take `ws`, a device buffer of at least
+ * conv_info_t::workspace_bytes (the maximum over the three passes).  They cannot see its
+ * size: a buffer smaller than that is written past its end.  Callers that want the size
+ * checked use conv_fwd_ws / conv_bwd_data_ws / conv_upd_ws below, which take ws_bytes and
+ * return CONV_EWORKSPACE (nothing is launched) when it is smaller than what that pass
+ * of this plan needs. */
 
 /* Algorithm 1 with padding:  out[n,k,oj,oi] = sum_{c,r,s} in[n,c,ij,ii] * wt[k,c,r,s].
  * in: blocked I; wt: blocked W; out: blocked O (fully overwritten, padded
@@ -156,7 +180,7 @@ conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, vo
  * over all (oj,r), (oi,s) that map to (ij,ii); positions no term maps to are 0.
  * dout: blocked dO; wt: blocked W (the same buffer conv_fwd takes); din: blocked
  * dI, fully overwritten.  ws: workspace_bytes of scratch (holds the transposed,
- * tap-flipped weights of the duality of Section II-H). */
+ * tap-flipped weights of the duality of Section II-I). */
 conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, void *din,
                             void *ws, void *stream);
 
@@ -167,7 +191,16 @@ conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, v
 conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *dwt,
                        void *ws, void *stream);
 
-/* Layout conversion, pure permutations in the tensor's own element type
+/* The three passes with the workspace size checked (see "Workspace" above); otherwise
+ * identical to conv_fwd, conv_bwd_data and conv_upd. */
+conv_status_t conv_fwd_ws(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
+                          size_t ws_bytes, void *stream);
+conv_status_t conv_bwd_data_ws(conv_handle_t h, const void *dout, const void *wt, void *din,
+                               void *ws, size_t ws_bytes, void *stream);
+conv_status_t conv_upd_ws(conv_handle_t h, const void *in, const void *dout, void *dwt, void *ws,
+                          size_t ws_bytes, void *stream);
+
+/* Layout conversion (Algorithm 2's blocked layouts, Section II-B), pure permutations in the tensor's own element type
  * (dW: fp32).  "nchw"/"kcrs" are the logical layouts, "blk" the blocked ones. */
 conv_status_t conv_pack_in(conv_handle_t h, const void *nchw, void *blk, void *stream);
 conv_status_t conv_pack_out(conv_handle_t h, const void *nkpq, void *blk, void *stream);
@@ -178,7 +211,10 @@ conv_status_t conv_unpack_wt(conv_handle_t h, const void *blk, void *kcrs, void 
 conv_status_t conv_unpack_dwt(conv_handle_t h, const void *blk_f32, void *kcrs_f32, void *stream);
 
 /* Name, launch geometry and dynamic LDS bytes of the kernel a pass would
- * launch (pass: 0 fwd, 1 bwd_data, 2 upd); for benchmarks and profiles. */
+ * launch (pass: 0 fwd, 1 bwd_data, 2 upd): what the set-up decided (Section II-H's
+ * dryrun record, in readable form); for benchmarks and profiles.  buf receives a
+ * NUL-terminated string of at most buflen bytes.  CONV_EINVAL for NULL / buflen 0 /
+ * an unknown pass, CONV_EUNSUPPORTED if the pass has no kernel. */
 conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buflen);
 
 #ifdef __cplusplus

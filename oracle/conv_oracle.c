@@ -6,10 +6,10 @@
  * header, table or helper with the GPU kernels.  It exists so that the GPU
  * results can be compared against the plain definition.
  *
- * Every function is the paper's naive seven-loop nest written out:
- *   forward          -- "Naive forward propagation loops"        (Algorithm 1)
- *   backward by data -- "Naive backward propagation loops"       (Algorithm 6)
- *   weight update    -- "Naive weight gradient update loops"     (Algorithm 8)
+ * Every function is one of the paper's naive seven-loop nests written out:
+ *   forward          -- Algorithm 1 (Section II-A)
+ *   backward by data -- Algorithm 6 (Section II-I)
+ *   weight update    -- Algorithm 8 (Section II-J)
  * over the logical tensors of Section II: I[N][C][H][W], W[K][C][R][S],
  * O[N][K][P][Q] (row-major, last index fastest), in fp64 throughout.
  *

@@ -21,6 +21,7 @@ CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5
 EXPORTS = (
     "conv_create", "conv_create_rect", "conv_create_chunked", "conv_destroy", "conv_query", "conv_status_str",
     "conv_fwd", "conv_fwd_fused", "conv_fwd_fused_norm", "conv_bwd_data", "conv_upd",
+    "conv_fwd_ws", "conv_bwd_data_ws", "conv_upd_ws",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
@@ -77,6 +78,8 @@ def load():
     lib.conv_status_str.restype = ctypes.c_char_p
     for name in ("conv_fwd", "conv_bwd_data", "conv_upd"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp]
+    for name in ("conv_fwd_ws", "conv_bwd_data_ws", "conv_upd_ws"):
+        getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.conv_fwd_fused.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
     lib.conv_fwd_fused_norm.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp]
     for name in ("conv_pack_in", "conv_pack_out", "conv_pack_wt", "conv_unpack_in",
@@ -185,6 +188,25 @@ def conv_bwd_data(h, dout, wt, din, ws, stream=None):
 def conv_upd(h, inp, dout, dwt, ws, stream=None):
     _check(load().conv_upd(h, _ptr(inp), _ptr(dout), _ptr(dwt), _ptr(ws), _stream(stream)),
            "conv_upd")
+
+
+def _ws_bytes(ws):
+    return 0 if ws is None else ws.numel() * ws.element_size()
+
+
+def conv_fwd_ws(h, inp, wt, out, ws, stream=None):
+    _check(load().conv_fwd_ws(h, _ptr(inp), _ptr(wt), _ptr(out), _ptr(ws), _ws_bytes(ws),
+                              _stream(stream)), "conv_fwd_ws")
+
+
+def conv_bwd_data_ws(h, dout, wt, din, ws, stream=None):
+    _check(load().conv_bwd_data_ws(h, _ptr(dout), _ptr(wt), _ptr(din), _ptr(ws), _ws_bytes(ws),
+                                   _stream(stream)), "conv_bwd_data_ws")
+
+
+def conv_upd_ws(h, inp, dout, dwt, ws, stream=None):
+    _check(load().conv_upd_ws(h, _ptr(inp), _ptr(dout), _ptr(dwt), _ptr(ws), _ws_bytes(ws),
+                              _stream(stream)), "conv_upd_ws")
 
 
 def _perm(name):

@@ -1,15 +1,32 @@
 // C ABI of libconv_mi355x: descriptor validation and per-layer planning (done
-// once at conv_create, the analogue of the paper's set-up phase, Section II-G),
+// once at conv_create, the analogue of the dryrun phase of Section II-H),
 // and the entry points that only enqueue kernels.
 #include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
+#include <unordered_map>
 
 #include "conv_internal.h"
 
 using namespace convmi;
+
+namespace convmi {
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::unordered_map<const void *, size_t> have;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &cur = have[kernel];
+    if (bytes <= cur) return hipSuccess;
+    const hipError_t err =
+        hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (err == hipSuccess) cur = bytes;
+    return err;
+}
+}  // namespace convmi
 
 namespace {
 
@@ -983,7 +1000,7 @@ const char *conv_status_str(conv_status_t s)
         case CONV_OK: return "ok";
         case CONV_EINVAL: return "invalid argument";
         case CONV_EUNSUPPORTED: return "unsupported problem";
-        case CONV_EWORKSPACE: return "workspace missing";
+        case CONV_EWORKSPACE: return "workspace missing or too small";
         case CONV_ELAUNCH: return "kernel launch failed";
     }
     return "unknown status";
@@ -1026,7 +1043,24 @@ conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
         pad_h < 0 || pad_w < 0)
         return CONV_EINVAL;
     if (d.dtype != CONV_F32 && d.dtype != CONV_BF16) return CONV_EINVAL;
-    if (d.H + 2 * pad_h < d.R || d.W + 2 * pad_w < d.S) return CONV_EINVAL;
+    // Everything below this point is computed in int; the extents are bounded here, in
+    // 64-bit, so that no later product or sum can leave the range.
+    const long long Hp = (long long)d.H + 2LL * pad_h, Wp = (long long)d.W + 2LL * pad_w;
+    if (Hp < d.R || Wp < d.S) return CONV_EINVAL;
+    const int kMaxExtent = 1 << 24, kMaxSmall = 1 << 16;
+    if (d.N > kMaxExtent || d.C > kMaxExtent || d.K > kMaxExtent || d.H > kMaxExtent ||
+        d.W > kMaxExtent || d.R > kMaxSmall || d.S > kMaxSmall || d.stride > kMaxSmall ||
+        pad_h > kMaxSmall || pad_w > kMaxSmall)
+        return CONV_EUNSUPPORTED;
+    {
+        const int V = vlen_of(d.dtype);
+        const double Cp = (double)ceil_div(d.C, V) * V, Kp = (double)ceil_div(d.K, V) * V;
+        const double P = (double)((Hp - d.R) / d.stride + 1), Q = (double)((Wp - d.S) / d.stride + 1);
+        const double kMaxElems = 549755813888.0;  // 2^39 elements per activation tensor
+        if ((double)d.N * Cp * d.H * d.W > kMaxElems || (double)d.N * Kp * P * Q > kMaxElems ||
+            Cp * Kp * d.R * d.S > 2147483647.0)
+            return CONV_EUNSUPPORTED;
+    }
 
     conv_plan *p = new (std::nothrow) conv_plan();
     if (!p) return CONV_EINVAL;
@@ -1049,24 +1083,33 @@ conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
     f.wt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * es;
     f.dwt_bytes = (size_t)f.Cp * d.R * d.S * f.Kp * sizeof(float);
 
-    p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, pad_h,
-                        pad_w, f.P, f.Q, 1, 0, 0, 0);
-    // Few tiles and a long reduction (small minibatch, inference): split the reduction
-    // over more workgroups, fp32 partial results in the workspace, summed in a fixed order.
+    // The tiled planners index rows, staged tiles and channel blocks with int products; they
+    // are only asked where those stay far inside the range (the kernels' own limits -- exact
+    // float reciprocals below 2^22, 24-bit multiplies -- are tighter still and checked by each
+    // planner).  Anything else runs on the untiled kernels, or in chunks of the minibatch.
+    const bool tiled_domain = (long long)(d.N + 1) * std::max<long long>(Hp, f.P) < (1LL << 24) &&
+                              Wp < (1 << 15) && f.Cp < (1 << 20) && f.Kp < (1 << 20) &&
+                              d.R <= 64 && d.S <= 64 && d.stride <= 64;
     p->fwd_ws = 0;
-    if (p->fwd.ok && p->fwd.a.total <= 128 && p->fwd.a.n_stage >= 4) {
-        IgemmArgs &a = p->fwd.a;
-        const int want = std::min(a.n_stage / 2, std::max(1, 512 / a.total));
-        if (want >= 2) {
-            a.st_per = ceil_div(a.n_stage, want);
-            a.ksplit = ceil_div(a.n_stage, a.st_per);
-            a.per_xcd = ceil_div(a.total * a.ksplit, 8);
-            p->fwd.grid = a.per_xcd * 8;
-            p->fwd_ws = (size_t)a.ksplit * d.N * f.Kp * f.P * f.Q * sizeof(float);
+    if (tiled_domain) {
+        p->fwd = plan_igemm(d.dtype, d.N, f.Cb, d.H, d.W, f.Kp, f.P, f.Q, d.R, d.S, d.stride, pad_h,
+                            pad_w, f.P, f.Q, 1, 0, 0, 0);
+        // Few tiles and a long reduction (small minibatch, inference): split the reduction
+        // over more workgroups, fp32 partial results in the workspace, summed in a fixed order.
+        if (p->fwd.ok && p->fwd.a.total <= 128 && p->fwd.a.n_stage >= 4) {
+            IgemmArgs &a = p->fwd.a;
+            const int want = std::min(a.n_stage / 2, std::max(1, 512 / a.total));
+            if (want >= 2) {
+                a.st_per = ceil_div(a.n_stage, want);
+                a.ksplit = ceil_div(a.n_stage, a.st_per);
+                a.per_xcd = ceil_div(a.total * a.ksplit, 8);
+                p->fwd.grid = a.per_xcd * 8;
+                p->fwd_ws = (size_t)a.ksplit * d.N * f.Kp * f.P * f.Q * sizeof(float);
+            }
         }
+        plan_bwd(p);
+        plan_upd(p);
     }
-    plan_bwd(p);
-    plan_upd(p);
     // A pass without a tiled plan falls to the direct kernels (any filter, stride and pad).
     if (direct_fits(d.dtype, d.N, f.Cb, f.Kb, d.H, d.W, f.P, f.Q, d.R, d.S)) {
         p->fwd_direct = !p->fwd.ok;
@@ -1371,6 +1414,45 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
     return CONV_OK;
 }
 
+namespace {
+// bytes of workspace a pass of this plan reads or writes
+size_t pass_ws_bytes(const conv_plan *h, int pass)
+{
+    const bool chunked = pass == 0 ? h->fwd_chunked : pass == 1 ? h->bwd_chunked : h->upd_chunked;
+    if (chunked) {
+        size_t need = h->chunk ? pass_ws_bytes(h->chunk, pass) : 0;
+        if (h->tail) need = std::max(need, pass_ws_bytes(h->tail, pass));
+        if (pass == 2) need = h->chunk_ws + (size_t)h->n_chunks * h->info.dwt_bytes;
+        return need;
+    }
+    return pass == 0 ? h->fwd_ws : pass == 1 ? h->bwd_ws : h->upd_ws;
+}
+}  // namespace
+
+conv_status_t conv_fwd_ws(conv_handle_t h, const void *in, const void *wt, void *out, void *ws,
+                          size_t ws_bytes, void *stream)
+{
+    if (!h) return CONV_EINVAL;
+    if (ws_bytes < pass_ws_bytes(h, 0)) return CONV_EWORKSPACE;
+    return conv_fwd(h, in, wt, out, ws, stream);
+}
+
+conv_status_t conv_bwd_data_ws(conv_handle_t h, const void *dout, const void *wt, void *din,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    if (!h) return CONV_EINVAL;
+    if (ws_bytes < pass_ws_bytes(h, 1)) return CONV_EWORKSPACE;
+    return conv_bwd_data(h, dout, wt, din, ws, stream);
+}
+
+conv_status_t conv_upd_ws(conv_handle_t h, const void *in, const void *dout, void *dwt, void *ws,
+                          size_t ws_bytes, void *stream)
+{
+    if (!h) return CONV_EINVAL;
+    if (ws_bytes < pass_ws_bytes(h, 2)) return CONV_EWORKSPACE;
+    return conv_upd(h, in, dout, dwt, ws, stream);
+}
+
 #define CHECK_PACK_ARGS(h, a, b)                                  \
     if (!(h) || !(a) || !(b)) return CONV_EINVAL;                 \
     if (!aligned16(a) || !aligned16(b)) return CONV_EINVAL;
@@ -1437,9 +1519,12 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
     if ((pass == 0 && h->fwd_direct) || (pass == 1 && h->bwd_direct) || (pass == 2 && h->upd_direct)) {
         const DirectArgs &a = h->da;
         const int V = h->info.vlen;
-        const size_t grid = pass == 0   ? ((size_t)a.N * a.Kb * a.P * a.Q * V + 255) / 256
-                            : pass == 1 ? ((size_t)a.N * a.Cb * a.H * a.W * V + 255) / 256
-                                        : (size_t)a.Cb * a.R * a.S * a.Kb;
+        // (the kernels stride over what a capped grid of 2^22 workgroups does not reach)
+        const size_t grid = std::min<size_t>(
+            pass == 0   ? ((size_t)a.N * a.Kb * a.P * a.Q * V + 255) / 256
+            : pass == 1 ? ((size_t)a.N * a.Cb * a.H * a.W * V + 255) / 256
+                        : (size_t)a.Cb * a.R * a.S * a.Kb,
+            (size_t)1 << 22);
         snprintf(buf, buflen, "direct dt=%d RS=%dx%d stride=%d threads=256 grid=%zu lds=%d launches=1",
                  (int)h->d.dtype, a.R, a.S, a.stride, grid, pass == 2 ? 4 * V * V * 4 : 0);
         return CONV_OK;

@@ -12,7 +12,7 @@ namespace convmi {
 
 // ---------------------------------------------------------------------------
 // Arguments of the implicit-GEMM kernel that serves the forward pass and, via
-// the two duality scenarios of Section II-H, the backward-by-data pass.
+// the two duality scenarios of Section II-I, the backward-by-data pass.
 //
 //   out[n][kb][oy][ox][:] = sum_{cb,r,s,c} in[n][cb][oy*stride-pad_h+r][ox*stride-pad_w+s][c]
 //                                          * wt[cb][r][s][k][c]
@@ -75,6 +75,10 @@ struct IgemmVariant {
     int ppt;     // staged input pixels per thread
     int nb = 2;  // LDS buffers of the staging ring
 };
+
+// Raise a kernel's dynamic-LDS limit to at least `bytes` (once per kernel and size; safe to
+// call from several host threads, whatever handles they use).
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
 
 hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes,
                         int grid, hipStream_t stream);

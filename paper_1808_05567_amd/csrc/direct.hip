@@ -1,5 +1,5 @@
 // Direct convolution without tiling: the three passes written as the loop nests
-// of Algorithms 1, 5 (its gather form) and 8 over the blocked layouts of Section II-B,
+// of Algorithms 1, 6 (its gather form) and 8 over the blocked layouts of Section II-B,
 // one thread per result element (forward, backward) or one workgroup per
 // vlen x vlen block of dW (update).  These kernels serve the descriptors that no
 // tiled MFMA kernel is instantiated for (a filter shape outside the tables, a row
@@ -10,6 +10,8 @@
 // result summed in one fixed order (channel block, filter row, filter column,
 // channel for the first two; pixel order, then a fixed tree, for the update), so
 // every call returns the same bits.
+#include <algorithm>
+
 #include "conv_internal.h"
 
 namespace convmi {
@@ -67,8 +69,8 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a)
 {
     constexpr int V = Vec<DT>::V;
     const size_t total = (size_t)a.N * a.Kb * a.P * a.Q * V;
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
+    // (a grid has at most 2^32 work-items: larger tensors take several elements per thread)
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
     const int kv = (int)(e % V);
     size_t t = e / V;
     const int oi = (int)(t % a.Q); t /= a.Q;
@@ -98,17 +100,17 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a)
     if (a.resid) y += Vec<DT>::load1(a.resid, e);
     if (a.relu) y = fmaxf(y, 0.f);
     Vec<DT>::store1(a.y, e, y);
+    }
 }
 
-// Backward by data, the gather form of Algorithm 5: thread e owns
+// Backward by data, the gather form of Algorithm 6: thread e owns
 // din[n][cb][ij][ii][cv] and visits the output pixels whose window holds (ij, ii).
 template <int DT>
 __global__ __launch_bounds__(256) void direct_bwd_kernel(const DirectArgs a)
 {
     constexpr int V = Vec<DT>::V;
     const size_t total = (size_t)a.N * a.Cb * a.H * a.W * V;
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
     const int cv = (int)(e % V);
     size_t t = e / V;
     const int ii = (int)(t % a.W); t /= a.W;
@@ -136,6 +138,7 @@ __global__ __launch_bounds__(256) void direct_bwd_kernel(const DirectArgs a)
             }
         }
     Vec<DT>::store1(a.y, e, acc);
+    }
 }
 
 // Weight update, Algorithm 8 without the minibatch split: workgroup b owns the
@@ -147,11 +150,13 @@ __global__ __launch_bounds__(256) void direct_upd_kernel(const DirectArgs a)
 {
     constexpr int V = Vec<DT>::V;
     __shared__ float red[4][V * V];
-    int b = blockIdx.x;
-    const int kb = b % a.Kb; b /= a.Kb;
-    const int s = b % a.S; b /= a.S;
-    const int r = b % a.R;
-    const int cb = b / a.R;
+    const size_t nblk = (size_t)a.Cb * a.R * a.S * a.Kb;
+    for (size_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+    size_t b = blk;
+    const int kb = (int)(b % a.Kb); b /= a.Kb;
+    const int s = (int)(b % a.S); b /= a.S;
+    const int r = (int)(b % a.R);
+    const int cb = (int)(b / a.R);
     float acc[V][V];
 #pragma unroll
     for (int k = 0; k < V; ++k)
@@ -191,12 +196,16 @@ __global__ __launch_bounds__(256) void direct_upd_kernel(const DirectArgs a)
         const int Kp = a.Kb * V;
         static_cast<float *>(a.y)[((((size_t)cb * a.R + r) * a.S + s) * Kp + (size_t)kb * V) * V + i] = v;
     }
+    __syncthreads();  // red[] is reused by the next block of dW
+    }
 }
 
 template <typename K> hipError_t launch(K kernel, const DirectArgs &a, size_t blocks, hipStream_t stream)
 {
-    if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    if (blocks == 0) return hipErrorInvalidValue;
+    // grid x block stays below the 2^32 work-items of a dispatch; the kernels stride over the rest
+    const size_t kMaxBlocks = 1u << 22;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)std::min(blocks, kMaxBlocks)), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -204,10 +213,11 @@ template <typename K> hipError_t launch(K kernel, const DirectArgs &a, size_t bl
 
 bool direct_fits(int dtype, int N, int Cb, int Kb, int H, int W, int P, int Q, int R, int S)
 {
-    const size_t V = (size_t)vlen_of(dtype);
-    const size_t lim = 0x7FFFFFFFull * 256;
-    return (size_t)N * Kb * P * Q * V <= lim && (size_t)N * Cb * H * W * V <= lim &&
-           (size_t)Cb * R * S * Kb <= 0x7FFFFFFFull;
+    // element indices are 64-bit and the grids are capped: what bounds these kernels is the
+    // tensor size conv_create accepts (2^39 elements per activation tensor)
+    const double V = (double)vlen_of(dtype), lim = 549755813888.0 * 2;
+    return (double)N * Kb * P * Q * V <= lim && (double)N * Cb * H * W * V <= lim &&
+           (double)Cb * R * S * Kb <= 2147483647.0;
 }
 
 hipError_t launch_direct_fwd(int dtype, const DirectArgs &a, hipStream_t stream)

@@ -1,6 +1,6 @@
 // Implicit-GEMM direct convolution on MFMA for gfx950: the kernel behind the
 // forward pass (Algorithm 1 of the paper, with padding) and, through the two
-// duality scenarios of Section II-H, the backward-by-data pass (Algorithm 6).
+// duality scenarios of Section II-I, the backward-by-data pass (Algorithm 6).
 //
 // Mapping of the paper's ingredients:
 //   * Section II-B blocked layouts: channels are blocked by v = 16 bytes/element
@@ -178,13 +178,9 @@ hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_by
 {
     IgemmEntry *e = find_igemm(v);
     if (!e) return hipErrorInvalidDeviceFunction;
-    if (lds_bytes > e->lds_attr) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        e->lds_attr = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(e->fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(e->fn, dim3(grid), dim3(v.wk * v.wm * 64), lds_bytes, stream, a);
     return hipGetLastError();
 }

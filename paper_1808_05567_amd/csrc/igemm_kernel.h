@@ -555,13 +555,12 @@ typedef void (*igemm_fn_t)(const IgemmArgs);
 struct IgemmEntry {
     IgemmVariant v;
     igemm_fn_t fn;
-    size_t lds_attr;
 };
 
 #define IGEMM_ENTRY_NB(DT, WK, WM, FK, FM, NPL, R, S, PPT, NB)                  \
     {                                                                            \
         {DT, WK, WM, FK, FM, NPL, R, S, PPT, NB},                                \
-            igemm_kernel<DT, WK, WM, FK, FM, NPL, R, S, PPT, NB>, 0              \
+            igemm_kernel<DT, WK, WM, FK, FM, NPL, R, S, PPT, NB>                 \
     }
 #define IGEMM_ENTRY(DT, WK, WM, FK, FM, NPL, R, S, PPT) \
     IGEMM_ENTRY_NB(DT, WK, WM, FK, FM, NPL, R, S, PPT, 2)

@@ -1,6 +1,6 @@
 // Instantiations of the implicit-GEMM convolution kernel for the rectangular and
 // 5x5 filters of Inception-style networks (1x7, 7x1, 1x3, 3x1, 5x5), forward and,
-// through the stride-1 duality of Section II-H, backward by data.  The kernel is
+// through the stride-1 duality of Section II-I, backward by data.  The kernel is
 // the one the square ResNet filters use; only the compile-time filter extent and
 // the per-thread share of the staged input tile differ.
 #include "igemm_kernel.h"

@@ -3,7 +3,7 @@
 // work on (Section II-B; block = 16 bytes of channels).  Pure permutations:
 // no arithmetic, padded channel slots are written as zero.
 //
-// Also the weight transform of the backward-by-data duality (Section II-H):
+// Also the weight transform of the backward-by-data duality (Section II-I):
 // channel roles swapped and taps flipped, optionally decimated by the stride.
 #include "conv_internal.h"
 
@@ -12,11 +12,11 @@ namespace convmi {
 // X[N][C][H][W] -> Xb[N][Cb][H][W][V]; one thread per 16-byte block.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void pack_act_kernel(const T *__restrict__ src, T *__restrict__ dst,
-                                                       int C, int Cb, int HW, size_t total)
+                                                       int C, int Cb, size_t HW, size_t total)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int hw = (int)(idx % HW);
+    // (a grid has at most 2^32 work-items: larger tensors take several blocks per thread)
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+    const size_t hw = idx % HW;
     const size_t t = idx / HW;
     const int cb = (int)(t % Cb);
     const size_t n = t / Cb;
@@ -29,15 +29,15 @@ __global__ __launch_bounds__(256) void pack_act_kernel(const T *__restrict__ src
     T *d = dst + idx * V;
 #pragma unroll
     for (int j = 0; j < V; ++j) d[j] = v[j];
+    }
 }
 
 template <typename T, int V>
 __global__ __launch_bounds__(256) void unpack_act_kernel(const T *__restrict__ src, T *__restrict__ dst,
-                                                         int C, int Cb, int HW, size_t total)
+                                                         int C, int Cb, size_t HW, size_t total)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int hw = (int)(idx % HW);
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+    const size_t hw = idx % HW;
     const size_t t = idx / HW;
     const int cb = (int)(t % Cb);
     const size_t n = t / Cb;
@@ -46,6 +46,7 @@ __global__ __launch_bounds__(256) void unpack_act_kernel(const T *__restrict__ s
     for (int j = 0; j < V; ++j) {
         const int c = cb * V + j;
         if (c < C) dst[(n * C + c) * HW + hw] = s[j];
+    }
     }
 }
 
@@ -133,7 +134,13 @@ __global__ __launch_bounds__(256) void wt_merge_kernel(const WtMergeArgs a, int 
     for (int kk = 0; kk < V; ++kk) dst[(size_t)idx * V + kk] = val[kk];
 }
 
-static inline int blocks_for(size_t total) { return (int)((total + 255) / 256); }
+// (grid x 256 threads stays below the 2^32 work-items of a dispatch; the activation kernels
+// stride over what is left, the weight tensors are bounded at conv_create)
+static inline int blocks_for(size_t total)
+{
+    const size_t b = (total + 255) / 256;
+    return (int)(b < (1u << 22) ? b : (1u << 22));
+}
 
 hipError_t launch_pack_act(int dtype, const void *nchw, void *blk, int N, int C, int H, int W,
                            hipStream_t stream)
@@ -142,10 +149,10 @@ hipError_t launch_pack_act(int dtype, const void *nchw, void *blk, int N, int C,
     const size_t total = (size_t)N * Cb * H * W;
     if (dtype == CONV_BF16)
         hipLaunchKernelGGL((pack_act_kernel<uint16_t, 8>), dim3(blocks_for(total)), dim3(256), 0, stream,
-                           (const uint16_t *)nchw, (uint16_t *)blk, C, Cb, H * W, total);
+                           (const uint16_t *)nchw, (uint16_t *)blk, C, Cb, (size_t)H * W, total);
     else
         hipLaunchKernelGGL((pack_act_kernel<uint32_t, 4>), dim3(blocks_for(total)), dim3(256), 0, stream,
-                           (const uint32_t *)nchw, (uint32_t *)blk, C, Cb, H * W, total);
+                           (const uint32_t *)nchw, (uint32_t *)blk, C, Cb, (size_t)H * W, total);
     return hipGetLastError();
 }
 
@@ -156,10 +163,10 @@ hipError_t launch_unpack_act(int dtype, const void *blk, void *nchw, int N, int 
     const size_t total = (size_t)N * Cb * H * W;
     if (dtype == CONV_BF16)
         hipLaunchKernelGGL((unpack_act_kernel<uint16_t, 8>), dim3(blocks_for(total)), dim3(256), 0,
-                           stream, (const uint16_t *)blk, (uint16_t *)nchw, C, Cb, H * W, total);
+                           stream, (const uint16_t *)blk, (uint16_t *)nchw, C, Cb, (size_t)H * W, total);
     else
         hipLaunchKernelGGL((unpack_act_kernel<uint32_t, 4>), dim3(blocks_for(total)), dim3(256), 0,
-                           stream, (const uint32_t *)blk, (uint32_t *)nchw, C, Cb, H * W, total);
+                           stream, (const uint32_t *)blk, (uint32_t *)nchw, C, Cb, (size_t)H * W, total);
     return hipGetLastError();
 }
 

@@ -2,7 +2,7 @@
 //
 //   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
 //
-// Mapping of the paper's ingredients (Section II-I, Algorithm 9):
+// Mapping of the paper's ingredients (Section II-J, Algorithm 9):
 //   * the VLEN x VLEN dW block kept in registers across the spatial loops becomes
 //     a (32*FC) x (32*FK) MFMA accumulator tile per filter tap, all R*S taps
 //     of the tile resident in one wave (M = input channels, N = output
@@ -560,17 +560,16 @@ typedef void (*upd_fn_t)(const UpdArgs);
 struct UpdEntry {
     UpdVariant v;
     upd_fn_t fn;
-    size_t lds_attr;
 };
 
 #define UPD_F32_ENTRY(R, S, FC, FK, GI, GO, PF)                                          \
     {                                                                                    \
-        {CONV_F32, R, S, 2, 2, FC, FK, GI, GO}, upd_f32_kernel<R, S, FC, FK, GI, GO, PF>, 0 \
+        {CONV_F32, R, S, 2, 2, FC, FK, GI, GO}, upd_f32_kernel<R, S, FC, FK, GI, GO, PF>    \
     }
 #define UPD_BF16_ENTRY(R, S, WC, WK, FC, FK, PI, PO)                                     \
     {                                                                                    \
         {CONV_BF16, R, S, WC, WK, FC, FK, PI, PO},                                       \
-            upd_bf16_kernel<R, S, WC, WK, FC, FK, PI, PO>, 0                             \
+            upd_bf16_kernel<R, S, WC, WK, FC, FK, PI, PO>                                \
     }
 
 static UpdEntry g_upd[] = {
@@ -612,13 +611,9 @@ hipError_t launch_upd(const UpdVariant &v, const UpdArgs &a, size_t lds_bytes, i
 {
     UpdEntry *e = find_upd(v);
     if (!e) return hipErrorInvalidDeviceFunction;
-    if (lds_bytes > e->lds_attr) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        e->lds_attr = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(e->fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(e->fn, dim3(grid), dim3(256), lds_bytes, stream, a);
     return hipGetLastError();
 }

@@ -345,15 +345,14 @@ typedef void (*upd_rows_fn_t)(const UpdArgs);
 struct UpdRowsEntry {
     UpdRowsVariant v;
     upd_rows_fn_t fn;
-    size_t lds_attr;
 };
 #define UPD_ROWS_ENTRY(R, S, WC, WK, WP, FC, FK)                                         \
     {                                                                                    \
-        {R, S, WC, WK, WP, FC, FK}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK>, 0    \
+        {R, S, WC, WK, WP, FC, FK}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK>       \
     }
 #define UPD_ROWS_ENTRY_STRIDED(R, S, WC, WK, WP, FC, FK)                                 \
     {                                                                                    \
-        {R, S, WC, WK, WP, FC, FK, 1}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK, true>, 0 \
+        {R, S, WC, WK, WP, FC, FK, 1}, upd_rows_bf16_kernel<R, S, WC, WK, WP, FC, FK, true>    \
     }
 static UpdRowsEntry g_rows[] = {
     UPD_ROWS_ENTRY(3, 3, 2, 4, 1, 1, 1),  // 64 x 128 channels, eight waves
@@ -398,13 +397,9 @@ hipError_t launch_upd_rows(const UpdRowsVariant &v, const UpdArgs &a, size_t lds
 {
     UpdRowsEntry *e = find_rows(v);
     if (!e) return hipErrorInvalidDeviceFunction;
-    if (lds_bytes > e->lds_attr) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        e->lds_attr = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(e->fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(e->fn, dim3(grid), dim3(v.wc * v.wk * v.wp * 64), lds_bytes, stream, a);
     return hipGetLastError();
 }

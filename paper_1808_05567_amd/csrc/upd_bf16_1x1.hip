@@ -4,7 +4,7 @@
 //
 //   dW[k,c] = sum over (n,oj,oi) of I[n,c,oj*stride,oi*stride] * dO[n,k,oj,oi]
 //
-// Mapping of Section II-I / Algorithm 9:
+// Mapping of Section II-J / Algorithm 9:
 //   * the dW block kept in registers across the spatial loops is an
 //     (FC*32) x (FK*32) channel block per wave, up to 64 x 128 (eight 32x32 MFMA
 //     accumulator tiles): M = input channels, N = output channels;
@@ -21,7 +21,7 @@
 //   * parallelisation: grid = (split of the pixel list) x (channel blocks); where
 //     the channel block needs fewer than eight waves the spare waves take
 //     alternate 16-pixel groups into private accumulators, summed through LDS
-//     after the last band ("T copies + reduction" of Section II-I inside the
+//     after the last band ("T copies + reduction" of Section II-J inside the
 //     workgroup).  Every split writes a private partial dW that the reduce kernel
 //     sums in a fixed order.
 #include <type_traits>
@@ -281,10 +281,9 @@ typedef void (*upd_flat_fn_t)(const UpdArgs);
 struct UpdFlatEntry {
     UpdRowsVariant v;  // (r = s = 1)
     upd_flat_fn_t fn;
-    bool attr_set;
 };
 #define UPD_FLAT_ENTRY(WC, WK, WP, FC, FK) \
-    {{1, 1, WC, WK, WP, FC, FK}, upd_bf16_1x1_kernel<WC, WK, WP, FC, FK>, false}
+    {{1, 1, WC, WK, WP, FC, FK}, upd_bf16_1x1_kernel<WC, WK, WP, FC, FK>}
 static UpdFlatEntry g_flat[] = {
     // input channels x output channels of the workgroup's dW block
     UPD_FLAT_ENTRY(4, 2, 1, 2, 4),  // 256 x 256
@@ -317,13 +316,9 @@ hipError_t launch_upd_bf16_1x1(const UpdRowsVariant &v, const UpdArgs &a, int gr
     UpdFlatEntry *e = find_flat(v);
     if (!e) return hipErrorInvalidDeviceFunction;
     const size_t lds_bytes = upd_bf16_1x1_lds_bytes(v);
-    if (!e->attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(e->fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        e->attr_set = true;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(e->fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(e->fn, dim3(grid), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
 }

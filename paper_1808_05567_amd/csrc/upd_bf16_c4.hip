@@ -20,7 +20,7 @@
 //
 // Eight waves = 2 x 32 output channels x four pixel groups that take alternate pairs of
 // 8-pixel runs into private accumulators, summed through LDS after the last band (the
-// "T copies + reduction" of Section II-I inside the workgroup).  Bands are double
+// "T copies + reduction" of Section II-J inside the workgroup).  Bands are double
 // buffered, staged by loads that write straight into LDS (Section II-E).
 #include "conv_internal.h"
 
@@ -272,15 +272,9 @@ hipError_t launch_upd_c4_bf16(int r, int s, const UpdArgs &a, size_t lds_bytes, 
     if (r == 7 && s == 7) fn = upd_c4_bf16_kernel<7, 7>;
     if (r == 3 && s == 3) fn = upd_c4_bf16_kernel<3, 3>;
     if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attr[2] = {0, 0};
-    size_t &cur = attr[r == 7 ? 0 : 1];
-    if (lds_bytes > cur) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        cur = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
 }

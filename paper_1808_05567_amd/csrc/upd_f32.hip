@@ -4,13 +4,13 @@
 //
 //   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
 //
-// Same mapping of Section II-I / Algorithm 9 as the four-wave kernel (M = 64
+// Same mapping of Section II-J / Algorithm 9 as the four-wave kernel (M = 64
 // input channels, N = 64 output channels, reduction = pixels, all R*S taps of
 // a 32x32 block resident in one wave), with these differences:
 //   * 2 x 2 waves over (input, output) channels times TWO pixel groups: the
 //     groups take alternate pixel pairs of a band into private accumulators, which
 //     are summed through LDS after the last band (the "T copies + reduction"
-//     of Section II-I inside the workgroup).  A CU therefore always runs two
+//     of Section II-J inside the workgroup).  A CU therefore always runs two
 //     waves per SIMD, which is what keeps the matrix core busy while a wave
 //     issues its LDS reads.
 //   * One workgroup owns the whole LDS: the band of the next step streams in
@@ -367,42 +367,26 @@ hipError_t launch_upd_f32_bands(int r, int s, int layout, const UpdArgs &a, size
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
     const int odd = a.Q & 1;
-    int slot = -1;
     if (layout != 0) {
         if (!upd_f32_bands_layout_exists(r, s, layout, odd != 0)) return hipErrorInvalidDeviceFunction;
         fn = layout == 1 ? upd_f32_bands_kernel<3, 3, true, 1, 2> : upd_f32_bands_kernel<3, 3, true, 1, 1>;
-        static size_t attr2[2] = {0, 0};
-        size_t &at = attr2[layout - 1];
-        if (lds_bytes > at) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 (int)lds_bytes);
-            if (err != hipSuccess) return err;
-            at = lds_bytes;
-        }
+        if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
+            err != hipSuccess)
+            return err;
         hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
         return hipGetLastError();
     }
-#define BANDS_CASE(IDX, RR, SS)                                                                 \
-    if (r == RR && s == SS) {                                                                   \
-        fn = odd ? upd_f32_bands_kernel<RR, SS, true> : upd_f32_bands_kernel<RR, SS, false>;    \
-        slot = IDX;                                                                             \
-    }
-    BANDS_CASE(0, 3, 3)
-    BANDS_CASE(1, 1, 7)
-    BANDS_CASE(2, 1, 3)
-    BANDS_CASE(3, 3, 1)
+#define BANDS_CASE(RR, SS) \
+    if (r == RR && s == SS) fn = odd ? upd_f32_bands_kernel<RR, SS, true> : upd_f32_bands_kernel<RR, SS, false>;
+    BANDS_CASE(3, 3)
+    BANDS_CASE(1, 7)
+    BANDS_CASE(1, 3)
+    BANDS_CASE(3, 1)
 #undef BANDS_CASE
     if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attrs[4][2] = {};
-    size_t &attr = attrs[slot][odd];
-    if (lds_bytes > attr) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        attr = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
 }

@@ -4,7 +4,7 @@
 //
 //   dW[k,c] = sum over (n,oj,oi) of I[n,c,oj*stride,oi*stride] * dO[n,k,oj,oi]
 //
-// Mapping of Section II-I / Algorithm 9:
+// Mapping of Section II-J / Algorithm 9:
 //   * the dW block kept in registers across the spatial loops is a 128 x 64
 //     channel block per wave (eight 32x32 MFMA accumulator tiles);
 //   * the reduction runs over pixels, two per MFMA (the lane halves).  The blocked
@@ -21,7 +21,7 @@
 //   * parallelisation: the grid is (split of the pixel list) x (channel blocks);
 //     where side B has fewer than 256 channels the spare waves take alternate
 //     pixel pairs into private accumulators, summed through LDS after the last
-//     band ("T copies + reduction" of Section II-I inside the workgroup).  Every
+//     band ("T copies + reduction" of Section II-J inside the workgroup).  Every
 //     split writes a private partial dW that the reduce kernel sums in a fixed order.
 #include "conv_internal.h"
 
@@ -263,21 +263,14 @@ hipError_t launch_upd_f32_1x1(int wb, bool a_is_in, const UpdArgs &a, int grid, 
 {
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
-    int slot = -1;
-    if (wb == 4) { fn = a_is_in ? upd_f32_1x1_kernel<4, true> : upd_f32_1x1_kernel<4, false>; slot = 0; }
-    if (wb == 2) { fn = a_is_in ? upd_f32_1x1_kernel<2, true> : upd_f32_1x1_kernel<2, false>; slot = 2; }
-    if (wb == 1) { fn = a_is_in ? upd_f32_1x1_kernel<1, true> : upd_f32_1x1_kernel<1, false>; slot = 4; }
+    if (wb == 4) { fn = a_is_in ? upd_f32_1x1_kernel<4, true> : upd_f32_1x1_kernel<4, false>; }
+    if (wb == 2) { fn = a_is_in ? upd_f32_1x1_kernel<2, true> : upd_f32_1x1_kernel<2, false>; }
+    if (wb == 1) { fn = a_is_in ? upd_f32_1x1_kernel<1, true> : upd_f32_1x1_kernel<1, false>; }
     if (!fn) return hipErrorInvalidDeviceFunction;
-    slot += a_is_in ? 0 : 1;
     const size_t lds_bytes = upd_f32_1x1_lds_bytes(wb);
-    static bool attr_set[6] = {false, false, false, false, false, false};
-    if (!attr_set[slot]) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        attr_set[slot] = true;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
 }

@@ -11,7 +11,7 @@
 // and one accumulator tile per filter row r, all R rows resident in the wave.
 // Eight waves = 2 x 32 output channels x FOUR pixel groups that take alternate pixel
 // pairs of a band into private accumulators, summed through LDS after the last band
-// (the "T copies + reduction" of Section II-I inside the workgroup).  The band of the
+// (the "T copies + reduction" of Section II-J inside the workgroup).  The band of the
 // next step (dO rows and the input rows they touch) streams into the second LDS buffer
 // while the current one is consumed (Section II-E), one barrier per band: fp32 by loads
 // that write straight into LDS, bf16 through registers (where it is converted).
@@ -308,15 +308,9 @@ hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_b
     if (r == 7 && s == 7) fn = bf ? upd_c4_f32_kernel<7, 7, true> : upd_c4_f32_kernel<7, 7, false>;
     if (r == 3 && s == 3) fn = bf ? upd_c4_f32_kernel<3, 3, true> : upd_c4_f32_kernel<3, 3, false>;
     if (!fn) return hipErrorInvalidDeviceFunction;
-    static size_t attr[4] = {0, 0, 0, 0};
-    size_t &cur = attr[(r == 7 ? 0 : 1) + (bf ? 2 : 0)];
-    if (lds_bytes > cur) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
-        if (err != hipSuccess) return err;
-        cur = lds_bytes;
-    }
+    if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
+        err != hipSuccess)
+        return err;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
 }

@@ -111,7 +111,7 @@ def _layer(shape, dtype):
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", DIRECT, ids=lambda s: "x".join(map(str, s)).replace(" ", ""))
 def test_direct_kernels_match_oracle(shape, dtype):
-    """Algorithms 1, 5 and 8 as plain loop nests over the blocked layouts, for descriptors no
+    """Algorithms 1, 6 and 8 as plain loop nests over the blocked layouts, for descriptors no
     tiled kernel fits: every pass has a kernel and matches the oracle."""
     N, C, K, H, W, R, S, stride, pad = shape
     I, Wt, dO = make_inputs(shape, dtype, layer_id=41)

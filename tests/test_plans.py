@@ -214,3 +214,49 @@ def test_extreme_descriptors_plan_quickly_and_within_bounds():
         assert time.time() - t0 < 20.0, shape
         _check(info, plans)
         assert info.workspace_bytes <= max(2 * (info.in_bytes + info.out_bytes), 8e9) + 64 * info.dwt_bytes
+
+
+@pytest.mark.parametrize("bad", [dict(C=2 ** 31 - 1), dict(K=2 ** 31 - 1), dict(W=2 ** 31 - 1),
+                                 dict(H=2 ** 31 - 1), dict(N=2 ** 31 - 1), dict(stride=2 ** 31 - 1),
+                                 dict(R=2 ** 20, H=2 ** 21), dict(pad=2 ** 30),
+                                 dict(N=2 ** 24, C=2 ** 12, H=2 ** 12, W=2 ** 12)],
+                         ids=lambda b: ",".join("%s=%d" % kv for kv in b.items()))
+def test_extents_beyond_the_size_limits_are_refused_not_miscomputed(bad):
+    """Extents near INT32_MAX once left the planner's int arithmetic (a garbage plan, a division
+    by zero, half a minute inside conv_create): they are bounded in 64-bit before any planning."""
+    import time
+    d = dict(N=2, C=8, K=8, H=8, W=8, R=3, S=3, stride=1, pad=1, dtype=0)
+    d.update(bad)
+    t0 = time.time()
+    with pytest.raises(conv.ConvError) as e:
+        conv.conv_create(**d)
+    assert e.value.status == conv.CONV_EUNSUPPORTED
+    assert time.time() - t0 < 1.0
+
+
+def test_large_but_legal_extents_plan_within_bounds():
+    """Just inside the limits: a plan comes back at once, every figure positive."""
+    import time
+    for shape in ((1, 2 ** 20, 8, 1, 1, 1, 1, 1, 0), (2 ** 24, 4, 4, 1, 1, 1, 1, 1, 0),
+                  (1, 4, 4, 2 ** 18, 2 ** 18, 3, 3, 1, 1), (1, 8, 8, 70000, 9, 5, 3, 60000, (0, 1)),
+                  (3, 8, 8, 9, 40000, 3, 3, 1, 1)):
+        t0 = time.time()
+        info, plans = _plans(shape, conv.CONV_F32)
+        assert time.time() - t0 < 5.0, shape
+        _check(info, plans)
+        assert info.P >= 1 and info.Q >= 1 and info.in_bytes > 0 and info.out_bytes > 0
+
+
+def test_checked_workspace_entry_points_refuse_a_short_buffer():
+    """conv_*_ws return CONV_EWORKSPACE before anything is launched (host only here: the
+    pointers are never dereferenced because the size check comes first)."""
+    lib = conv.load()
+    h = conv.conv_create(4, 64, 64, 14, 14, 3, 3, 1, 1, 0)
+    try:
+        need = conv.conv_query(h).workspace_bytes
+        assert need > 0
+        assert lib.conv_bwd_data_ws(h, 16, 16, 16, 16, 0, None) == conv.CONV_EWORKSPACE
+        assert lib.conv_upd_ws(h, 16, 16, 16, 16, need // 2, None) == conv.CONV_EWORKSPACE
+        assert lib.conv_upd_ws(None, 16, 16, 16, 16, need, None) == conv.CONV_EINVAL
+    finally:
+        conv.conv_destroy(h)
