@@ -1,20 +1,25 @@
 """Benchmark of the convolution hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16]
-                    [--workload resnet50|inception_v3] [--layers 4,8,13,18|all]
-                    [--table] [--table-dir DIR] [--no-cpu]
+                    [--workload resnet50|inception_v3] [--layers all|4,8,13,18]
+                    [--table] [--table-dir DIR] [--no-cpu] [--no-ceilings]
 
 A "step" is one pass of the whole hot path over one minibatch: forward,
 backward-by-data and weight update (partial + reduce) of every layer in the
 workload, on tensors already resident in HBM in the blocked layout.  The default
-workload is the configuration the headline metric is quoted on: the four
-ResNet-50 3x3 layers of Table I (ids 4, 8, 13, 18), fp32, N = 256, stride 1,
-pad 1, seeded synthetic inputs.  Prints ONE JSON line.
+workload is the full layer set the headline metric is quoted on: all 20
+ResNet-50 layers of Table I at N = 256 (the four 3x3 layers, the fifteen 1x1
+layers and the 7x7 first layer), seeded synthetic inputs.  With no --dtype the
+run times that workload twice: in fp32 (the headline: value, ms_per_step,
+roofline, cpu_baseline) and in bf16 (the "bf16" object of the same line); both
+carry per-class (3x3 / 1x1 / conv1) rates per pass.  "measured_ceilings" holds
+what this device sustains on an MFMA issue loop, a 1 GiB copy and an L2 -> LDS
+streaming loop.  Prints ONE JSON line.
 
 --table additionally times every requested layer/pass on its own (in the cycling
 loop and repeated back to back) and writes a per-layer table (TFLOP/s, % of MFMA
-peak, % of the layer's roofline ceiling) as JSON into --table-dir and as text to
-stderr.
+peak, % of the layer's roofline ceiling at the published and at the measured
+ceilings) as JSON into --table-dir and as text to stderr.
 """
 from __future__ import annotations
 
@@ -38,19 +43,21 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
+                    help="one type only (default: fp32 as the headline plus a bf16 block)")
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "inception_v3"],
                     help="layer table: ResNet-50 (Table I of the paper) or the distinct "
                          "Inception-v3 shapes (second workload; --layers all)")
     ap.add_argument("--layers", default=None,
-                    help="comma-separated layer ids of the workload, or 'all' "
-                         "(default: 4,8,13,18 for resnet50, all for inception_v3)")
+                    help="comma-separated layer ids of the workload, or 'all' (the default)")
     ap.add_argument("--batch", type=int, default=N_BATCH)
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--table-dir", default=os.path.join(ROOT, "gpurun_out"),
                     help="where --table writes layers_<workload>_<dtype>.json")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--cpu-batch", type=int, default=128)
+    ap.add_argument("--no-ceilings", action="store_true")
+    ap.add_argument("--cpu-batch", type=int, default=0,
+                    help="minibatch of the oracle's timed sample (default: sized to the workload)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
@@ -69,8 +76,11 @@ def parse():
 
 
 CALIB_BYTES = 1 << 30
-TRAFFIC_FILE = {"f32": "igemm_f32_resnet50_3x3_n256_hbm_traffic.json",
-                "bf16": "igemm_bf16_resnet50_3x3_n256_hbm_traffic.json"}
+# committed counter summaries (HBM bytes per dispatch) by workload: (layers, dtype) -> file
+TRAFFIC_FILE = {("all", "f32"): "igemm_upd_f32_resnet50_all_n256_hbm_traffic.json",
+                ("all", "bf16"): "igemm_upd_bf16_resnet50_all_n256_hbm_traffic.json",
+                ("4,8,13,18", "f32"): "igemm_f32_resnet50_3x3_n256_hbm_traffic.json",
+                ("4,8,13,18", "bf16"): "igemm_bf16_resnet50_3x3_n256_hbm_traffic.json"}
 
 
 def summarize_pmc(fetch_csv, write_csv, out):
@@ -143,35 +153,48 @@ def summarize_counters(path, out):
 
 
 def algorithmic_bytes(l, N, es, which):
-    """Each operand once: I + W + O (dW fp32 for the update pass)."""
-    i = N * l.C * l.H * l.W * es
+    """Each operand once: I + W + O (dW fp32 for the update pass).  An unpadded 1x1 filter
+    with a stride reads (forward, update) only the N*C*P*Q input pixels it samples; its
+    backward pass still writes all of dI (the zeros included)."""
+    sampled = l.R == 1 and l.S == 1 and l.stride > 1 and l.pads == (0, 0) and which != "bwd"
+    i = N * l.C * (l.P * l.Q if sampled else l.H * l.W) * es
     o = N * l.K * l.P * l.Q * es
     w = l.K * l.C * l.R * l.S
     return i + o + w * (4 if which == "upd" else es)
 
 
-def make_layers(ids, N, dtype_name, workload="resnet50"):
+def layer_class(l):
+    """The three families of Table I the target names separately."""
+    if l.R == 1 and l.S == 1:
+        return "1x1"
+    return "conv1" if l.C <= 4 else "%dx%d" % (l.R, l.S)
+
+
+def make_layers(ids, N, dtype_names, workload="resnet50"):
+    """One resident layer set per requested type, all fed from the same generated host
+    arrays (bf16: rounded once, to nearest even, by the upload's type conversion)."""
     import torch
     from paper_1808_05567_amd import conv, inputs
-    dt = conv.CONV_BF16 if dtype_name == "bf16" else conv.CONV_F32
-    out = []
+    out = {d: [] for d in dtype_names}
     for lid in ids:
         l = inputs.layer(lid, workload)
-        L = conv.ConvLayer(N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dt)
         I = inputs.gen_input(N, l.C, l.H, l.W, lid)
         Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
         dO = inputs.gen_outgrad(N, l.K, l.P, l.Q, lid)
-        # separate resident buffers per pass so that no pass overwrites another's input
-        L.set_input(I)
-        L.set_weights(Wt)
-        L.x_blk = L.in_blk
-        L.dy_blk = torch.empty_like(L.out_blk)
-        L.out_blk, keep = L.dy_blk, L.out_blk
-        L.set_outgrad(dO)
-        L.out_blk = keep
-        L.dx_blk = torch.empty_like(L.in_blk)
+        for d in dtype_names:
+            dt = conv.CONV_BF16 if d == "bf16" else conv.CONV_F32
+            L = conv.ConvLayer(N, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dt)
+            # separate resident buffers per pass so that no pass overwrites another's input
+            L.set_input(I)
+            L.set_weights(Wt)
+            L.x_blk = L.in_blk
+            L.dy_blk = torch.empty_like(L.out_blk)
+            L.out_blk, keep = L.dy_blk, L.out_blk
+            L.set_outgrad(dO)
+            L.out_blk = keep
+            L.dx_blk = torch.empty_like(L.in_blk)
+            out[d].append((l, L))
         del I, Wt, dO
-        out.append((l, L))
     torch.cuda.synchronize()
     return out
 
@@ -184,6 +207,130 @@ def launch(L, which):
         conv.conv_bwd_data(L.h, L.dy_blk, L.wt_blk, L.dx_blk, L.ws)
     else:
         conv.conv_upd(L.h, L.x_blk, L.dy_blk, L.dwt_blk, L.ws)
+
+
+PASSES = ("fwd", "bwd", "upd")
+
+
+def time_workload(layers, N, steps, warmup):
+    """W untimed steps, then exactly K timed steps between two synchronisations; every launch
+    sits between two events on the stream the kernels run on (torch's current stream is the
+    one handed to the library).  Returns wall seconds and the mean duration (ms) per
+    (layer id, pass)."""
+    import torch
+
+    for _ in range(warmup):
+        for _, L in layers:
+            for which in PASSES:
+                launch(L, which)
+    torch.cuda.synchronize()
+    ev = {}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for l, L in layers:
+            for which in PASSES:
+                a = torch.cuda.Event(enable_timing=True)
+                b = torch.cuda.Event(enable_timing=True)
+                a.record()
+                launch(L, which)
+                b.record()
+                ev.setdefault((l.id, which), []).append((a, b))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
+    return wall, per
+
+
+def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
+    """Whole-workload rate, per-class rates and the roofline block of the dominant kernel."""
+    peak = MFMA_PEAK[dtype_name]
+    flops_step = sum(3 * l.flops(N) for l, _ in layers)
+    ms_per_step = wall * 1e3 / steps
+    value = flops_step / (wall / steps) / 1e12
+
+    def rate(ls, which):
+        fl = sum(l.flops(N) for l in ls)
+        ms = sum(per[(l.id, which)] for l in ls)
+        return fl / (ms * 1e-3) / 1e12
+
+    per_class = {}
+    for cls in sorted({layer_class(l) for l, _ in layers}):
+        ls = [l for l, _ in layers if layer_class(l) == cls]
+        tf = {w: rate(ls, w) for w in PASSES}
+        allp = sum(3 * l.flops(N) for l in ls) / (sum(per[(l.id, w)] for l in ls for w in PASSES) * 1e-3) / 1e12
+        per_class[cls] = {"layers": [l.id for l in ls],
+                          "per_pass_tflops": {w: round(tf[w], 2) for w in PASSES},
+                          "per_pass_pct_of_mfma_peak": {w: round(100 * tf[w] / peak, 1) for w in PASSES},
+                          "tflops": round(allp, 2), "pct_of_mfma_peak": round(100 * allp / peak, 1)}
+    # Dominant kernel: the implicit-GEMM kernel.  A forward launch is exactly one launch of it,
+    # so the forward events are its launch durations: achieved = algorithmic flops of the
+    # forward launches / their summed duration.
+    all_l = [l for l, _ in layers]
+    achieved = rate(all_l, "fwd")
+    # HBM bytes per implicit-GEMM launch (forward and backward launches together: the counter
+    # run cannot tell them apart), from the committed rocprofv3 counter summary of this same
+    # workload; null when there is none.
+    traffic = None
+    if traffic_file and os.path.exists(traffic_file):
+        try:
+            ks = json.load(open(traffic_file))["kernels"]
+            ig = [(v["calls"], v["fetch_bytes"] + v["write_bytes"]) for k, v in ks.items()
+                  if "igemm_kernel" in k]
+            traffic = round(sum(c * b for c, b in ig) / sum(c for c, _ in ig))
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": traffic,
+                "kernel": "igemm_kernel (the forward launches of the workload's layers)",
+                "per_pass_tflops": {w: round(rate(all_l, w), 2) for w in PASSES}}
+    return {"value": round(value, 3), "ms_per_step": round(ms_per_step, 4),
+            "pct_of_mfma_peak": round(100 * value / peak, 2), "per_class": per_class,
+            "roofline": roofline}
+
+
+def measure_ceilings():
+    """What this device sustains on loops that do nothing else (kernels of the library's own
+    ceilings.hip, timed here with events): MFMA issue per type, a 1 GiB copy, L2 -> LDS
+    streaming in the forward kernel's staging pattern."""
+    import torch
+    from paper_1808_05567_amd import conv
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            best = ms if best is None else min(best, ms)
+        return best * 1e-3
+
+    out = {}
+    blocks, iters = 256 * 2, 20000      # two waves per SIMD on every CU
+    sink = torch.empty(256 * 8 * 256, dtype=torch.float32, device="cuda")
+    for name, dt, k in (("mfma_f32_tflops", conv.CONV_F32, 2), ("mfma_bf16_tflops", conv.CONV_BF16, 16)):
+        it = iters if dt == conv.CONV_BF16 else iters // 2
+        s = timed(lambda: conv.conv_ceiling_mfma(dt, blocks, it, sink))
+        out[name] = round(blocks * 4 * it * 8 * 2 * 32 * 32 * k / s / 1e12, 1)
+    src = torch.empty(CALIB_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    s = timed(lambda: conv.conv_ceiling_copy(dst, src, CALIB_BYTES))
+    out["hbm_copy_tbps"] = round(2 * CALIB_BYTES / s / 1e12, 2)
+    del dst
+    for name, nb in (("l2_to_lds_tbps_1wg_per_cu", 256), ("l2_to_lds_tbps_8wg_per_cu", 2048)):
+        it = 2000
+        s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 16 << 20, nb, it, sink))
+        out[name] = round(nb * it * 32768 / s / 1e12, 2)
+    del src, sink
+    out["note"] = ("MFMA: 512 workgroups x 4 waves (two waves per SIMD), eight independent 32x32 "
+                   "accumulator tiles per wave; copy: 1 GiB, read + write bytes counted; L2->LDS: "
+                   "32 KiB windows re-read from L2 with loads that write into LDS")
+    return out
 
 
 def cpu_baseline(ids, n_cpu, workload="resnet50"):
@@ -205,7 +352,7 @@ def cpu_baseline(ids, n_cpu, workload="resnet50"):
         oracle.upd(I, dO, l.R, l.S, l.stride, l.pad)
         secs += time.perf_counter() - t0
         flops += 3 * l.flops(n_cpu)
-    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+    return {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle",
             "sample": "layers %s, fwd+bwd_data+upd, fp64 naive loops, minibatch %d instead of %d "
                       "(%.1f s of CPU time)" % (",".join(map(str, ids)), n_cpu, N_BATCH, secs)}
@@ -248,6 +395,8 @@ def lib_gemm_context(args):
 def main():
     args = parse()
     if args.lib_gemm:
+        args.dtype = args.dtype or "f32"
+        args.layers = args.layers or "4,8,13,18"
         lib_gemm_context(args)
         return
     if args.summarize_pmc:
@@ -264,24 +413,19 @@ def main():
     from paper_1808_05567_amd import inputs
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.layers is None:
-        args.layers = "4,8,13,18" if args.workload == "resnet50" else "all"
+        args.layers = "all"
     if args.layers == "all":
         ids = [l.id for l in inputs.WORKLOADS[args.workload]]
     else:
         ids = [int(x) for x in args.layers.split(",")]
     N = args.batch
-    es = 2 if args.dtype == "bf16" else 4
-    layers = make_layers(ids, N, args.dtype, args.workload)
-    passes = ("fwd", "bwd", "upd")
+    dtypes = [args.dtype] if args.dtype else ["f32", "bf16"]
+    head = dtypes[0]
+    sets = make_layers(ids, N, dtypes, args.workload)
 
-    def step():
-        for _, L in layers:
-            for which in passes:
-                launch(L, which)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measure_ceilings()
     if args.calib_copy:
         src = torch.empty(CALIB_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -290,161 +434,146 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # Per-launch HIP events on the stream the kernels run on (torch's current
-    # stream is the one handed to the library), recorded inside the timed region.
-    ev = {}
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        for l, L in layers:
-            for which in passes:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record()
-                launch(L, which)
-                b.record()
-                ev.setdefault((l.id, which), []).append((a, b))
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    wname = "ResNet-50 Table I" if args.workload == "resnet50" else "Inception-v3 (distinct shapes)"
+    summ, pers = {}, {}
+    for d in dtypes:
+        wall, per = time_workload(sets[d], N, args.steps, args.warmup)
+        tf = None
+        if args.workload == "resnet50" and N == N_BATCH and (args.layers, d) in TRAFFIC_FILE:
+            tf = os.path.join(ROOT, "profiles", TRAFFIC_FILE[(args.layers, d)])
+        summ[d] = summarize(sets[d], N, d, wall, per, args.steps, tf)
+        pers[d] = per
 
-    flops_step = sum(3 * l.flops(N) for l, _ in layers)
-    ms_per_step = wall * 1e3 / args.steps
-    value = flops_step / (wall / args.steps) / 1e12
-
-    per = {}
-    for key, pairs in ev.items():
-        per[key] = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)  # ms
-    # Dominant kernel: the implicit-GEMM kernel; its forward launches are single-kernel
-    # passes, so their event durations are its launch durations.
-    fwd_flops = sum(l.flops(N) for l, _ in layers)
-    fwd_ms = sum(per[(l.id, "fwd")] for l, _ in layers)
-    achieved = fwd_flops / (fwd_ms * 1e-3) / 1e12
-    peak = MFMA_PEAK[args.dtype]
-    # HBM bytes per igemm launch, from the committed rocprofv3 counter summary of this
-    # same workload (see profiles/); null when the workload differs or none exists.
-    traffic = None
-    tf_path = os.path.join(ROOT, "profiles", TRAFFIC_FILE[args.dtype])
-    if (args.workload == "resnet50" and args.layers == "4,8,13,18" and N == N_BATCH
-            and os.path.exists(tf_path)):
-        try:
-            ks = json.load(open(tf_path))["kernels"]
-            ig = [(v["calls"], v["fetch_bytes"] + v["write_bytes"]) for k, v in ks.items()
-                  if "igemm_kernel" in k]
-            traffic = round(sum(c * b for c, b in ig) / sum(c for c, _ in ig))
-        except Exception:
-            traffic = None
-    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": traffic,
-                "kernel": "igemm_kernel (forward launches of the workload's layers)",
-                "per_pass_tflops": {
-                    w: round(sum(l.flops(N) for l, _ in layers) /
-                             (sum(per[(l.id, w)] for l, _ in layers) * 1e-3) / 1e12, 2)
-                    for w in passes}}
-
+    h = summ[head]
     result = {
         "metric": "conv TFLOPS per pass (fwd/bwd/upd) on %s layers; %% of MFMA peak" % (
             "ResNet-50" if args.workload == "resnet50" else "Inception-v3"),
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "%s layers %s, N=%d, %s, fwd+bwd_data+upd per layer, "
-                               "blocked tensors resident in HBM" % (
-                                   "ResNet-50 Table I" if args.workload == "resnet50"
-                                   else "Inception-v3 (distinct shapes)", args.layers, N, args.dtype),
-                   "pct_of_mfma_peak": round(100 * value / peak, 2)},
-        "roofline": roofline,
+        "value": h["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": h["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": head, "data": "synthetic",
+        "config": {"workload": "%s, layers %s (%d layers), N=%d, %s, fwd+bwd_data+upd per layer, "
+                               "blocked tensors resident in HBM" % (wname, args.layers, len(ids), N, head),
+                   "pct_of_mfma_peak": h["pct_of_mfma_peak"], "per_class": h["per_class"]},
+        "roofline": h["roofline"],
     }
+    for d in dtypes[1:]:
+        result[d] = {"workload": "the same layers and passes, N=%d, %s tensors, fp32 accumulation, "
+                                 "fp32 weight gradients" % (N, d),
+                     "value": summ[d]["value"], "unit": "TFLOP/s", "ms_per_step": summ[d]["ms_per_step"],
+                     "steps": args.steps, "warmup": args.warmup,
+                     "pct_of_mfma_peak": summ[d]["pct_of_mfma_peak"], "per_class": summ[d]["per_class"],
+                     "roofline": summ[d]["roofline"]}
+    if ceilings:
+        result["measured_ceilings"] = ceilings
 
     if args.table:
-        # The timed loop above cycles through all layers and passes, so at N = 256 every
-        # launch finds its operands evicted from the 256 MB last-level cache (the cold
-        # regime).  The warm regime: the same launch repeated back to back on the same
-        # buffers (what a layer benchmark that loops over one layer measures).
-        warm = {}
-        for l, L in layers:
-            for which in passes:
-                launch(L, which)
-                evs = []
-                for _ in range(max(3, args.steps)):
-                    a0 = torch.cuda.Event(enable_timing=True)
-                    a1 = torch.cuda.Event(enable_timing=True)
-                    a0.record()
-                    launch(L, which)
-                    a1.record()
-                    evs.append((a0, a1))
-                torch.cuda.synchronize()
-                warm[(l.id, which)] = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
-        rows = []
-        for l, L in layers:
-            for which in passes:
-                ms = per[(l.id, which)]
-                tf = l.flops(N) / (ms * 1e-3) / 1e12
-                by = algorithmic_bytes(l, N, es, which)
-                ceil = min(peak, l.flops(N) / by * HBM_PEAK)
-                rows.append({"layer": l.id, "pass": which, "ms": round(ms, 4), "tflops": round(tf, 2),
-                             "pct_mfma_peak": round(100 * tf / peak, 1),
-                             "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
-                             "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1),
-                             "ms_warm": round(warm[(l.id, which)], 4)})
-        from paper_1808_05567_amd import conv as _conv
-        # forward pass with bias + residual + ReLU fused into its store, timed on its own
-        # (dy_blk, a tensor of the output's shape, stands in for the residual)
-        for l, L in layers:
-            bias = torch.zeros(L.info.Kp, dtype=torch.float32, device="cuda")
-            kw = dict(bias=bias, residual=L.dy_blk, relu=True, ws=L.ws)
-            _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+        for d in dtypes:
+            layer_table(args, sets[d], N, d, pers[d], ceilings)
+
+    for d in dtypes:
+        for _, L in sets[d]:
+            L.close()
+    if not args.no_cpu:
+        n_cpu = args.cpu_batch or (32 if len(ids) > 8 else 128)
+        result["cpu_baseline"] = cpu_baseline(ids, n_cpu, args.workload)
+    print(json.dumps(result), flush=True)
+
+
+def layer_table(args, layers, N, dtype_name, per, ceilings):
+    """Per layer and pass: the cycling loop's duration (operands evicted from the 256 MB
+    last-level cache between launches: cold), the same launch repeated back to back (warm),
+    % of the published MFMA peak, % of the layer's own ceiling min(MFMA peak, AI x HBM rate)
+    at the published figures and at the measured ones."""
+    import torch
+    from paper_1808_05567_amd import conv as _conv
+    es = 2 if dtype_name == "bf16" else 4
+    peak = MFMA_PEAK[dtype_name]
+    m_peak = (ceilings or {}).get("mfma_%s_tflops" % dtype_name)
+    m_hbm = (ceilings or {}).get("hbm_copy_tbps")
+    warm = {}
+    for l, L in layers:
+        for which in PASSES:
+            launch(L, which)
             evs = []
-            for _ in range(args.steps):
+            for _ in range(max(3, args.steps)):
                 a0 = torch.cuda.Event(enable_timing=True)
                 a1 = torch.cuda.Event(enable_timing=True)
                 a0.record()
-                _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+                launch(L, which)
                 a1.record()
                 evs.append((a0, a1))
             torch.cuda.synchronize()
-            ms = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
-            tf = l.flops(N) / (ms * 1e-3) / 1e12
-            by = algorithmic_bytes(l, N, es, "fwd") + N * l.K * l.P * l.Q * es
-            ceil = min(peak, l.flops(N) / by * HBM_PEAK)
-            rows.append({"layer": l.id, "pass": "fwd_fused", "ms": round(ms, 4), "tflops": round(tf, 2),
-                         "pct_mfma_peak": round(100 * tf / peak, 1),
-                         "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
-                         "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
-        # layout conversion, timed on its own (the passes work on resident blocked tensors)
-        for l, L in layers:
-            nchw = torch.empty((N, l.C, l.H, l.W), dtype=L.tdtype, device="cuda")
-            nkpq = torch.empty((N, l.K, l.P, l.Q), dtype=L.tdtype, device="cuda")
-            for name, fn, src, dst, by in (
-                    ("pack_in", _conv.conv_pack_in, nchw, L.x_blk, 2 * nchw.numel() * es),
-                    ("unpack_out", _conv.conv_unpack_out, L.out_blk, nkpq, 2 * nkpq.numel() * es)):
-                fn(L.h, src, dst)
-                a0 = torch.cuda.Event(enable_timing=True)
-                a1 = torch.cuda.Event(enable_timing=True)
-                a0.record()
-                for _ in range(5):
-                    fn(L.h, src, dst)
-                a1.record()
-                torch.cuda.synchronize()
-                ms = a0.elapsed_time(a1) / 5
-                rows.append({"layer": l.id, "pass": name, "ms": round(ms, 4), "tflops": 0.0,
-                             "pct_mfma_peak": 0.0, "ceiling_tflops": 0.0, "pct_ceiling": 0.0,
-                             "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
-            del nchw, nkpq
-        os.makedirs(args.table_dir, exist_ok=True)
-        path = os.path.join(args.table_dir, "layers_%s%s.json" % (
-            "" if args.workload == "resnet50" else args.workload + "_", args.dtype))
-        with open(path, "w") as f:
-            json.dump(rows, f, indent=1)
-        for r in rows:
-            print("# L%-2d %-10s %8.3f ms %8.2f TF/s %5.1f%% peak %5.1f%% of ceiling %7.1f GB/s%s" % (
-                r["layer"], r["pass"], r["ms"], r["tflops"], r["pct_mfma_peak"], r["pct_ceiling"],
-                r["alg_GBps"], "  warm %8.3f ms" % r["ms_warm"] if "ms_warm" in r else ""),
-                file=sys.stderr)
+            warm[(l.id, which)] = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
 
-    for _, L in layers:
-        L.close()
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(ids, args.cpu_batch, args.workload)
-    print(json.dumps(result), flush=True)
+    def row(l, which, ms, by, extra=None):
+        tf = l.flops(N) / (ms * 1e-3) / 1e12
+        ceil = min(peak, l.flops(N) / by * HBM_PEAK)
+        r = {"layer": l.id, "pass": which, "ms": round(ms, 4), "tflops": round(tf, 2),
+             "pct_mfma_peak": round(100 * tf / peak, 1),
+             "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
+             "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)}
+        if m_peak and m_hbm:
+            mc = min(m_peak, l.flops(N) / by * m_hbm)
+            r["measured_ceiling_tflops"] = round(mc, 1)
+            r["pct_measured_ceiling"] = round(100 * tf / mc, 1)
+        if extra:
+            r.update(extra)
+        return r
+
+    rows = []
+    for l, L in layers:
+        for which in PASSES:
+            rows.append(row(l, which, per[(l.id, which)], algorithmic_bytes(l, N, es, which),
+                            {"ms_warm": round(warm[(l.id, which)], 4)}))
+    # forward pass with bias + residual + ReLU fused into its store, timed on its own
+    # (dy_blk, a tensor of the output's shape, stands in for the residual)
+    for l, L in layers:
+        bias = torch.zeros(L.info.Kp, dtype=torch.float32, device="cuda")
+        kw = dict(bias=bias, residual=L.dy_blk, relu=True, ws=L.ws)
+        _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+        evs = []
+        for _ in range(args.steps):
+            a0 = torch.cuda.Event(enable_timing=True)
+            a1 = torch.cuda.Event(enable_timing=True)
+            a0.record()
+            _conv.conv_fwd_fused(L.h, L.x_blk, L.wt_blk, L.out_blk, **kw)
+            a1.record()
+            evs.append((a0, a1))
+        torch.cuda.synchronize()
+        ms = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
+        rows.append(row(l, "fwd_fused", ms,
+                        algorithmic_bytes(l, N, es, "fwd") + N * l.K * l.P * l.Q * es))
+    # layout conversion, timed on its own (the passes work on resident blocked tensors)
+    for l, L in layers:
+        nchw = torch.empty((N, l.C, l.H, l.W), dtype=L.tdtype, device="cuda")
+        nkpq = torch.empty((N, l.K, l.P, l.Q), dtype=L.tdtype, device="cuda")
+        for name, fn, src, dst, by in (
+                ("pack_in", _conv.conv_pack_in, nchw, L.x_blk, 2 * nchw.numel() * es),
+                ("unpack_out", _conv.conv_unpack_out, L.out_blk, nkpq, 2 * nkpq.numel() * es)):
+            fn(L.h, src, dst)
+            a0 = torch.cuda.Event(enable_timing=True)
+            a1 = torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(5):
+                fn(L.h, src, dst)
+            a1.record()
+            torch.cuda.synchronize()
+            ms = a0.elapsed_time(a1) / 5
+            rows.append({"layer": l.id, "pass": name, "ms": round(ms, 4), "tflops": 0.0,
+                         "pct_mfma_peak": 0.0, "ceiling_tflops": 0.0, "pct_ceiling": 0.0,
+                         "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)})
+        del nchw, nkpq
+    os.makedirs(args.table_dir, exist_ok=True)
+    path = os.path.join(args.table_dir, "layers_%s%s.json" % (
+        "" if args.workload == "resnet50" else args.workload + "_", dtype_name))
+    with open(path, "w") as f:
+        json.dump(rows, f, indent=1)
+    for r in rows:
+        print("# %-4s L%-2d %-10s %8.3f ms %8.2f TF/s %5.1f%% peak %5.1f%% of ceiling%s %7.1f GB/s%s" % (
+            dtype_name, r["layer"], r["pass"], r["ms"], r["tflops"], r["pct_mfma_peak"], r["pct_ceiling"],
+            " (%5.1f%% of measured)" % r["pct_measured_ceiling"] if "pct_measured_ceiling" in r else "",
+            r["alg_GBps"], "  warm %8.3f ms" % r["ms_warm"] if "ms_warm" in r else ""),
+            file=sys.stderr)
 
 
 if __name__ == "__main__":

@@ -217,6 +217,32 @@ conv_status_t conv_unpack_dwt(conv_handle_t h, const void *blk_f32, void *kcrs_f
  * an unknown pass, CONV_EUNSUPPORTED if the pass has no kernel. */
 conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buflen);
 
+/* Measured ceilings of the device, for the roofline columns of a benchmark (Section III
+ * quotes kernel rates against the machine's peak; these loops measure what part of a
+ * published peak this device sustains on a loop that does nothing else).  They only
+ * launch: the caller owns every buffer and times the launch with events on `stream`.
+ * None of them is part of the convolution path.
+ *
+ * conv_ceiling_mfma: `blocks` workgroups of 4 waves, each wave issuing `iters` rounds of
+ *   eight independent 32x32 MFMAs of the type (fp32: 32x32x2, bf16: 32x32x16) from
+ *   registers.  Flops = blocks * 4 * iters * 8 * 2*32*32*k, k = 2 (fp32) or 16 (bf16).
+ *   sink: device, blocks * 256 floats, written once (keeps the loop alive).
+ * conv_ceiling_copy: dst[0, bytes) = src[0, bytes), 16 bytes per lane; device pointers,
+ *   16-byte aligned, bytes a multiple of 16.  HBM traffic = 2 * bytes.
+ * conv_ceiling_l2_to_lds: `blocks` workgroups of 4 waves, each streaming its own 32 KiB
+ *   window of src (window index = workgroup index modulo src_bytes / 32 KiB) into LDS
+ *   `iters` times with 16-byte loads that write straight into LDS: the staging pattern of
+ *   the forward kernel, served from L2 after the first pass.  Bytes moved =
+ *   blocks * iters * 32 KiB.  src: device, 16-byte aligned, 32 KiB <= src_bytes < 4 GiB;
+ *   sink as above.
+ * Errors: CONV_EINVAL for a NULL or misaligned pointer or a count < 1, CONV_EUNSUPPORTED
+ * beyond the stated sizes, CONV_ELAUNCH if the runtime refuses the launch. */
+conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink,
+                                void *stream);
+conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *stream);
+conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks,
+                                     int32_t iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

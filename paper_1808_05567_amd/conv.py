@@ -25,6 +25,7 @@ EXPORTS = (
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
+    "conv_ceiling_mfma", "conv_ceiling_copy", "conv_ceiling_l2_to_lds",
 )
 
 
@@ -86,6 +87,9 @@ def load():
                  "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt"):
         getattr(lib, name).argtypes = [vp, vp, vp, vp]
     lib.conv_describe.argtypes = [vp, ctypes.c_int32, ctypes.c_char_p, ctypes.c_size_t]
+    lib.conv_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.conv_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
     for name in EXPORTS:
         if name != "conv_status_str":
             getattr(lib, name).restype = ctypes.c_int
@@ -207,6 +211,20 @@ def conv_bwd_data_ws(h, dout, wt, din, ws, stream=None):
 def conv_upd_ws(h, inp, dout, dwt, ws, stream=None):
     _check(load().conv_upd_ws(h, _ptr(inp), _ptr(dout), _ptr(dwt), _ptr(ws), _ws_bytes(ws),
                               _stream(stream)), "conv_upd_ws")
+
+
+def conv_ceiling_mfma(dtype, blocks, iters, sink, stream=None):
+    _check(load().conv_ceiling_mfma(dtype, blocks, iters, _ptr(sink), _stream(stream)),
+           "conv_ceiling_mfma")
+
+
+def conv_ceiling_copy(dst, src, nbytes, stream=None):
+    _check(load().conv_ceiling_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "conv_ceiling_copy")
+
+
+def conv_ceiling_l2_to_lds(src, src_bytes, blocks, iters, sink, stream=None):
+    _check(load().conv_ceiling_l2_to_lds(_ptr(src), src_bytes, blocks, iters, _ptr(sink),
+                                         _stream(stream)), "conv_ceiling_l2_to_lds")
 
 
 def _perm(name):

@@ -1416,7 +1416,7 @@ conv_status_t conv_upd(conv_handle_t h, const void *in, const void *dout, void *
 
 namespace {
 // bytes of workspace a pass of this plan reads or writes
-size_t pass_ws_bytes(const conv_plan *h, int pass)
+static size_t pass_ws_bytes(const conv_plan *h, int pass)
 {
     const bool chunked = pass == 0 ? h->fwd_chunked : pass == 1 ? h->bwd_chunked : h->upd_chunked;
     if (chunked) {

@@ -1,0 +1,137 @@
+// Measured ceilings of the machine, for the benchmark's roofline columns: what the matrix
+// cores, the HBM and the L2 -> LDS path of THIS device sustain on loops that do nothing else.
+// The convolution kernels are priced against the published peaks; these loops say how much
+// of a published peak a kernel can reach at all (Section III of the paper likewise quotes
+// its kernels against what the machine sustains on a plain compute loop).
+//
+// None of this is on the convolution path: the entry points only launch, take every buffer
+// from the caller and are timed by the caller with events on the same stream.
+#include <algorithm>
+
+#include "conv_internal.h"
+
+namespace convmi {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// `iters` rounds of eight independent 32x32 MFMAs per wave (eight accumulator tiles, 128
+// registers: the register blocking of the convolution kernels), operands held in registers.
+template <bool BF16>
+__global__ __launch_bounds__(256) void mfma_issue_kernel(float *sink, int iters)
+{
+    f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc[i][t] = (float)i;  // (distinct chains: nothing to merge)
+    const float seed = (float)(threadIdx.x & 7) * 0.125f;
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (BF16) {
+            bf16x8 a, b;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                a[t] = (__bf16)(seed + (float)t);
+                b[t] = (__bf16)(seed - (float)t);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(seed, seed + 1.0f, acc[i], 0, 0, 0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s += acc[i][t];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// dst[i] = src[i], 16 bytes per lane and step, grid-stride.
+__global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                   size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+// The staging pattern of the implicit-GEMM kernel with nothing behind it: every workgroup
+// streams its own 32 KB window of `src` (small enough to stay in the L2 of its XCD) into a
+// ring of two LDS buffers with 16-byte loads that write straight into LDS, `iters` times.
+constexpr int kWindow = 32 * 1024;
+__global__ __launch_bounds__(256) void l2_to_lds_kernel(const void *src, size_t src_bytes, float *sink,
+                                                        int iters)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t windows = src_bytes / kWindow;
+    const size_t base = ((size_t)blockIdx.x % windows) * kWindow;
+    const rsrc_t r = make_rsrc(src, base, base + kWindow);
+    // 2048 chunks of 16 bytes per window: 8 wave-level loads per wave
+    for (int it = 0; it < iters; ++it) {
+        unsigned char *buf = lds + (it & 1) * kWindow;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int chunk = (i * 4 + wave) * 64;
+            load_to_lds_16(r, (unsigned)(chunk + lane) * 16u, 0u, buf + chunk * 16);
+        }
+        // (at most one window's loads in flight behind the one being waited for)
+        if (it > 0) __builtin_amdgcn_s_waitcnt(0x0F78 | 8);  // vmcnt(8): the previous window landed
+    }
+    wait_all_memory();
+    __syncthreads();
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] =
+        reinterpret_cast<const float *>(lds)[(threadIdx.x * 4 + blockIdx.x) % (2 * kWindow / 4)];
+}
+
+}  // namespace
+}  // namespace convmi
+
+using namespace convmi;
+
+extern "C" {
+
+conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink, void *stream)
+{
+    if ((dtype != CONV_F32 && dtype != CONV_BF16) || blocks < 1 || iters < 1 || !sink) return CONV_EINVAL;
+    if (dtype == CONV_BF16)
+        hipLaunchKernelGGL(mfma_issue_kernel<true>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink,
+                           iters);
+    else
+        hipLaunchKernelGGL(mfma_issue_kernel<false>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink,
+                           iters);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || bytes < 16 || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+        return CONV_EINVAL;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(src), n16);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks, int32_t iters,
+                                     float *sink, void *stream)
+{
+    if (!src || !sink || src_bytes < (size_t)kWindow || blocks < 1 || iters < 1 || ((uintptr_t)src & 15))
+        return CONV_EINVAL;
+    if (src_bytes >= ((size_t)1 << 32)) return CONV_EUNSUPPORTED;
+    const size_t lds_bytes = 2 * kWindow;
+    if (ensure_dynamic_lds(reinterpret_cast<const void *>(l2_to_lds_kernel), lds_bytes) != hipSuccess)
+        return CONV_ELAUNCH;
+    hipLaunchKernelGGL(l2_to_lds_kernel, dim3(blocks), dim3(256), lds_bytes, (hipStream_t)stream, src,
+                       src_bytes, sink, iters);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+}  // extern "C"

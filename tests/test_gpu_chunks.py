@@ -7,7 +7,7 @@ import pytest
 import oracle
 from paper_1808_05567_amd import conv, inputs
 
-from gpu_util import TOL, make_inputs, rel_l2, run_pass
+from gpu_util import assert_close, make_inputs, run_pass
 
 pytestmark = pytest.mark.gpu
 
@@ -38,11 +38,11 @@ def test_chunked_passes_match_oracle(shape, max_images, dtype):
             assert conv.conv_describe(L.h, which).startswith("chunks=%d images=%d: " % (n_chunks, max_images))
         assert L.info.upd_splits == n_chunks
         got = run_pass(L, "fwd", I=I, Wt=Wt)
-        assert rel_l2(got, oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.fwd(I, Wt, stride, pad), dtype, "fwd")
         got = run_pass(L, "bwd", dO=dO, Wt=Wt)
-        assert rel_l2(got, oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype, "bwd")
         got = run_pass(L, "upd", I=I, dO=dO)
-        assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+        assert_close(got, oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32, "upd")
     finally:
         L.close()
 
@@ -76,7 +76,7 @@ def test_chunked_fused_forward_takes_the_residual_slice(dtype):
         torch.cuda.synchronize()
         got = L.get_output().float().cpu().numpy()
         ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias, residual=res, relu=True, scale=scale)
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_close(got, ref, dtype, "fused chunks")
     finally:
         L.close()
 
@@ -122,7 +122,7 @@ def _sampled_parity(shape, dtype, seed, chunked):
         got = out[imgs].float().cpu().numpy()
         assert bool(torch.isfinite(out).all())
         del out
-        assert rel_l2(got, oracle.fwd(I[imgs], Wt, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.fwd(I[imgs], Wt, stride, pad), dtype, "fwd")
         print("fwd done", flush=True)
 
         L.set_outgrad(dO)
@@ -133,7 +133,7 @@ def _sampled_parity(shape, dtype, seed, chunked):
         got = din[imgs].float().cpu().numpy()
         assert bool(torch.isfinite(din).all())
         del din
-        assert rel_l2(got, oracle.bwd_data(dO[imgs], Wt, H, W, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.bwd_data(dO[imgs], Wt, H, W, stride, pad), dtype, "bwd")
         print("bwd done", flush=True)
 
         L.set_input(I)   # (the backward pass wrote dI over the blocked input)
@@ -148,7 +148,7 @@ def _sampled_parity(shape, dtype, seed, chunked):
         ent = np.concatenate([np.array([[0, 0, 0, 0], [K - 1, C - 1, R - 1, S - 1]], dtype=np.int32), ent])
         ref = sum(oracle.upd_entries(I[a:b], dO[a:b], R, S, stride, pad, ent)
                   for a, b in ((0, N // 2), (N // 2, N)))
-        assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5
+        assert_close(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref, conv.CONV_F32, "upd entries")
     finally:
         L.close()
 

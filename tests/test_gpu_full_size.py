@@ -11,15 +11,25 @@ import pytest
 import oracle
 from paper_1808_05567_amd import conv, inputs
 
-from gpu_util import TOL, rel_l2, run_pass
+from gpu_util import assert_close, run_pass
 
 pytestmark = pytest.mark.gpu
 
 N = 256
-CASES = [(1, conv.CONV_F32), (4, conv.CONV_F32), (8, conv.CONV_F32), (13, conv.CONV_F32), (18, conv.CONV_F32),
-         (2, conv.CONV_F32), (6, conv.CONV_F32), (17, conv.CONV_F32), (20, conv.CONV_F32),
-         (4, conv.CONV_BF16), (13, conv.CONV_BF16), (18, conv.CONV_BF16), (7, conv.CONV_BF16),
-         (14, conv.CONV_BF16), (1, conv.CONV_BF16)]
+# every layer of Table I in both types: each layer has its own tile, split and kernel variant
+# (layer-major order, so that the two types of a layer share one set of generated inputs)
+CASES = [(l.id, dt) for l in inputs.TABLE_I for dt in (conv.CONV_F32, conv.CONV_BF16)]
+_generated = {}
+
+
+def _inputs_of(l, lid):
+    """Seeded fp32 operands of a layer at N = 256, kept for the next case of the same layer."""
+    if lid not in _generated:
+        _generated.clear()
+        _generated[lid] = (inputs.gen_input(N, l.C, l.H, l.W, lid),
+                           inputs.gen_weights(l.K, l.C, l.R, l.S, lid),
+                           inputs.gen_outgrad(N, l.K, l.P, l.Q, lid))
+    return _generated[lid]
 
 
 def _entries(rng, K, C, R, S, count):
@@ -55,9 +65,7 @@ def test_inception_v3_layer_at_n256(lid, dtype):
 
 def _layer_at_n256(l, lid, dtype):
     print("layer", lid, "dtype", dtype, flush=True)
-    I = inputs.gen_input(N, l.C, l.H, l.W, lid)
-    Wt = inputs.gen_weights(l.K, l.C, l.R, l.S, lid)
-    dO = inputs.gen_outgrad(N, l.K, l.P, l.Q, lid)
+    I, Wt, dO = _inputs_of(l, lid)
     if dtype == conv.CONV_BF16:
         I, Wt, dO = (inputs.round_to_bf16(x) for x in (I, Wt, dO))
     rng = np.random.default_rng(1000 + lid)
@@ -66,17 +74,17 @@ def _layer_at_n256(l, lid, dtype):
     try:
         got = run_pass(L, "fwd", I=I, Wt=Wt)
         ref = oracle.fwd(I[imgs], Wt, l.stride, l.pad)
-        assert rel_l2(got[imgs], ref) <= TOL[dtype]
+        assert_close(got[imgs], ref, dtype, "fwd")
         assert np.isfinite(got).all()
         got = run_pass(L, "bwd", dO=dO, Wt=Wt)
         ref = oracle.bwd_data(dO[imgs], Wt, l.H, l.W, l.stride, l.pad)
-        assert rel_l2(got[imgs], ref) <= TOL[dtype]
+        assert_close(got[imgs], ref, dtype, "bwd")
         assert np.isfinite(got).all()
         got = run_pass(L, "upd", I=I, dO=dO)
         ent = _entries(rng, l.K, l.C, l.R, l.S, 512 if l.H > 200 else 2048)
         ref = oracle.upd_entries(I.astype(np.float64), dO.astype(np.float64), l.R, l.S,
                                  l.stride, l.pad, ent)
-        assert rel_l2(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref) <= 1e-5
+        assert_close(got[ent[:, 0], ent[:, 1], ent[:, 2], ent[:, 3]], ref, conv.CONV_F32, "upd")
         assert np.isfinite(got).all()
     finally:
         L.close()
@@ -150,6 +158,6 @@ def test_single_image_inference_forward(lid, dtype):
     L = conv.ConvLayer(1, l.C, l.K, l.H, l.W, l.R, l.S, l.stride, l.pad, dtype=dtype)
     try:
         got = run_pass(L, "fwd", I=I, Wt=Wt)
-        assert rel_l2(got, oracle.fwd(I, Wt, l.stride, l.pad)) <= TOL[dtype]
+        assert_close(got, oracle.fwd(I, Wt, l.stride, l.pad), dtype, "fwd")
     finally:
         L.close()

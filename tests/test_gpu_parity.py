@@ -7,7 +7,7 @@ import pytest
 import oracle
 from paper_1808_05567_amd import conv, inputs
 
-from gpu_util import TOL, make_inputs, rel_l2, run_pass
+from gpu_util import assert_close, make_inputs, run_pass
 
 pytestmark = pytest.mark.gpu
 
@@ -121,11 +121,11 @@ def test_direct_kernels_match_oracle(shape, dtype):
                  (conv.PASS_FWD, conv.PASS_BWD_DATA, conv.PASS_UPD)]
         assert "direct" in kinds, kinds
         got = run_pass(L, "fwd", I=I, Wt=Wt)
-        assert rel_l2(got, oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.fwd(I, Wt, stride, pad), dtype, "fwd")
         got = run_pass(L, "bwd", dO=dO, Wt=Wt)
-        assert rel_l2(got, oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype, "bwd")
         got = run_pass(L, "upd", I=I, dO=dO)
-        assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+        assert_close(got, oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32, "upd")
     finally:
         L.close()
 
@@ -138,12 +138,12 @@ def test_three_passes_match_oracle(shape, dtype):
     L = _layer(shape, dtype)
     try:
         got = run_pass(L, "fwd", I=I, Wt=Wt)
-        assert rel_l2(got, oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.fwd(I, Wt, stride, pad), dtype, "fwd")
         got = run_pass(L, "bwd", dO=dO, Wt=Wt)
-        assert rel_l2(got, oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
+        assert_close(got, oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype, "bwd")
         got = run_pass(L, "upd", I=I, dO=dO)
         # weight gradients are fp32 for both dtypes; bf16 products are exact in fp32
-        assert rel_l2(got, oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+        assert_close(got, oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32, "upd")
     finally:
         L.close()
 
@@ -158,10 +158,10 @@ def test_rectangular_filters_match_oracle(shape, dtype):
     I, Wt, dO = make_inputs(shape, dtype, layer_id=30 + R + 2 * S)
     L = _layer(shape, dtype)
     try:
-        assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
-        assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
-                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
-        assert rel_l2(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+        assert_close(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad), dtype, "fwd")
+        assert_close(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                     oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype, "bwd")
+        assert_close(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32, "upd")
     finally:
         L.close()
 
@@ -210,12 +210,12 @@ def test_seeded_descriptor_sweep_matches_oracle(shape, dtype):
     L = _layer(shape, dtype)
     ran = 0
     try:
-        for which, ref, tol in (
-                ("fwd", lambda: oracle.fwd(I, Wt, stride, pad), TOL[dtype]),
-                ("bwd", lambda: oracle.bwd_data(dO, Wt, H, W, stride, pad), TOL[dtype]),
-                ("upd", lambda: oracle.upd(I, dO, R, S, stride, pad), 1e-5)):
+        for which, ref, kind in (
+                ("fwd", lambda: oracle.fwd(I, Wt, stride, pad), dtype),
+                ("bwd", lambda: oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype),
+                ("upd", lambda: oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32)):
             got = run_pass(L, which, I=I, Wt=Wt, dO=dO)
-            assert rel_l2(got, ref()) <= tol, which
+            assert_close(got, ref(), kind, which)
             ran += 1
     finally:
         L.close()
@@ -232,10 +232,10 @@ def test_few_channel_layers_match_oracle(shape, dtype):
     I, Wt, dO = make_inputs(shape, dtype, layer_id=1)
     L = _layer(shape, dtype)
     try:
-        assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= TOL[dtype]
-        assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
-                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[dtype]
-        assert rel_l2(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad)) <= 1e-5
+        assert_close(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad), dtype, "fwd")
+        assert_close(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                     oracle.bwd_data(dO, Wt, H, W, stride, pad), dtype, "bwd")
+        assert_close(run_pass(L, "upd", I=I, dO=dO), oracle.upd(I, dO, R, S, stride, pad), conv.CONV_F32, "upd")
     finally:
         L.close()
 
@@ -249,8 +249,8 @@ def test_first_layer_backward_bf16(shape):
     I, Wt, dO = make_inputs(shape, conv.CONV_BF16, layer_id=1)
     L = _layer(shape, conv.CONV_BF16)
     try:
-        assert rel_l2(run_pass(L, "bwd", dO=dO, Wt=Wt),
-                      oracle.bwd_data(dO, Wt, H, W, stride, pad)) <= TOL[conv.CONV_BF16]
+        assert_close(run_pass(L, "bwd", dO=dO, Wt=Wt),
+                     oracle.bwd_data(dO, Wt, H, W, stride, pad), conv.CONV_BF16, "bwd")
     finally:
         L.close()
 
@@ -262,7 +262,9 @@ def test_first_layer_backward_bf16(shape):
                          ids=["3x3", "1x1s2", "1x1s2wide", "6x6direct", "4x4s2direct"])
 def test_integer_inputs_are_exact(shape, dtype):
     """Small integers: every product and partial sum is exact in fp32 (and the
-    values are exact in bf16), so any summation order gives the oracle's bits."""
+    values are exact in bf16), so any summation order gives the oracle's bits; a bf16
+    output is that exact value rounded once (to nearest even), in both the forward and the
+    backward pass."""
     N, C, K, H, W, R, S, stride, pad = shape
     P, Q = oracle.out_hw(H, W, R, S, stride, pad)
     I = inputs.gen_small_ints((N, C, H, W), -2, 2, which=3)
@@ -270,16 +272,17 @@ def test_integer_inputs_are_exact(shape, dtype):
     dO = inputs.gen_small_ints((N, K, P, Q), -2, 2, which=5)
     L = _layer(shape, dtype)
     try:
-        # bf16 outputs hold integers exactly only up to 256: 4*C*R*S must stay below
-        # that for an exact bf16 store, so compare fwd/bwd exactly in fp32 only
         got = run_pass(L, "upd", I=I, dO=dO)
         assert np.array_equal(got, oracle.upd(I, dO, R, S, stride, pad))
-        if dtype == conv.CONV_F32:
-            assert np.array_equal(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad))
-            assert np.array_equal(run_pass(L, "bwd", dO=dO, Wt=Wt),
-                                  oracle.bwd_data(dO, Wt, H, W, stride, pad))
-        else:
-            assert rel_l2(run_pass(L, "fwd", I=I, Wt=Wt), oracle.fwd(I, Wt, stride, pad)) <= 4e-3
+        # (all sums stay far below 2^24, so the fp32 accumulator holds the oracle's value exactly;
+        # a bf16 store keeps 8 significant bits of it)
+        out_type = inputs.round_to_bf16 if dtype == conv.CONV_BF16 else (lambda x: x)
+        ref = oracle.fwd(I, Wt, stride, pad)
+        assert np.abs(ref).max() < 2 ** 24
+        assert np.array_equal(run_pass(L, "fwd", I=I, Wt=Wt), out_type(ref.astype(np.float32)))
+        ref = oracle.bwd_data(dO, Wt, H, W, stride, pad)
+        assert np.abs(ref).max() < 2 ** 24
+        assert np.array_equal(run_pass(L, "bwd", dO=dO, Wt=Wt), out_type(ref.astype(np.float32)))
     finally:
         L.close()
 
@@ -398,7 +401,7 @@ def test_fused_forward_matches_oracle(shape, dtype):
             ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias if "bias" in kw else None,
                                    residual=res if "residual" in kw else None,
                                    relu=kw.get("relu", False), scale=scale if "scale" in kw else None)
-            assert rel_l2(got, ref) <= TOL[dtype], kw.keys()
+            assert_close(got, ref, dtype, "fused %s" % sorted(kw))
             if kw.get("relu"):
                 assert got.min() >= 0.0
         # in place: the residual is the output buffer itself
@@ -407,6 +410,6 @@ def test_fused_forward_matches_oracle(shape, dtype):
         torch.cuda.synchronize()
         got = L.get_output().float().cpu().numpy()
         ref = oracle.fwd_fused(I, Wt, stride, pad, bias=bias, residual=res, relu=True)
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_close(got, ref, dtype, "fused in place")
     finally:
         L.close()
