@@ -283,6 +283,9 @@ def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
                 "frac": round(achieved / peak, 4), "traffic": traffic,
                 "kernel": "igemm_kernel (the forward launches of the workload's layers)",
                 "per_pass_tflops": {w: round(rate(all_l, w), 2) for w in PASSES}}
+    es = 2 if dtype_name == "bf16" else 4
+    alg = {w: sum(algorithmic_bytes(l, N, es, w) for l in all_l) for w in PASSES}
+    roofline["algorithmic_bytes_per_step"] = alg
     return {"value": round(value, 3), "ms_per_step": round(ms_per_step, 4),
             "pct_of_mfma_peak": round(100 * value / peak, 2), "per_class": per_class,
             "roofline": roofline}
@@ -322,14 +325,17 @@ def measure_ceilings():
     s = timed(lambda: conv.conv_ceiling_copy(dst, src, CALIB_BYTES))
     out["hbm_copy_tbps"] = round(2 * CALIB_BYTES / s / 1e12, 2)
     del dst
-    for name, nb in (("l2_to_lds_tbps_1wg_per_cu", 256), ("l2_to_lds_tbps_8wg_per_cu", 2048)):
-        it = 2000
-        s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 16 << 20, nb, it, sink))
-        out[name] = round(nb * it * 32768 / s / 1e12, 2)
+    for wgs in (1, 2, 4):
+        for regs in (False, True):
+            it, nb = 4000, 256 * wgs
+            s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 24 << 20, nb, it, sink, regs))
+            out["l2_to_lds_tbps_%dwg_per_cu_%s" % (wgs, "via_registers" if regs else "lds_direct")] = round(
+                nb * it * 16384 / s / 1e12, 2)
     del src, sink
     out["note"] = ("MFMA: 512 workgroups x 4 waves (two waves per SIMD), eight independent 32x32 "
                    "accumulator tiles per wave; copy: 1 GiB, read + write bytes counted; L2->LDS: "
-                   "32 KiB windows re-read from L2 with loads that write into LDS")
+                   "workgroups of 4 waves streaming 96 KiB windows that hit the L2 but not the "
+                   "32 KiB L1, with loads that write into LDS or through registers")
     return out
 
 

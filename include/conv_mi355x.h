@@ -229,19 +229,23 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
  *   sink: device, blocks * 256 floats, written once (keeps the loop alive).
  * conv_ceiling_copy: dst[0, bytes) = src[0, bytes), 16 bytes per lane; device pointers,
  *   16-byte aligned, bytes a multiple of 16.  HBM traffic = 2 * bytes.
- * conv_ceiling_l2_to_lds: `blocks` workgroups of 4 waves, each streaming its own 32 KiB
- *   window of src (window index = workgroup index modulo src_bytes / 32 KiB) into LDS
- *   `iters` times with 16-byte loads that write straight into LDS: the staging pattern of
- *   the forward kernel, served from L2 after the first pass.  Bytes moved =
- *   blocks * iters * 32 KiB.  src: device, 16-byte aligned, 32 KiB <= src_bytes < 4 GiB;
- *   sink as above.
+ * conv_ceiling_l2_to_lds: `blocks` workgroups of 4 waves, each streaming its own 96 KiB
+ *   window of src (window index = workgroup index modulo src_bytes / 96 KiB) into LDS,
+ *   16 KiB per step, `iters` steps, round and round: larger than a CU's vector L1, so after
+ *   the first pass the loads are served by the XCD's L2 as long as the windows of the
+ *   workgroups sharing an XCD fit it (src_bytes = 24 MiB: 32 windows of 96 KiB per XCD).
+ *   through_registers == 0: 16-byte loads that write straight into LDS (the staging pattern of
+ *   the forward kernel); != 0: 16-byte loads into registers followed by LDS writes.
+ *   Bytes moved = blocks * iters * 16 KiB.  src: device, 16-byte aligned,
+ *   96 KiB <= src_bytes < 4 GiB; sink as above.
  * Errors: CONV_EINVAL for a NULL or misaligned pointer or a count < 1, CONV_EUNSUPPORTED
  * beyond the stated sizes, CONV_ELAUNCH if the runtime refuses the launch. */
 conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink,
                                 void *stream);
 conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *stream);
 conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks,
-                                     int32_t iters, float *sink, void *stream);
+                                     int32_t iters, int32_t through_registers, float *sink,
+                                     void *stream);
 
 #ifdef __cplusplus
 }

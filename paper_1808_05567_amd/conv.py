@@ -89,7 +89,8 @@ def load():
     lib.conv_describe.argtypes = [vp, ctypes.c_int32, ctypes.c_char_p, ctypes.c_size_t]
     lib.conv_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.conv_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
-    lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           vp, vp]
     for name in EXPORTS:
         if name != "conv_status_str":
             getattr(lib, name).restype = ctypes.c_int
@@ -222,8 +223,9 @@ def conv_ceiling_copy(dst, src, nbytes, stream=None):
     _check(load().conv_ceiling_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "conv_ceiling_copy")
 
 
-def conv_ceiling_l2_to_lds(src, src_bytes, blocks, iters, sink, stream=None):
-    _check(load().conv_ceiling_l2_to_lds(_ptr(src), src_bytes, blocks, iters, _ptr(sink),
+def conv_ceiling_l2_to_lds(src, src_bytes, blocks, iters, sink, through_registers=False, stream=None):
+    _check(load().conv_ceiling_l2_to_lds(_ptr(src), src_bytes, blocks, iters,
+                                         1 if through_registers else 0, _ptr(sink),
                                          _stream(stream)), "conv_ceiling_l2_to_lds")
 
 

@@ -2,6 +2,7 @@
 // once at conv_create, the analogue of the dryrun phase of Section II-H),
 // and the entry points that only enqueue kernels.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -125,7 +126,8 @@ int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
 // dynamic LDS at most `lds_cap` bytes.  Returns ok=false if nothing fits.
 IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap, int nb = 2)
+                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap, int nb = 2,
+                    int npl_want = 0)
 {
     IgemmPlan pl;
     const int V = vlen_of(dtype);
@@ -140,7 +142,14 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
         npl = (Cb % 4 == 0) ? 4 : 1;
     else
         npl = (Cb % 2 == 0) ? 2 : 1;
+    if (npl_want > 0) {
+        if (Cb % npl_want != 0) return pl;
+        npl = npl_want;
+    }
+    // (eight waves: two groups of four, each staging its half of a step's planes)
+    if (wk * wm == 8 && npl % 2 != 0) return pl;
 
+    // (NT: threads of one staging group -- the input tile's chunks are dealt per group)
     const int TK = wk * fk * 32, TM = wm * fm * 32, NT = 256;
     const int nent = ((R * S * npl + 1) / 2) * 2;
 
@@ -193,7 +202,30 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     a.inv_P = 1.0f / (float)P; a.inv_Hs = 1.0f / (float)Hs;
     a.inv_LW = 1.0f / (float)LW; a.inv_TQ = 1.0f / (float)TQ;
     a.total = a.n_mt * a.n_qt * a.n_kt;
-    a.per_xcd = ceil_div(a.total, 8);
+    {
+        // Tiles over the XCDs (see the kernel): bytes from beyond the L2s are about
+        // gk x input + (8/gk) x weights, provided an XCD's share of the weights (1/gk of
+        // them) leaves room in its 4 MB L2 for the input tiles in flight.
+        const double in_b = (double)N * Cb * (sampled ? (double)P * Q : (double)H * W) * 16.0;
+        const double wt_b = (double)Cb * R * S * Kp * 16.0;
+        int best_gk = 1;
+        double best = 0;
+        for (int gk = 1; gk <= 8; gk *= 2) {
+            if (gk > a.n_kt) break;
+            if (a.n_kt % gk != 0 && gk > 1) continue;
+            double cost = gk * in_b + (8.0 / gk) * wt_b;
+            if (wt_b / gk > 2.0e6) cost += 8.0 * in_b;  // the weights would not stay resident
+            if (gk == 1 || cost < best) { best = cost; best_gk = gk; }
+        }
+        if (const char *env = getenv("CONVMI_IGEMM_GK")) {
+            const int g = atoi(env);
+            if ((g == 1 || g == 2 || g == 4 || g == 8) && g <= a.n_kt && a.n_kt % g == 0) best_gk = g;
+        }
+        a.gk = best_gk;
+        a.kt_per = ceil_div(a.n_kt, a.gk);
+        a.mq_per = ceil_div(a.n_mt * a.n_qt, 8 / a.gk);
+        a.per_xcd = a.kt_per * a.mq_per;
+    }
     a.n_stage = ceil_div(Cb, npl);
     a.st_per = a.n_stage;
     pl.v = IgemmVariant{dtype, wk, wm, fk, fm, npl, R, S, ppt, nb};
@@ -262,6 +294,35 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
                 best_cost = cost;
             }
         }
+    // Tuning aid: CONVMI_IGEMM_CAND="wk,wm,fk,fm,nb,npl" asks for one kernel variant wherever it
+    // exists and fits (npl 0: the default planes per step); unset in normal use.
+    if (const char *env = getenv("CONVMI_IGEMM_CAND")) {
+        int wk = 0, wm = 0, fk = 0, fm = 0, nb = 2, npl = 0;
+        if (sscanf(env, "%d,%d,%d,%d,%d,%d", &wk, &wm, &fk, &fm, &nb, &npl) >= 4 && wk > 0 && wm > 0 &&
+            fk > 0 && fm > 0 && (wk * wm == 4 || wk * wm == 8) && nb >= 2 && nb <= 4) {
+            IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
+                                    ostr, oy0, ox0, zero_fill, wk, wm, fk, fm, (size_t)kMaxLds, nb, npl);
+            if (c.ok) return c;
+        }
+    }
+    // bf16, eight waves (two per SIMD inside one workgroup, one workgroup per CU): a 256 x 256
+    // tile for 1x1 filters (four MFMA rounds per step), 128 x 512 for 3x3.  One staged tile
+    // feeds twice the MFMAs of two four-wave workgroups, which is what layers bound by the
+    // rate at which a CU pulls tiles in from memory gain from (measured at N = 256: 5 - 12 %
+    // on the 1x1 layers with at least 256 output rows and 128 input channels, 2 - 6 % on the
+    // 28 x 28 and 14 x 14 3x3 layers).  Not for results narrower than the tile, and not where
+    // the tiles would not fill the chip (there the four-wave tiles, or a split reduction, do).
+    if (dtype == CONV_BF16 && best.ok) {
+        IgemmPlan c;
+        if (R * S == 1 && Kp >= 256 && Cb % 8 == 0)
+            c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr, oy0,
+                          ox0, zero_fill, 4, 2, 2, 4, (size_t)kMaxLds, 2, 8);
+        else if (R == 3 && S == 3 && stride == 1 && Kp >= 128 && Cb % 2 == 0)
+            c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr, oy0,
+                          ox0, zero_fill, 2, 4, 2, 4, (size_t)kMaxLds, 2, 2);
+        if (c.ok && c.a.total >= 150 && igemm_waste(c, N, P, Q, Kp) <= 1.1 * igemm_waste(best, N, P, Q, Kp))
+            return c;
+    }
     // bf16 1x1: a reduction step is two MFMA rounds, far shorter than a trip to memory; a
     // third buffer keeps the loads two steps ahead where it fits the same LDS budget
     if (dtype == CONV_BF16 && R * S == 1 && best.ok && best.a.n_stage >= 3) {
@@ -1535,9 +1596,9 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         if (!p->ok) return CONV_EUNSUPPORTED;
         snprintf(buf, buflen,
                  "igemm dt=%d waves=%dx%d frags=%dx%d npl=%d RS=%dx%d ppt=%d TR=%d TQ=%d tiles=%d "
-                 "(m=%d q=%d k=%d) grid=%d lds=%zu stages=%d ksplit=%d launches=%d",
+                 "(m=%d q=%d k=%d) xcd_kgroups=%d grid=%d lds=%zu stages=%d ksplit=%d launches=%d",
                  p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.r, p->v.s, p->v.ppt,
-                 p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->grid, p->lds,
+                 p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->a.gk, p->grid, p->lds,
                  p->a.n_stage, p->a.ksplit, pass == 0 ? 1 : h->n_bwd);
         return CONV_OK;
     }

@@ -61,9 +61,15 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, cons
 }
 
 // The staging pattern of the implicit-GEMM kernel with nothing behind it: every workgroup
-// streams its own 32 KB window of `src` (small enough to stay in the L2 of its XCD) into a
-// ring of two LDS buffers with 16-byte loads that write straight into LDS, `iters` times.
-constexpr int kWindow = 32 * 1024;
+// streams its own 96 KiB window of `src` into a ring of two 16 KiB LDS buffers, 16 KiB per
+// step, `iters` steps, going round the window.  A window is larger than a CU's 32 KiB vector
+// L1, and the windows that the workgroups of one XCD touch (at most 32 distinct ones) fit its
+// 4 MiB L2: after the first pass every load is an L2 hit that misses the L1.
+//   DIRECT: 16-byte loads that write straight into LDS (what the convolution kernels use);
+//   else: 16-byte loads into registers, then 16-byte LDS writes.
+constexpr int kStep = 16 * 1024;
+constexpr int kWindow = 6 * kStep;
+template <bool DIRECT>
 __global__ __launch_bounds__(256) void l2_to_lds_kernel(const void *src, size_t src_bytes, float *sink,
                                                         int iters)
 {
@@ -73,21 +79,39 @@ __global__ __launch_bounds__(256) void l2_to_lds_kernel(const void *src, size_t 
     const size_t windows = src_bytes / kWindow;
     const size_t base = ((size_t)blockIdx.x % windows) * kWindow;
     const rsrc_t r = make_rsrc(src, base, base + kWindow);
-    // 2048 chunks of 16 bytes per window: 8 wave-level loads per wave
+    // 1024 chunks of 16 bytes per step: 4 wave-level loads per wave
+    int sub = 0;
     for (int it = 0; it < iters; ++it) {
-        unsigned char *buf = lds + (it & 1) * kWindow;
+        unsigned char *buf = lds + (it & 1) * kStep;
+        const unsigned soff = (unsigned)sub * (unsigned)kStep;
+        if constexpr (DIRECT) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int chunk = (i * 4 + wave) * 64;
-            load_to_lds_16(r, (unsigned)(chunk + lane) * 16u, 0u, buf + chunk * 16);
+            for (int i = 0; i < 4; ++i) {
+                const int chunk = (i * 4 + wave) * 64;
+                load_to_lds_16(r, (unsigned)(chunk + lane) * 16u, soff, buf + chunk * 16);
+            }
+            // (the previous step's loads have landed; this step's four stay in flight)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+        } else {
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int chunk = (i * 4 + wave) * 64;
+                v[i] = __builtin_amdgcn_raw_buffer_load_b128(r, (unsigned)(chunk + lane) * 16u, soff, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int chunk = (i * 4 + wave) * 64;
+                *reinterpret_cast<u32x4 *>(buf + (chunk + lane) * 16) = v[i];
+            }
         }
-        // (at most one window's loads in flight behind the one being waited for)
-        if (it > 0) __builtin_amdgcn_s_waitcnt(0x0F78 | 8);  // vmcnt(8): the previous window landed
+        sub = sub == 5 ? 0 : sub + 1;
     }
     wait_all_memory();
     __syncthreads();
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] =
-        reinterpret_cast<const float *>(lds)[(threadIdx.x * 4 + blockIdx.x) % (2 * kWindow / 4)];
+        reinterpret_cast<const float *>(lds)[(threadIdx.x * 4 + blockIdx.x) % (2 * kStep / 4)];
 }
 
 }  // namespace
@@ -121,16 +145,18 @@ conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *
 }
 
 conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks, int32_t iters,
-                                     float *sink, void *stream)
+                                     int32_t through_registers, float *sink, void *stream)
 {
     if (!src || !sink || src_bytes < (size_t)kWindow || blocks < 1 || iters < 1 || ((uintptr_t)src & 15))
         return CONV_EINVAL;
     if (src_bytes >= ((size_t)1 << 32)) return CONV_EUNSUPPORTED;
-    const size_t lds_bytes = 2 * kWindow;
-    if (ensure_dynamic_lds(reinterpret_cast<const void *>(l2_to_lds_kernel), lds_bytes) != hipSuccess)
-        return CONV_ELAUNCH;
-    hipLaunchKernelGGL(l2_to_lds_kernel, dim3(blocks), dim3(256), lds_bytes, (hipStream_t)stream, src,
-                       src_bytes, sink, iters);
+    const size_t lds_bytes = 2 * kStep;
+    if (through_registers)
+        hipLaunchKernelGGL(l2_to_lds_kernel<false>, dim3(blocks), dim3(256), lds_bytes, (hipStream_t)stream,
+                           src, src_bytes, sink, iters);
+    else
+        hipLaunchKernelGGL(l2_to_lds_kernel<true>, dim3(blocks), dim3(256), lds_bytes, (hipStream_t)stream,
+                           src, src_bytes, sink, iters);
     return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }
 

@@ -51,7 +51,10 @@ struct IgemmArgs {
     // 1.0f / P, Hs, LW, TQ for the kernel's exact small divisions (see fast_div)
     float inv_P, inv_Hs, inv_LW, inv_TQ;
     int total;     // workgroups doing work
-    int per_xcd;   // ceil(total / 8)
+    int per_xcd;   // workgroups per XCD (the grid is 8 * per_xcd)
+    // Tiles over the 8 XCDs: gk channel groups of kt_per channel tiles x 8/gk pixel groups
+    // of mq_per pixel tiles (per_xcd = kt_per * mq_per); unused when the reduction is split
+    int gk, kt_per, mq_per;
     int n_stage;   // ceil(Cb / planes per stage)
     // Reduction split (few tiles, long reduction): workgroup lin covers tile
     // lin % total and reduction steps [sp*st_per, (sp+1)*st_per), sp = lin / total,

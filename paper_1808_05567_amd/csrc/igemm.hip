@@ -79,6 +79,17 @@ static IgemmEntry g_igemm[] = {
     // bf16 1x1: a step is only two MFMA rounds, so the loads run two steps ahead
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),
+    // bf16, eight waves (two per SIMD inside one workgroup, 128 accumulator registers each)
+    // 1x1: 256 x 256 and 128 x 512 tiles, two or four MFMA rounds per step
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 4, 2, 4, 1, 1, 1, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 2),
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 4, 1, 1, 2, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 8, 1, 1, 2, 2),
+    // 3x3: 128 x 512 tiles
+    IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 3),
+    IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 4),
 };
 
 static IgemmEntry *find_in(IgemmEntry *tab, int n, const IgemmVariant &v)

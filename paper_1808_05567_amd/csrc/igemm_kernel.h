@@ -92,11 +92,19 @@ struct Elem<CONV_BF16> {
 
 // NB: LDS buffers of the staging ring (2 = double buffering; more = the loads run further ahead)
 template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT, int NB = 2>
-__global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128) ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
     constexpr int V = E_::V;
     constexpr int NT = WK * WM * 64;
+    // Four or eight waves.  Eight waves are two groups of four for the staging of the input
+    // tile: each group brings in its own half of a step's channel planes, with the chunk
+    // bookkeeping of a four-wave workgroup.  (Two waves per SIMD inside ONE workgroup share
+    // one staged tile: half the bytes pulled into LDS per flop of two four-wave workgroups.)
+    static_assert(NT == 256 || NT == 512, "four or eight waves");
+    constexpr int NG = NT / 256;
+    static_assert(NPL % NG == 0, "every wave group stages whole planes");
+    constexpr int NPLG = NPL / NG;  // planes a wave group stages per step
     constexpr int TK = WK * FK * 32;
     constexpr int NTAPS = R * S;
     constexpr int NENT = ((NTAPS * NPL + 1) / 2) * 2;  // reduction entries per step, even
@@ -119,17 +127,33 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     const int wave_k = wave % WK;
     const int wave_m = wave / WK;
 
-    // Workgroup -> tile.  Hardware deals consecutive workgroup ids round-robin
-    // over the 8 XCDs; give every XCD a contiguous run of tiles.
+    // Workgroup -> tile.  Hardware deals consecutive workgroup ids round-robin over the 8
+    // XCDs, each with an L2 of its own.  The tiles are dealt to the XCDs as a grid of gk
+    // channel groups x 8/gk pixel groups: an XCD works through its pixel tiles one after the
+    // other, all of its channel tiles of a pixel tile side by side (the staged input tile is
+    // fetched from beyond the L2 once per XCD that needs it), while its share of the weights,
+    // 1/gk of them, stays resident in its L2 for the whole launch.  The planner picks gk so
+    // that the bytes fetched from beyond the L2s, gk x input + (8/gk) x weights, are least.
     const int bid = blockIdx.x;
-    const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
-    if (lin >= a.total * a.ksplit) return;
-    const int sp = lin / a.total;  // reduction split this workgroup serves
-    const int tile = lin - sp * a.total;
+    int sp = 0, kt, rest;
+    if (a.ksplit > 1) {
+        // reduction split (few tiles): copy sp of tile lin % total, tiles in plain order
+        const int lin = (bid & 7) * a.per_xcd + (bid >> 3);
+        if (lin >= a.total * a.ksplit) return;
+        sp = lin / a.total;
+        const int tile = lin - sp * a.total;
+        kt = tile % a.n_kt;
+        rest = tile / a.n_kt;
+    } else {
+        const int x = bid & 7, j = bid >> 3;
+        const int kg = x % a.gk, mg = x / a.gk;
+        const int mql = j / a.kt_per;
+        kt = kg * a.kt_per + (j - mql * a.kt_per);
+        rest = mg * a.mq_per + mql;
+        if (kt >= a.n_kt || mql >= a.mq_per || rest >= a.n_mt * a.n_qt) return;
+    }
     const int sbeg = sp * a.st_per;                  // its first reduction step ...
     const int nst = min(a.n_stage - sbeg, a.st_per);  // ... and how many (at least one)
-    const int kt = tile % a.n_kt;
-    const int rest = tile / a.n_kt;
     const int qt = rest % a.n_qt;
     const int mt = rest / a.n_qt;
     const int k0 = kt * TK;
@@ -154,11 +178,13 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     // surplus loads repeat the last chunk group (same bytes to the same place),
     // which keeps the staging code free of branches.
     const int wave_chunk = wave * 64;
+    const int grp = wave >> 2;               // staging group of this wave
+    const int grp_chunk = (wave & 3) * 64;   // its first chunk within the group's share
     // ---- per-thread source byte offsets of the staged input pixels (plane 0)
     unsigned g_off[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
-        const int p = min(i * NT + wave_chunk, a.PLS - 64) + lane;
+        const int p = min(i * 256 + grp_chunk, a.PLS - 64) + lane;
         unsigned off = kOutOfRange;
         if (p < a.LRW) {
             const int row = fast_div(p, inv_LW);
@@ -202,17 +228,18 @@ __global__ __launch_bounds__(WK *WM * 64, (FK * FM * 16 <= 128 ? 2 : 1)) void ig
     const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
     const rsrc_t rsrc_wt = make_rsrc(a.wt, 0, wt_bytes);
     // Load number l of a step: the input loads (plane-major) come first, then the weights.
-    constexpr int NLOADS = NPL * PPT + WPT;
+    constexpr int NLOADS = NPLG * PPT + WPT;
     auto fetch_one = [&](int st, int l) {
         const int cb0 = (sbeg + st) * NPL;
         unsigned char *wb = lds + (st % NB) * bufbytes;
         unsigned char *ib = wb + WBYTES;
-        if (l < NPL * PPT) {
-            const int pl = l / PPT, i = l - pl * PPT;
+        if (l < NPLG * PPT) {
+            const int j = l / PPT, i = l - j * PPT;
+            const int pl = grp * NPLG + j;
             load_to_lds_16(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
-                           ib + (pl * a.PLS + min(i * NT + wave_chunk, a.PLS - 64)) * 16);
+                           ib + (pl * a.PLS + min(i * 256 + grp_chunk, a.PLS - 64)) * 16);
         } else {
-            const int i = l - NPL * PPT;
+            const int i = l - NPLG * PPT;
             load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
                            wb + min(i * NT + wave_chunk, WCH - 64) * 16);
         }

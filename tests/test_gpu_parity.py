@@ -43,6 +43,11 @@ SMALL = [
     (3, 32, 32, 11, 15, 3, 3, 1, 1),
     (1, 8, 16, 5, 147, 3, 3, 1, 1),       # ... in strips of 49 columns
     (3, 40, 72, 10, 13, 7, 7, 2, 3),      # 7x7 stride 2 over many channels (fp32 forward: direct kernel)
+    # enough 256 x 256 / 128 x 512 tiles for the bf16 eight-wave variants (ragged last pixel tile)
+    (25, 128, 512, 28, 28, 1, 1, 1, 0),   # 1x1 forward: 2 channel tiles x 78 pixel tiles, two steps
+    (32, 512, 128, 56, 56, 1, 1, 2, 0),   # 1x1 stride 2 backward: scatter with zero fill from eight waves
+    (50, 32, 256, 28, 28, 3, 3, 1, 1),    # 3x3 forward: two wave groups staging one halo tile
+    (52, 256, 32, 27, 29, 3, 3, 1, 1),    # 3x3 backward, odd extents
 ]
 
 
