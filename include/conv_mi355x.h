@@ -61,7 +61,9 @@ typedef enum {
     CONV_EUNSUPPORTED = 2, /* valid problem beyond the library's size limits   */
     CONV_EWORKSPACE = 3,   /* workspace required but ws == NULL, or (the _ws
                               entry points) smaller than the pass needs        */
-    CONV_ELAUNCH = 4       /* the HIP runtime refused a launch                 */
+    CONV_ELAUNCH = 4,      /* the HIP runtime refused a launch                 */
+    CONV_ESCRATCH = 5      /* conv_bwd_data_noalloc: the pass needs more scratch
+                              than the library's static device buffer holds    */
 } conv_status_t;
 
 /* Problem statement (Section II notation).  One stride and one pad for both
@@ -183,6 +185,27 @@ conv_status_t conv_fwd_fused(conv_handle_t h, const void *in, const void *wt, vo
  * tap-flipped weights of the duality of Section II-I). */
 conv_status_t conv_bwd_data(conv_handle_t h, const void *dout, const void *wt, void *din,
                             void *ws, void *stream);
+
+/* conv_bwd_data for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, kernels and results as conv_bwd_data, without `ws`: the
+ * scratch (the transposed, tap-flipped weights) lives in a static device array of
+ * conv_noalloc_scratch_bytes() = 16 MiB that the library's code object brings along
+ * (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates nothing and frees nothing.
+ *   - A plan whose backward pass needs more scratch returns CONV_ESCRATCH before anything
+ *     is launched (all layers of Table I fit: at most 9.4 MB, layer 18 in fp32).
+ *   - The array keeps the previous call's contents; nothing has to start at zero, because
+ *     the weight transform writes every byte the convolution kernel then reads.
+ *   - All calls on one GPU share the one array: calls that may overlap on a GPU (different
+ *     streams, different host threads) race on it.  Serialise them, or use conv_bwd_data
+ *     with a workspace per stream.
+ *   - The array's address is looked up on the first call on each device (the device that
+ *     is current at the call); CONV_ELAUNCH if the runtime cannot provide it. */
+conv_status_t conv_bwd_data_noalloc(conv_handle_t h, const void *dout, const void *wt, void *din,
+                                    void *stream);
+/* Size of that static scratch array in bytes. */
+size_t conv_noalloc_scratch_bytes(void);
 
 /* Algorithm 8 with padding:  dwt[k,c,r,s] = sum_{n,oj,oi} in[n,c,ij,ii] * dout[n,k,oj,oi].
  * in: blocked I; dout: blocked dO; dwt: blocked dW, fp32, fully overwritten.

@@ -16,12 +16,13 @@ CONV_F32 = 0
 CONV_BF16 = 1
 PASS_FWD, PASS_BWD_DATA, PASS_UPD = 0, 1, 2
 
-CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH = range(5)
+CONV_OK, CONV_EINVAL, CONV_EUNSUPPORTED, CONV_EWORKSPACE, CONV_ELAUNCH, CONV_ESCRATCH = range(6)
 
 EXPORTS = (
     "conv_create", "conv_create_rect", "conv_create_chunked", "conv_destroy", "conv_query", "conv_status_str",
     "conv_fwd", "conv_fwd_fused", "conv_fwd_fused_norm", "conv_bwd_data", "conv_upd",
     "conv_fwd_ws", "conv_bwd_data_ws", "conv_upd_ws",
+    "conv_bwd_data_noalloc", "conv_noalloc_scratch_bytes",
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
@@ -91,8 +92,11 @@ def load():
     lib.conv_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            vp, vp]
+    lib.conv_bwd_data_noalloc.argtypes = [vp, vp, vp, vp, vp]
+    lib.conv_noalloc_scratch_bytes.argtypes = []
+    lib.conv_noalloc_scratch_bytes.restype = ctypes.c_size_t
     for name in EXPORTS:
-        if name != "conv_status_str":
+        if name not in ("conv_status_str", "conv_noalloc_scratch_bytes"):
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -193,6 +197,11 @@ def conv_bwd_data(h, dout, wt, din, ws, stream=None):
 def conv_upd(h, inp, dout, dwt, ws, stream=None):
     _check(load().conv_upd(h, _ptr(inp), _ptr(dout), _ptr(dwt), _ptr(ws), _stream(stream)),
            "conv_upd")
+
+
+def conv_bwd_data_noalloc(h, dout, wt, din, stream=None):
+    _check(load().conv_bwd_data_noalloc(h, _ptr(dout), _ptr(wt), _ptr(din), _stream(stream)),
+           "conv_bwd_data_noalloc")
 
 
 def _ws_bytes(ws):

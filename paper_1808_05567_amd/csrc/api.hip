@@ -1063,6 +1063,7 @@ const char *conv_status_str(conv_status_t s)
         case CONV_EUNSUPPORTED: return "unsupported problem";
         case CONV_EWORKSPACE: return "workspace missing or too small";
         case CONV_ELAUNCH: return "kernel launch failed";
+        case CONV_ESCRATCH: return "problem needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -1513,6 +1514,48 @@ conv_status_t conv_upd_ws(conv_handle_t h, const void *in, const void *dout, voi
     if (ws_bytes < pass_ws_bytes(h, 2)) return CONV_EWORKSPACE;
     return conv_upd(h, in, dout, dwt, ws, stream);
 }
+
+// ---------------------------------------------------------------------------
+// Backward by data for callers that cannot allocate: the transformed weights live in a
+// file-scope device array instead of a caller-provided workspace.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+// Every GPU the library runs on holds its own copy of this array, at its own address, until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+// Device address of `scratch` on the current device (looked up once per device), or null.
+static void *scratch_of_current_device()
+{
+    static std::mutex mu;
+    static void *ptr_of[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        ptr_of[dev] = ptr;
+    }
+    return ptr_of[dev];
+}
+}  // namespace
+
+conv_status_t conv_bwd_data_noalloc(conv_handle_t h, const void *dout, const void *wt, void *din,
+                                    void *stream)
+{
+    if (!h || !dout || !wt || !din) return CONV_EINVAL;
+    if (pass_ws_bytes(h, 1) > kScratchBytes) return CONV_ESCRATCH;
+    void *ptr = scratch_of_current_device();
+    if (!ptr) return CONV_ELAUNCH;
+    return conv_bwd_data(h, dout, wt, din, ptr, stream);
+}
+
+size_t conv_noalloc_scratch_bytes(void) { return kScratchBytes; }
 
 #define CHECK_PACK_ARGS(h, a, b)                                  \
     if (!(h) || !(a) || !(b)) return CONV_EINVAL;                 \
