@@ -77,10 +77,10 @@ def parse():
 
 CALIB_BYTES = 1 << 30
 # committed counter summaries (HBM bytes per dispatch) by workload: (layers, dtype) -> file
-TRAFFIC_FILE = {("all", "f32"): "igemm_upd_f32_resnet50_all_n256_hbm_traffic.json",
-                ("all", "bf16"): "igemm_upd_bf16_resnet50_all_n256_hbm_traffic.json",
-                ("4,8,13,18", "f32"): "igemm_f32_resnet50_3x3_n256_hbm_traffic.json",
-                ("4,8,13,18", "bf16"): "igemm_bf16_resnet50_3x3_n256_hbm_traffic.json"}
+L1X1 = "2,3,5,6,7,9,10,11,12,14,15,16,17,19,20"
+TRAFFIC_FILE = {(ly, dt): "igemm_upd_%s_resnet50_%s_n256_hbm_traffic.json" % (dt, wl)
+                for wl, ly in (("all", "all"), ("3x3", "4,8,13,18"), ("1x1", L1X1))
+                for dt in ("f32", "bf16")}
 
 
 def summarize_pmc(fetch_csv, write_csv, out):
@@ -94,14 +94,17 @@ def summarize_pmc(fetch_csv, write_csv, out):
         for r in csv.DictReader(open(path)):
             if r["Counter_Name"] == counter:
                 acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
-        return {k: sum(v) / len(v) for k, v in acc.items()}, {k: len(v) for k, v in acc.items()}
+        return ({k: sum(v) / len(v) for k, v in acc.items()}, {k: len(v) for k, v in acc.items()},
+                {k: max(v) for k, v in acc.items()})
 
-    fetch, calls = load(fetch_csv, "FETCH_SIZE")
-    write, _ = load(write_csv, "WRITE_SIZE")
+    fetch, calls, fetch_max = load(fetch_csv, "FETCH_SIZE")
+    write, _, write_max = load(write_csv, "WRITE_SIZE")
+    # the calibration copy: the largest dispatch of torch's copy kernel (the same kernel also
+    # serves a few tiny copies, so its largest reading is taken, not its mean)
     copy = [k for k in fetch if "copy" in k.lower() or "elementwise" in k.lower()]
-    copy = max(copy, key=lambda k: fetch[k]) if copy else None
-    f_scale = (CALIB_BYTES / 1024.0) / fetch[copy] if copy else 1.0
-    w_scale = (CALIB_BYTES / 1024.0) / write[copy] if copy and write.get(copy) else 1.0
+    copy = max(copy, key=lambda k: fetch_max[k]) if copy else None
+    f_scale = (CALIB_BYTES / 1024.0) / fetch_max[copy] if copy else 1.0
+    w_scale = (CALIB_BYTES / 1024.0) / write_max[copy] if copy and write_max.get(copy) else 1.0
     rows = {}
     for k in fetch:
         rows[k] = {"calls": calls[k], "fetch_bytes": fetch[k] * 1024 * f_scale,
