@@ -215,6 +215,26 @@ def launch(L, which):
 PASSES = ("fwd", "bwd", "upd")
 
 
+def bound_calls(layers):
+    """The same three C-ABI calls per layer with their arguments marshalled once: a bf16 step
+    is about 5 ms of GPU work in some 120 kernel launches, so per-call Python work in the timed
+    loop (pointer look-ups, stream queries) must stay well below that."""
+    import ctypes
+    import torch
+    from paper_1808_05567_amd import conv
+    lib = conv.load()
+    vp = ctypes.c_void_p
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    calls = []
+    for l, L in layers:
+        p = {k: vp(getattr(L, k).data_ptr()) for k in ("x_blk", "wt_blk", "out_blk", "dy_blk", "dx_blk",
+                                                       "dwt_blk", "ws")}
+        calls.append((l.id, "fwd", lib.conv_fwd, (L.h, p["x_blk"], p["wt_blk"], p["out_blk"], p["ws"], st)))
+        calls.append((l.id, "bwd", lib.conv_bwd_data, (L.h, p["dy_blk"], p["wt_blk"], p["dx_blk"], p["ws"], st)))
+        calls.append((l.id, "upd", lib.conv_upd, (L.h, p["x_blk"], p["dy_blk"], p["dwt_blk"], p["ws"], st)))
+    return calls
+
+
 def time_workload(layers, N, steps, warmup):
     """W untimed steps, then exactly K timed steps between two synchronisations; every launch
     sits between two events on the stream the kernels run on (torch's current stream is the
@@ -222,25 +242,33 @@ def time_workload(layers, N, steps, warmup):
     (layer id, pass)."""
     import torch
 
+    calls = bound_calls(layers)
+    # events are created (and recorded once, which is what allocates them) before the clock starts
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+           for _ in range(steps)]
+    for row in evs:
+        for a, b in row:
+            a.record()
+            b.record()
     for _ in range(warmup):
-        for _, L in layers:
-            for which in PASSES:
-                launch(L, which)
+        for _, _, fn, args in calls:
+            assert fn(*args) == 0
     torch.cuda.synchronize()
-    ev = {}
     t0 = time.perf_counter()
-    for _ in range(steps):
-        for l, L in layers:
-            for which in PASSES:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record()
-                launch(L, which)
-                b.record()
-                ev.setdefault((l.id, which), []).append((a, b))
+    for k in range(steps):
+        row = evs[k]
+        for i, (_, _, fn, args) in enumerate(calls):
+            a, b = row[i]
+            a.record()
+            rc = fn(*args)
+            b.record()
+            if rc != 0:
+                raise RuntimeError("conv call failed with status %d" % rc)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
+    per = {}
+    for i, (lid, which, _, _) in enumerate(calls):
+        per[(lid, which)] = sum(evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(steps)) / steps
     return wall, per
 
 

@@ -55,6 +55,9 @@ struct IgemmArgs {
     // Tiles over the 8 XCDs: gk channel groups of kt_per channel tiles x 8/gk pixel groups
     // of mq_per pixel tiles (per_xcd = kt_per * mq_per); unused when the reduction is split
     int gk, kt_per, mq_per;
+    // Channel tile kt of pixel tile mq starts its reduction at step
+    // (kt * rot_k + mq * rot_m) mod (its number of steps) and wraps round (0, 0: all start at 0)
+    int rot_k, rot_m;
     int n_stage;   // ceil(Cb / planes per stage)
     // Reduction split (few tiles, long reduction): workgroup lin covers tile
     // lin % total and reduction steps [sp*st_per, (sp+1)*st_per), sp = lin / total,

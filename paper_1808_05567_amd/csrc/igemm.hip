@@ -83,6 +83,8 @@ static IgemmEntry g_igemm[] = {
     // 1x1: 256 x 256 and 128 x 512 tiles, two or four MFMA rounds per step
     IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 4, 2, 4, 1, 1, 1, 3),
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 4),
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 5),
     IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 2),
     IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 4, 1, 1, 2, 3),

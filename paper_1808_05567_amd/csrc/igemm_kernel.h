@@ -156,6 +156,13 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
     const int nst = min(a.n_stage - sbeg, a.st_per);  // ... and how many (at least one)
     const int qt = rest % a.n_qt;
     const int mt = rest / a.n_qt;
+    // Workgroups that share a staged tile -- the channel tiles of one pixel tile share its input,
+    // the pixel tiles of one channel tile its weights -- run side by side.  If they all walked the
+    // reduction in the same order they would all ask for the same lines at the same moment and
+    // all wait for the one fetch from beyond the L2; started at different steps, one of them
+    // fetches a line and the others find it resident.  (The order of a sum changes with the
+    // tile, not from run to run.)
+    const int rot = (int)(((unsigned)kt * (unsigned)a.rot_k + (unsigned)rest * (unsigned)a.rot_m) % (unsigned)nst);
     const int k0 = kt * TK;
     const int q0 = qt * a.TQ;
     const int rho0 = mt * a.TR;
@@ -230,7 +237,10 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
     // Load number l of a step: the input loads (plane-major) come first, then the weights.
     constexpr int NLOADS = NPLG * PPT + WPT;
     auto fetch_one = [&](int st, int l) {
-        const int cb0 = (sbeg + st) * NPL;
+        // (the workgroup's reduction starts at step rot and wraps round: see IgemmArgs::rot_k)
+        int sr = st + rot;
+        if (sr >= nst) sr -= nst;
+        const int cb0 = (sbeg + sr) * NPL;
         unsigned char *wb = lds + (st % NB) * bufbytes;
         unsigned char *ib = wb + WBYTES;
         if (l < NPLG * PPT) {
