@@ -356,17 +356,27 @@ def measure_ceilings():
     s = timed(lambda: conv.conv_ceiling_copy(dst, src, CALIB_BYTES))
     out["hbm_copy_tbps"] = round(2 * CALIB_BYTES / s / 1e12, 2)
     del dst
-    for wgs in (1, 2, 4):
+    win = 96 * 1024
+    for wgs in (1, 2):
         for regs in (False, True):
             it, nb = 4000, 256 * wgs
-            s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 24 << 20, nb, it, sink, regs))
+            s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 256 * win, nb, it, sink, regs))
             out["l2_to_lds_tbps_%dwg_per_cu_%s" % (wgs, "via_registers" if regs else "lds_direct")] = round(
                 nb * it * 16384 / s / 1e12, 2)
+    # 1024 workgroups on 2048 windows: the 256 windows an XCD's workgroups touch (24 MiB) do not
+    # fit its 4 MiB L2, all of them (192 MiB) fit the 256 MiB last-level cache -- the rate at
+    # which tiles come in from beyond the L2
+    for regs in (False, True):
+        it, nb = 2000, 1024
+        s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 2048 * win, nb, it, sink, regs))
+        out["beyond_l2_to_lds_tbps_4wg_per_cu_%s" % ("via_registers" if regs else "lds_direct")] = round(
+            nb * it * 16384 / s / 1e12, 2)
     del src, sink
     out["note"] = ("MFMA: 512 workgroups x 4 waves (two waves per SIMD), eight independent 32x32 "
                    "accumulator tiles per wave; copy: 1 GiB, read + write bytes counted; L2->LDS: "
                    "workgroups of 4 waves streaming 96 KiB windows that hit the L2 but not the "
-                   "32 KiB L1, with loads that write into LDS or through registers")
+                   "32 KiB L1, with loads that write into LDS or through registers; beyond L2: "
+                   "the same with more windows per XCD than its L2 holds")
     return out
 
 

@@ -10,7 +10,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libconv_mi355x.so")
+# (CONVMI_LIB: another build of the same library, for tuning experiments)
+LIB_PATH = os.environ.get("CONVMI_LIB") or os.path.join(_HERE, "libconv_mi355x.so")
 
 CONV_F32 = 0
 CONV_BF16 = 1

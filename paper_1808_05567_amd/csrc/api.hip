@@ -265,9 +265,31 @@ double igemm_waste(const IgemmPlan &p, int N, int P, int Q, int Kp)
 // workgroups per CU overlap each other's barriers and staging) or all of it.
 // Preference: least wasted MFMA work, then two workgroups per CU, then the
 // wider channel tile (fewer re-reads of the input tile).
+IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
+                          int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
+                          int zero_fill);
+
 IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                      int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
                      int zero_fill)
+{
+    IgemmPlan p = plan_igemm_tile(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr,
+                                  oy0, ox0, zero_fill);
+    // One channel tile: every line of the input is staged by exactly one workgroup.  Loaded
+    // non-temporally it does not displace the weights in the L2 nor settle in the last-level
+    // cache on its way past (CONVMI_IGEMM_NT=0 keeps the default policy: a tuning aid).
+    const char *env = getenv("CONVMI_IGEMM_NT");
+    if (p.ok && p.a.n_kt == 1 && !(env && atoi(env) == 0)) {
+        IgemmVariant v = p.v;
+        v.nt = 1;
+        if (igemm_variant_exists(v)) p.v = v;
+    }
+    return p;
+}
+
+IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
+                          int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
+                          int zero_fill)
 {
     IgemmPlan best;
     double best_cost = 0;
@@ -1646,9 +1668,9 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
         if (pass == 1 && h->bwd_mode == 0) return CONV_EUNSUPPORTED;
         if (!p->ok) return CONV_EUNSUPPORTED;
         snprintf(buf, buflen,
-                 "igemm dt=%d waves=%dx%d frags=%dx%d npl=%d RS=%dx%d ppt=%d TR=%d TQ=%d tiles=%d "
+                 "igemm dt=%d waves=%dx%d frags=%dx%d npl=%d nt=%d RS=%dx%d ppt=%d TR=%d TQ=%d tiles=%d "
                  "(m=%d q=%d k=%d) xcd_kgroups=%d grid=%d lds=%zu stages=%d ksplit=%d launches=%d",
-                 p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.r, p->v.s, p->v.ppt,
+                 p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.nt, p->v.r, p->v.s, p->v.ppt,
                  p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->a.gk, p->grid, p->lds,
                  p->a.n_stage, p->a.ksplit, pass == 0 ? 1 : h->n_bwd);
         return CONV_OK;

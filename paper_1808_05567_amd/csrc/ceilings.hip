@@ -94,6 +94,9 @@ __global__ __launch_bounds__(256) void l2_to_lds_kernel(const void *src, size_t 
             __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
         } else {
             typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+            // (the window does not change, but every step must fetch it again: nothing moves
+            // across this point)
+            asm volatile("" ::: "memory");
             u32x4 v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

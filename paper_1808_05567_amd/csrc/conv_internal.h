@@ -80,6 +80,7 @@ struct IgemmVariant {
     int r, s;    // filter extent
     int ppt;     // staged input pixels per thread
     int nb = 2;  // LDS buffers of the staging ring
+    int nt = 0;  // 1: the input tile is loaded non-temporally (plans with one channel tile)
 };
 
 // Raise a kernel's dynamic-LDS limit to at least `bytes` (once per kernel and size; safe to
@@ -261,14 +262,22 @@ static __device__ __forceinline__ rsrc_t make_rsrc(const void *base, size_t skip
 }
 // 16-byte load from global memory straight into LDS: lane i of the wave writes
 // lds_wave_base + 16*i (the LDS base must be wave-uniform), zero if out of range.
+// POLICY: cache policy bits of the load (0: default; 2: non-temporal -- the line is the first
+// to leave the L2, for data that streams past once and must not push out what is re-read).
+template <int POLICY = 0>
 static __device__ __forceinline__ void load_to_lds_16(rsrc_t r, unsigned byte_off,
                                                       unsigned uniform_off,
                                                       unsigned char *lds_wave_base)
 {
     typedef __attribute__((address_space(3))) void *lds_vptr_t;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, uniform_off,
-                                             0, 0);
+                                             0, POLICY);
 }
+// Cache policy of the loads of the update kernels, which read both tensors exactly once:
+// non-temporal (the lines are not kept in the last-level cache and leave the L2 first).
+#ifndef CONVMI_UPD_POLICY
+#define CONVMI_UPD_POLICY 2
+#endif
 // Wait until every outstanding memory operation of this wave, staging loads included, is done.
 static __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 

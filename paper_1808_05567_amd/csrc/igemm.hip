@@ -92,6 +92,14 @@ static IgemmEntry g_igemm[] = {
     // 3x3: 128 x 512 tiles
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 3),
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 4),
+    // 1x1 with a single channel tile: the input streams past once, loaded non-temporally
+    IGEMM_ENTRY_NB_NT(CONV_F32, 4, 1, 1, 7, 4, 1, 1, 1, 2, 1),
+    IGEMM_ENTRY_NB_NT(CONV_F32, 2, 2, 1, 7, 4, 1, 1, 2, 2, 1),
+    IGEMM_ENTRY_NB_NT(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 2, 1),
+    IGEMM_ENTRY_NB_NT(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3, 1),
+    IGEMM_ENTRY_NB_NT(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 2, 1),
+    IGEMM_ENTRY_NB_NT(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3, 1),
+    IGEMM_ENTRY_NB_NT(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 2, 1),
 };
 
 static IgemmEntry *find_in(IgemmEntry *tab, int n, const IgemmVariant &v)
@@ -99,7 +107,7 @@ static IgemmEntry *find_in(IgemmEntry *tab, int n, const IgemmVariant &v)
     for (int i = 0; i < n; ++i) {
         const IgemmVariant &w = tab[i].v;
         if (w.dtype == v.dtype && w.wk == v.wk && w.wm == v.wm && w.fk == v.fk && w.fm == v.fm &&
-            w.npl == v.npl && w.r == v.r && w.s == v.s && w.ppt == v.ppt && w.nb == v.nb)
+            w.npl == v.npl && w.r == v.r && w.s == v.s && w.ppt == v.ppt && w.nb == v.nb && w.nt == v.nt)
             return &tab[i];
     }
     return nullptr;

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
                               ((size_t)(n * a.Cb + cb0 + gi) * a.H + ih) * a.W + iw;
 #pragma unroll
             for (int j = 0; j < NPI / GI; ++j)
-                vi[j] = (ok && cb0 + gi + GI * j < a.Cb) ? ip[(size_t)j * GI * HW] : zero4;
+                vi[j] = (ok && cb0 + gi + GI * j < a.Cb) ? __builtin_nontemporal_load(ip + (size_t)j * GI * HW) : zero4;
         }
         if (po < npxO_st) {
             const int trow = fast_div(po, inv_Qp);
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256, 2) void upd_f32_kernel(const UpdArgs a)
                               ((size_t)(n * a.Kb + kb0 + go) * a.P + oj) * a.Qpitch + a.q0 + col;
 #pragma unroll
             for (int j = 0; j < NPO / GO; ++j)
-                vo[j] = (ok && kb0 + go + GO * j < a.Kb) ? op[(size_t)j * GO * PQ] : zero4;
+                vo[j] = (ok && kb0 + go + GO * j < a.Kb) ? __builtin_nontemporal_load(op + (size_t)j * GO * PQ) : zero4;
         }
     };
     auto commit = [&]() {
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                     ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
                 }
                 ok = ok && (cb0 + pl) < a.Cb;
-                if (ok) v = ip[((size_t)(n * a.Cb + cb0 + pl) * a.H + ih) * a.W + iw];
+                if (ok) v = __builtin_nontemporal_load(ip + ((size_t)(n * a.Cb + cb0 + pl) * a.H + ih) * a.W + iw);
             }
             ireg[i] = v;
         }
@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256) void upd_bf16_kernel(const UpdArgs a)
                 if (trow < a.TR && rho < rho_end && (kb0 + pl) < a.Kb) {
                     const int n = rho / a.P;
                     const int oj = rho - n * a.P;
-                    v = op[((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Qpitch + a.q0 + col];
+                    v = __builtin_nontemporal_load(op + ((size_t)(n * a.Kb + kb0 + pl) * a.P + oj) * a.Qpitch + a.q0 + col);
                 }
             }
             oreg[i] = v;

@@ -157,11 +157,11 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         };
         // (channel blocks beyond the tensor are out of range as a whole: zeros)
         auto load_in = [&](int pl, int p0, unsigned off) {
-            load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+            load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
                            (unsigned)(cb0 + pl) * (unsigned)HW * 16u, ib + (pl * a.PLS_in + p0) * 16);
         };
         auto load_out = [&](int pl, int p0, unsigned off) {
-            load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+            load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                            (unsigned)(kb0 + pl) * (unsigned)PQ * 16u, ob + (pl * a.PLS_out + p0) * 16);
         };
         // Unit of staging work: one 64-position chunk x 8 planes (8 wave-level

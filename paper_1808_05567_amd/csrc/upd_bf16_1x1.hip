@@ -124,12 +124,12 @@ __global__ __launch_bounds__(512) void upd_bf16_1x1_kernel(const UpdArgs a)
         for (int j = 0; j < LI; ++j)
             si[SET][j] = __builtin_amdgcn_raw_buffer_load_b128(
                 rsrc_in, cb0 + wave + 8 * j < a.Cb ? off_in : kOutOfRange,
-                (unsigned)(cb0 + wave + 8 * j) * (unsigned)HW * 16u, 0);
+                (unsigned)(cb0 + wave + 8 * j) * (unsigned)HW * 16u, CONVMI_UPD_POLICY);
 #pragma unroll
         for (int j = 0; j < LO; ++j)
             so[SET][j] = __builtin_amdgcn_raw_buffer_load_b128(
                 rsrc_out, kb0 + wave + 8 * j < a.Kb ? off_out : kOutOfRange,
-                (unsigned)(kb0 + wave + 8 * j) * (unsigned)PQ * 16u, 0);
+                (unsigned)(kb0 + wave + 8 * j) * (unsigned)PQ * 16u, CONVMI_UPD_POLICY);
     };
     auto commit = [&](int buf, auto set_tag) {
         constexpr int SET = decltype(set_tag)::value;

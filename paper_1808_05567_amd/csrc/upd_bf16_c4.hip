@@ -128,7 +128,7 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
         unsigned off = kOutOfRange;
         for (int e = first; e < last; ++e) {
             if (e < nch_in) {
-                load_to_lds_16(rsrc_in, in_off(e * 64 + lane, lam0), 0u, ib + e * 64 * 16);
+                load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_in, in_off(e * 64 + lane, lam0), 0u, ib + e * 64 * 16);
             } else {
                 const int u = e - nch_in;
                 const int ch = u >> 3, pl = u & 7;
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
                     cur = ch;
                     off = out_off(ch * 64 + lane, rho0);
                 }
-                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                                (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
                                ob + (pl * a.PLS_out + ch * 64) * 16);
             }

@@ -122,11 +122,11 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
                 off = is_in ? in_off(ch * 64 + lane) : out_off(ch * 64 + lane);
             }
             if (is_in)
-                load_to_lds_16(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+                load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
                                (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
                                ib + (pl * a.PLS_in + ch * 64) * 16);
             else
-                load_to_lds_16(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
+                load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_out, kb0 + pl < a.Kb ? off : kOutOfRange,
                                (unsigned)(kb0 + pl) * (unsigned)PQ * 16u,
                                ob + (pl * a.PLS_out + ch * 64) * 16);
         }

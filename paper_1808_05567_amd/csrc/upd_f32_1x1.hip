@@ -113,13 +113,13 @@ __global__ __launch_bounds__(512) void upd_f32_1x1_kernel(const UpdArgs a)
         for (int j = 0; j < LA; ++j) {
             const bool ok = pa0 + my_plane + 16 * j < nplA;
             sa[j] = __builtin_amdgcn_raw_buffer_load_b128(
-                rsrcA, ok ? laneA : kOutOfRange, (unsigned)(pa0 + 2 * wave + 16 * j) * planeA, 0);
+                rsrcA, ok ? laneA : kOutOfRange, (unsigned)(pa0 + 2 * wave + 16 * j) * planeA, CONVMI_UPD_POLICY);
         }
 #pragma unroll
         for (int j = 0; j < LB; ++j) {
             const bool ok = pb0 + my_plane + 16 * j < nplB;
             sb[j] = __builtin_amdgcn_raw_buffer_load_b128(
-                rsrcB, ok ? laneB : kOutOfRange, (unsigned)(pb0 + 2 * wave + 16 * j) * planeB, 0);
+                rsrcB, ok ? laneB : kOutOfRange, (unsigned)(pb0 + 2 * wave + 16 * j) * planeB, CONVMI_UPD_POLICY);
         }
     };
     auto commit = [&](int buf) {

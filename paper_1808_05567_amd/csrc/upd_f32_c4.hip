@@ -139,7 +139,7 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int p = tid + 512 * i;
-            ri[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, in_off(p, lam0), 0u, 0);
+            ri[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, in_off(p, lam0), 0u, CONVMI_UPD_POLICY);
         }
 #pragma unroll
         for (int i = 0; i < NO; ++i) {
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
                 off += (unsigned)(kbb0 + blk) * (unsigned)PQ * 16u;
             else
                 off = kOutOfRange;
-            ro[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_out, off, 0u, 0);
+            ro[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_out, off, 0u, CONVMI_UPD_POLICY);
         }
     };
     auto commit_regs = [&](int buf) {
