@@ -166,6 +166,15 @@ def algorithmic_bytes(l, N, es, which):
     return i + o + w * (4 if which == "upd" else es)
 
 
+def written_bytes(l, N, es, which):
+    """The part of algorithmic_bytes that is the pass's result."""
+    if which == "fwd":
+        return N * l.K * l.P * l.Q * es
+    if which == "bwd":
+        return N * l.C * l.H * l.W * es
+    return l.K * l.C * l.R * l.S * 4
+
+
 def layer_class(l):
     """The three families of Table I the target names separately."""
     if l.R == 1 and l.S == 1:
@@ -346,7 +355,7 @@ def measure_ceilings():
 
     out = {}
     blocks, iters = 256 * 2, 20000      # two waves per SIMD on every CU
-    sink = torch.empty(256 * 8 * 256, dtype=torch.float32, device="cuda")
+    sink = torch.empty(256 * 32 * 256, dtype=torch.float32, device="cuda")
     for name, dt, k in (("mfma_f32_tflops", conv.CONV_F32, 2), ("mfma_bf16_tflops", conv.CONV_BF16, 16)):
         it = iters if dt == conv.CONV_BF16 else iters // 2
         s = timed(lambda: conv.conv_ceiling_mfma(dt, blocks, it, sink))
@@ -355,6 +364,10 @@ def measure_ceilings():
     dst = torch.empty_like(src)
     s = timed(lambda: conv.conv_ceiling_copy(dst, src, CALIB_BYTES))
     out["hbm_copy_tbps"] = round(2 * CALIB_BYTES / s / 1e12, 2)
+    s = timed(lambda: conv.conv_ceiling_read(src, CALIB_BYTES, sink))
+    out["hbm_read_tbps"] = round(CALIB_BYTES / s / 1e12, 2)
+    s = timed(lambda: conv.conv_ceiling_write(dst, CALIB_BYTES))
+    out["hbm_write_tbps"] = round(CALIB_BYTES / s / 1e12, 2)
     del dst
     win = 96 * 1024
     for wgs in (1, 2):
@@ -536,7 +549,8 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
     es = 2 if dtype_name == "bf16" else 4
     peak = MFMA_PEAK[dtype_name]
     m_peak = (ceilings or {}).get("mfma_%s_tflops" % dtype_name)
-    m_hbm = (ceilings or {}).get("hbm_copy_tbps")
+    m_rd = (ceilings or {}).get("hbm_read_tbps")
+    m_wr = (ceilings or {}).get("hbm_write_tbps")
     warm = {}
     for l, L in layers:
         for which in PASSES:
@@ -552,15 +566,19 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
             torch.cuda.synchronize()
             warm[(l.id, which)] = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
 
-    def row(l, which, ms, by, extra=None):
+    def row(l, which, ms, by, extra=None, wr=None):
         tf = l.flops(N) / (ms * 1e-3) / 1e12
         ceil = min(peak, l.flops(N) / by * HBM_PEAK)
         r = {"layer": l.id, "pass": which, "ms": round(ms, 4), "tflops": round(tf, 2),
              "pct_mfma_peak": round(100 * tf / peak, 1),
              "ceiling_tflops": round(ceil, 1), "pct_ceiling": round(100 * tf / ceil, 1),
              "alg_GBps": round(by / (ms * 1e-3) / 1e9, 1)}
-        if m_peak and m_hbm:
-            mc = min(m_peak, l.flops(N) / by * m_hbm)
+        if m_peak and m_rd and m_wr:
+            # (the measured ceiling: what is read at the measured read rate, what is written at
+            # the measured write rate, one after the other)
+            wr = written_bytes(l, N, es, which) if wr is None else wr
+            secs = (by - wr) / (m_rd * 1e12) + wr / (m_wr * 1e12)
+            mc = min(m_peak, l.flops(N) / secs / 1e12)
             r["measured_ceiling_tflops"] = round(mc, 1)
             r["pct_measured_ceiling"] = round(100 * tf / mc, 1)
         if extra:
@@ -589,7 +607,8 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
         torch.cuda.synchronize()
         ms = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
         rows.append(row(l, "fwd_fused", ms,
-                        algorithmic_bytes(l, N, es, "fwd") + N * l.K * l.P * l.Q * es))
+                        algorithmic_bytes(l, N, es, "fwd") + N * l.K * l.P * l.Q * es,
+                        wr=written_bytes(l, N, es, "fwd")))
     # layout conversion, timed on its own (the passes work on resident blocked tensors)
     for l, L in layers:
         nchw = torch.empty((N, l.C, l.H, l.W), dtype=L.tdtype, device="cuda")

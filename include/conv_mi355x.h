@@ -250,8 +250,12 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
  *   eight independent 32x32 MFMAs of the type (fp32: 32x32x2, bf16: 32x32x16) from
  *   registers.  Flops = blocks * 4 * iters * 8 * 2*32*32*k, k = 2 (fp32) or 16 (bf16).
  *   sink: device, blocks * 256 floats, written once (keeps the loop alive).
- * conv_ceiling_copy: dst[0, bytes) = src[0, bytes), 16 bytes per lane; device pointers,
- *   16-byte aligned, bytes a multiple of 16.  HBM traffic = 2 * bytes.
+ * conv_ceiling_copy: dst[0, bytes) = src[0, bytes), 16 bytes per lane, non-temporal loads
+ *   and stores (as the convolution kernels issue them for tensors that stream past once);
+ *   device pointers, 16-byte aligned, bytes a multiple of 16.  HBM traffic = 2 * bytes.
+ * conv_ceiling_read / conv_ceiling_write: the read half and the write half of that copy on
+ *   their own (read: sink receives 8192 * 256 words at most, device, at least that large;
+ *   write: dst is overwritten with a pattern).  HBM traffic = bytes.
  * conv_ceiling_l2_to_lds: `blocks` workgroups of 4 waves, each streaming its own 96 KiB
  *   window of src (window index = workgroup index modulo src_bytes / 96 KiB) into LDS,
  *   16 KiB per step, `iters` steps, round and round: larger than a CU's vector L1, so after
@@ -266,6 +270,8 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
 conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink,
                                 void *stream);
 conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *stream);
+conv_status_t conv_ceiling_read(const void *src, size_t bytes, float *sink, void *stream);
+conv_status_t conv_ceiling_write(void *dst, size_t bytes, void *stream);
 conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks,
                                      int32_t iters, int32_t through_registers, float *sink,
                                      void *stream);

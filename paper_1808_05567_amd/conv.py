@@ -27,7 +27,8 @@ EXPORTS = (
     "conv_pack_in", "conv_pack_out", "conv_pack_wt",
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
-    "conv_ceiling_mfma", "conv_ceiling_copy", "conv_ceiling_l2_to_lds",
+    "conv_ceiling_mfma", "conv_ceiling_copy", "conv_ceiling_read", "conv_ceiling_write",
+    "conv_ceiling_l2_to_lds",
 )
 
 
@@ -91,6 +92,8 @@ def load():
     lib.conv_describe.argtypes = [vp, ctypes.c_int32, ctypes.c_char_p, ctypes.c_size_t]
     lib.conv_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.conv_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.conv_ceiling_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.conv_ceiling_write.argtypes = [vp, ctypes.c_size_t, vp]
     lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            vp, vp]
     lib.conv_bwd_data_noalloc.argtypes = [vp, vp, vp, vp, vp]
@@ -231,6 +234,14 @@ def conv_ceiling_mfma(dtype, blocks, iters, sink, stream=None):
 
 def conv_ceiling_copy(dst, src, nbytes, stream=None):
     _check(load().conv_ceiling_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "conv_ceiling_copy")
+
+
+def conv_ceiling_read(src, nbytes, sink, stream=None):
+    _check(load().conv_ceiling_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "conv_ceiling_read")
+
+
+def conv_ceiling_write(dst, nbytes, stream=None):
+    _check(load().conv_ceiling_write(_ptr(dst), nbytes, _stream(stream)), "conv_ceiling_write")
 
 
 def conv_ceiling_l2_to_lds(src, src_bytes, blocks, iters, sink, through_registers=False, stream=None):

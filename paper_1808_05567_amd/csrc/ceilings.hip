@@ -52,12 +52,33 @@ __global__ __launch_bounds__(256) void mfma_issue_kernel(float *sink, int iters)
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// dst[i] = src[i], 16 bytes per lane and step, grid-stride.
-__global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
-                                                   size_t n16)
+// dst[i] = src[i], 16 bytes per lane and step, grid-stride; loads and stores non-temporal, as
+// the convolution kernels issue them for tensors that stream past once.
+typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void copy_kernel(copy_u32x4 *__restrict__ dst,
+                                                   const copy_u32x4 *__restrict__ src, size_t n16)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
-        dst[i] = src[i];
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// Read-only and write-only streams of the same form (what a pass that mostly reads, or mostly
+// writes, can reach; a copy pays for the turn-arounds between the two).
+__global__ __launch_bounds__(256) void read_kernel(const copy_u32x4 *__restrict__ src, size_t n16,
+                                                   unsigned *sink)
+{
+    copy_u32x4 x = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        const copy_u32x4 v = __builtin_nontemporal_load(src + i);
+        x[0] ^= v[0]; x[1] ^= v[1]; x[2] ^= v[2]; x[3] ^= v[3];
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = x[0] ^ x[1] ^ x[2] ^ x[3];
+}
+__global__ __launch_bounds__(256) void write_kernel(copy_u32x4 *__restrict__ dst, size_t n16)
+{
+    const copy_u32x4 v = {1u, 2u, 3u, (unsigned)threadIdx.x};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        __builtin_nontemporal_store(v, dst + i);
 }
 
 // The staging pattern of the implicit-GEMM kernel with nothing behind it: every workgroup
@@ -142,8 +163,28 @@ conv_status_t conv_ceiling_copy(void *dst, const void *src, size_t bytes, void *
         return CONV_EINVAL;
     const size_t n16 = bytes / 16;
     const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
-    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, static_cast<uint4 *>(dst),
-                       static_cast<const uint4 *>(src), n16);
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<copy_u32x4 *>(dst), static_cast<const copy_u32x4 *>(src), n16);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_read(const void *src, size_t bytes, float *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15)) return CONV_EINVAL;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<const copy_u32x4 *>(src), n16, reinterpret_cast<unsigned *>(sink));
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_write(void *dst, size_t bytes, void *stream)
+{
+    if (!dst || bytes < 16 || (bytes & 15) || ((uintptr_t)dst & 15)) return CONV_EINVAL;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(write_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<copy_u32x4 *>(dst), n16);
     return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }
 
