@@ -126,10 +126,13 @@ int max_band_rows(int N, int P, int TR, int Hs, int stride, int R)
 // dynamic LDS at most `lds_cap` bytes.  Returns ok=false if nothing fits.
 IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                     int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                    int zero_fill, int wk, int wm, int fk, int fm, size_t lds_cap, int nb = 2,
-                    int npl_want = 0)
+                    int zero_fill, const IgemmGeo &geo, int wk, int wm, int fk, int fm, size_t lds_cap,
+                    int nb = 2, int npl_want = 0)
 {
     IgemmPlan pl;
+    // (columns of the result `cstride` input pixels apart, and `ostr_x` output pixels apart)
+    const int cstride = geo.cstride > 0 ? geo.cstride : stride;
+    const int ostr_x = geo.ostr_x > 0 ? geo.ostr_x : ostr;
     const int V = vlen_of(dtype);
     // (1x1, no padding: only the pixels that are read are staged -- valid where every output
     // pixel has its input pixel; a residue class of a strided backward pass can be one row or
@@ -166,7 +169,7 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
             LR = TR;
         } else {
             Hs = (P - 1) * stride + R;
-            LW = (TQ - 1) * stride + S;
+            LW = (TQ - 1) * cstride + S;
             LR = max_band_rows(N, P, TR, Hs, stride, R);
         }
         const int need = ceil_div(LR * LW, NT);
@@ -188,8 +191,8 @@ IgemmPlan try_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q
     IgemmArgs &a = pl.a;
     memset(&a, 0, sizeof(a));
     a.N = N; a.Cb = Cb; a.H = H; a.W = W; a.Kp = Kp; a.P = P; a.Q = Q;
-    a.stride = stride; a.pad_h = pad_h; a.pad_w = pad_w;
-    a.OH = OH; a.OW = OW; a.ostr = ostr; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
+    a.stride = stride; a.cstride = cstride; a.pad_h = pad_h; a.pad_w = pad_w;
+    a.OH = OH; a.OW = OW; a.ostr = ostr; a.ostr_x = ostr_x; a.oy0 = oy0; a.ox0 = ox0; a.zero_fill = zero_fill;
     a.shuffle = 0; a.out_kb = Kp / V;
     a.ksplit = 1;
     a.scale = nullptr; a.bias = nullptr; a.resid = nullptr; a.relu = 0;
@@ -267,14 +270,14 @@ double igemm_waste(const IgemmPlan &p, int N, int P, int Q, int Kp)
 // wider channel tile (fewer re-reads of the input tile).
 IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                           int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                          int zero_fill);
+                          int zero_fill, const IgemmGeo &geo);
 
 IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                      int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                     int zero_fill)
+                     int zero_fill, const IgemmGeo &geo = IgemmGeo{})
 {
     IgemmPlan p = plan_igemm_tile(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr,
-                                  oy0, ox0, zero_fill);
+                                  oy0, ox0, zero_fill, geo);
     // One channel tile: every line of the input is staged by exactly one workgroup.  Loaded
     // non-temporally it does not displace the weights in the L2 nor settle in the last-level
     // cache on its way past (CONVMI_IGEMM_NT=0 keeps the default policy: a tuning aid).
@@ -289,7 +292,7 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
 
 IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P, int Q, int R, int S,
                           int stride, int pad_h, int pad_w, int OH, int OW, int ostr, int oy0, int ox0,
-                          int zero_fill)
+                          int zero_fill, const IgemmGeo &geo)
 {
     IgemmPlan best;
     double best_cost = 0;
@@ -307,7 +310,7 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
             if (TK > 64 && Kp <= TK / 2) continue;
             if (TK == 32 && Kp > 96) continue;  // (three 32-row tiles at most: 80 rows waste less so)
             IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
-                                    ostr, oy0, ox0, zero_fill, cd.wk, cd.wm, cd.fk, cd.fm, caps[ci]);
+                                    ostr, oy0, ox0, zero_fill, geo, cd.wk, cd.wm, cd.fk, cd.fm, caps[ci]);
             if (!c.ok) continue;
             // one workgroup per CU loses roughly a fifth to exposed barriers/staging
             double cost = igemm_waste(c, N, P, Q, Kp) * (ci == 0 ? 1.0 : 1.2) *
@@ -324,6 +327,21 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
                 best_cost = cost;
             }
         }
+    // Two cells per column (a strided backward pass into one channel block): the staged tile
+    // is twice as wide per result column, and with two channel planes per step the band that
+    // fits the LDS leaves a third of the pixel slots empty; one plane per step fits a full
+    // band (measured on the 7x7 stride-2 layer at N = 256, fp32: 1.65 ms against 1.07 ms).
+    if (geo.cstride > 1 && R * S > 1) {
+        for (const Cand &cd : cands) {
+            if (cd.fk == 2 && dtype != CONV_BF16) continue;
+            if (cd.wk * cd.fk * 32 != 32 || Kp > 32) continue;
+            IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
+                                    ostr, oy0, ox0, zero_fill, geo, cd.wk, cd.wm, cd.fk, cd.fm,
+                                    (size_t)kMaxLds, 2, 1);
+            if (c.ok && (!best.ok || igemm_waste(c, N, P, Q, Kp) < 0.9 * igemm_waste(best, N, P, Q, Kp)))
+                best = c;
+        }
+    }
     // Tuning aid: CONVMI_IGEMM_CAND="wk,wm,fk,fm,nb,npl" asks for one kernel variant wherever it
     // exists and fits (npl 0: the default planes per step); unset in normal use.
     if (const char *env = getenv("CONVMI_IGEMM_CAND")) {
@@ -331,7 +349,7 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
         if (sscanf(env, "%d,%d,%d,%d,%d,%d", &wk, &wm, &fk, &fm, &nb, &npl) >= 4 && wk > 0 && wm > 0 &&
             fk > 0 && fm > 0 && (wk * wm == 4 || wk * wm == 8) && nb >= 2 && nb <= 5) {
             IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW,
-                                    ostr, oy0, ox0, zero_fill, wk, wm, fk, fm, (size_t)kMaxLds, nb, npl);
+                                    ostr, oy0, ox0, zero_fill, geo, wk, wm, fk, fm, (size_t)kMaxLds, nb, npl);
             if (c.ok) return c;
         }
     }
@@ -342,14 +360,26 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
     // on the 1x1 layers with at least 256 output rows and 128 input channels, 2 - 6 % on the
     // 28 x 28 and 14 x 14 3x3 layers).  Not for results narrower than the tile, and not where
     // the tiles would not fill the chip (there the four-wave tiles, or a split reduction, do).
+    // ... except where the reduction is short (at most 256 channels) and the result wide: a
+    // tile then spends as long on its first loads and its stores as on its MFMAs, and two
+    // four-wave workgroups per CU with 128 x 256 tiles, which overlap each other's ends, are
+    // 10 - 12 % faster than one eight-wave workgroup (measured on the 128 -> 512 and
+    // 256 -> 1024 layers and the backward pass of 1024 -> 256).
+    if (dtype == CONV_BF16 && best.ok && R * S == 1 && stride == 1 && ostr == 1 && Kp >= 512 &&
+        Cb <= 32 && Cb % 4 == 0) {
+        IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr, oy0,
+                                ox0, zero_fill, geo, 2, 2, 2, 4, (size_t)kMaxLds / 2, 2, 4);
+        if (c.ok && c.a.total >= 300 && igemm_waste(c, N, P, Q, Kp) <= 1.1 * igemm_waste(best, N, P, Q, Kp))
+            return c;
+    }
     if (dtype == CONV_BF16 && best.ok) {
         IgemmPlan c;
         if (R * S == 1 && Kp >= 256 && Cb % 8 == 0)
             c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr, oy0,
-                          ox0, zero_fill, 4, 2, 2, 4, (size_t)kMaxLds, 2, 8);
+                          ox0, zero_fill, geo, 4, 2, 2, 4, (size_t)kMaxLds, 2, 8);
         else if (R == 3 && S == 3 && stride == 1 && Kp >= 128 && Cb % 2 == 0)
             c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr, oy0,
-                          ox0, zero_fill, 2, 4, 2, 4, (size_t)kMaxLds, 2, 2);
+                          ox0, zero_fill, geo, 2, 4, 2, 4, (size_t)kMaxLds, 2, 2);
         if (c.ok && c.a.total >= 150 && igemm_waste(c, N, P, Q, Kp) <= 1.1 * igemm_waste(best, N, P, Q, Kp))
             return c;
     }
@@ -358,7 +388,7 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
     if (dtype == CONV_BF16 && R * S == 1 && best.ok && best.a.n_stage >= 3) {
         const size_t cap = best.lds <= (size_t)kMaxLds / 2 ? (size_t)kMaxLds / 2 : (size_t)kMaxLds;
         IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr,
-                                oy0, ox0, zero_fill, best.v.wk, best.v.wm, best.v.fk, best.v.fm, cap, 3);
+                                oy0, ox0, zero_fill, geo, best.v.wk, best.v.wm, best.v.fk, best.v.fm, cap, 3);
         if (c.ok && c.a.total <= best.a.total) best = c;
     }
     return best;
@@ -432,11 +462,21 @@ void plan_bwd(conv_plan *p)
                 win[ax] = std::max(win[ax], std::max(sub[pp], 1) + sh[pp]);
             }
         }
-        m.Kb = f.Kb; m.Kp = f.Kp; m.R = d.R; m.S = d.S; m.R2 = win[0]; m.S2 = win[1]; m.st = st;
+        // Where the classes fill only half of an MFMA's 32 rows (fp32, stride 2), a column of
+        // the result stands for TWO cells side by side: 32 live rows, half the columns, and a
+        // window one tap wider (cell e of the pair reads its taps e columns to the right).
+        // (CONVMI_BWD_CELLS=1 keeps one cell per column: a tuning aid.)
+        int cells = (2 * st * st * f.vlen <= 32 && ceil_div(d.W, st) >= 2) ? 2 : 1;
+        if (const char *env = getenv("CONVMI_BWD_CELLS"); env && atoi(env) == 1) cells = 1;
         const int Hc = ceil_div(d.H, st), Wc = ceil_div(d.W, st);
-        if (padU[0] >= 0 && padU[1] >= 0) {
-            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, st * st * f.vlen, Hc, Wc, win[0], win[1], 1,
-                             padU[0], padU[1], d.H, d.W, st, 0, 0, 0);
+        for (; cells >= 1 && padU[0] >= 0 && padU[1] >= 0; --cells) {
+            m.Kb = f.Kb; m.Kp = f.Kp; m.R = d.R; m.S = d.S; m.R2 = win[0]; m.S2 = win[1] + cells - 1;
+            m.st = st; m.cells = cells;
+            IgemmGeo geo;
+            geo.cstride = cells;
+            geo.ostr_x = cells * st;
+            b.p = plan_igemm(d.dtype, d.N, f.Kb, f.P, f.Q, cells * st * st * f.vlen, Hc, ceil_div(Wc, cells),
+                             m.R2, m.S2, 1, padU[0], padU[1], d.H, d.W, st, 0, 0, 0, geo);
             if (b.p.ok) {
                 b.p.a.shuffle = 1;
                 b.p.a.out_kb = 1;
@@ -444,7 +484,7 @@ void plan_bwd(conv_plan *p)
                 b.ws_off = 0;
                 p->bwd_mode = 3;
                 p->n_bwd = 1;
-                p->bwd_ws = (size_t)f.Kb * win[0] * win[1] * st * st * f.vlen * f.vlen * es;
+                p->bwd_ws = (size_t)f.Kb * m.R2 * m.S2 * cells * st * st * f.vlen * f.vlen * es;
                 return;
             }
         }

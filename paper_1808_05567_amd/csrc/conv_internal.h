@@ -32,12 +32,15 @@ struct IgemmArgs {
     int Kp;        // output channels rounded up to vlen (rows of A)
     int P, Q;      // extent of the convolution result
     int stride, pad_h, pad_w;
+    int cstride;   // input pixels between consecutive result columns (== stride, except where a
+                   // column of the result stands for several cells of a strided backward pass)
     int OH, OW;    // extent of the output tensor (== P,Q unless scattering)
-    int ostr;      // result pixel (oj,oi) is written at (oj*ostr+oy0, oi*ostr+ox0)
+    int ostr;      // result pixel (oj,oi) is written at (oj*ostr+oy0, oi*ostr_x+ox0)
+    int ostr_x;    // (== ostr, except as for cstride)
     int oy0, ox0;
     int zero_fill; // ostr>1: also write zeros to the other positions of each ostr x ostr cell
-    int shuffle;   // ostr>1: result channel block b is position (b / ostr, b % ostr) of the
-                   // ostr x ostr cell of an output tensor with ONE channel block
+    int shuffle;   // ostr>1: result channel block b is position (b / ostr_x, b % ostr_x) of the
+                   // ostr x ostr_x cell of an output tensor with ONE channel block
     int out_kb;    // channel blocks of the output tensor
     int TR, TQ;    // tile = TR linear output rows (n*P+oj) x TQ columns
     int n_qt;      // column tiles
@@ -69,6 +72,12 @@ struct IgemmArgs {
     const float *bias;  // per output channel row, Kp entries, or null
     const void *resid;  // tensor of the output's layout and type added to the result, or null
     int relu;           // clamp at zero after the additions
+};
+
+// Optional geometry of a plan beyond the plain convolution's (0: as the strides say).
+struct IgemmGeo {
+    int cstride = 0;  // IgemmArgs::cstride
+    int ostr_x = 0;   // IgemmArgs::ostr_x
 };
 
 // Key of a kernel instantiation; the host picks one per pass at plan time.
@@ -115,8 +124,12 @@ hipError_t launch_wt_xform(int dtype, const WtXformArgs &a, hipStream_t stream);
 // source tap r = st*(rsub[py]-1-r2) + roff[py]; columns likewise.
 struct WtMergeArgs {
     const void *src;  // Wb[1][R][S][Kp][v]
-    void *dst;        // [Kb][R2][S2][st*st*v][v]
+    void *dst;        // [Kb][R2][S2][cells*st*st*v][v]
     int Kb, Kp, R, S, R2, S2, st;
+    // Cells per column of the result (1 or 2).  With 2, row block (py, e, px) holds class
+    // (py, px) of cell e of a pair of cells side by side, its taps e columns to the right in
+    // a window S2 = (the classes' common window) + 1 wide.
+    int cells;
     int rsub[4], roff[4], rsh[4];
     int ssub[4], soff[4], ssh[4];
 };

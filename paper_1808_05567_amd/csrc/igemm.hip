@@ -44,6 +44,9 @@ static IgemmEntry g_igemm[] = {
     // (an odd number of channel blocks of dO: one block per step)
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 1, 4, 4, 6),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 1, 4, 4, 6),
+    // (two cells per column: the window is one tap wider)
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 1, 4, 5, 9),
+    IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 4, 5, 8),
     // bf16
     IGEMM_ENTRY(CONV_BF16, 4, 1, 1, 7, 2, 3, 3, 2),
     IGEMM_ENTRY(CONV_BF16, 2, 2, 1, 7, 2, 3, 3, 3),
@@ -89,6 +92,7 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 4, 1, 1, 2, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 8, 1, 1, 2, 2),
+    IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 2, 4, 4, 1, 1, 1, 2),
     // 3x3: 128 x 512 tiles
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 3),
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 4),

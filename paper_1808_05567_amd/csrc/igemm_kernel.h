@@ -226,7 +226,7 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
                 const int lam = lam0 + row;
                 n = fast_div(lam, inv_Hs);
                 ih = lam - mul24(n, a.Hs) - a.pad_h;
-                iw = q0 * a.stride - a.pad_w + col;
+                iw = q0 * a.cstride - a.pad_w + col;
                 ok = n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             }
             if (ok) off = (unsigned)(mul24(mul24(mul24(n, a.Cb), a.H) + ih, a.W) + iw) * 16u;
@@ -294,13 +294,13 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
         const int oj = rho - mul24(n, a.P);
         int pos = a.sampled ? m
                             : mul24(mul24(n, a.Hs) + mul24(oj, a.stride) - lam0, a.LW) +
-                                  mul24(tcol, a.stride);
+                                  mul24(tcol, a.cstride);
         if (!ok) pos = 0;
         // lane halves read two channel planes, or (one plane per step) two taps
         bpos[j] = ((NPL == 1 ? 0 : h) * a.PLS + pos) * 16;
         obyte[j] = ok ? (unsigned)(mul24(mul24(mul24(n, Kb_out), a.OH) + mul24(oj, a.ostr) + a.oy0,
                                          a.OW) +
-                                   mul24(q0 + tcol, a.ostr) + a.ox0) * 16u
+                                   mul24(q0 + tcol, a.ostr_x) + a.ox0) * 16u
                       : kOutOfRange;
     }
     const int a_base = (h * TK + wave_k * FK * 32 + l32) * 16;
@@ -567,7 +567,7 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
         const int rho = rho0 + trow;
         const int n = fast_div(rho, inv_P);
         sy[j] = mul24(rho - mul24(n, a.P), a.ostr) + a.oy0;
-        sx[j] = mul24(q0 + tcol, a.ostr) + a.ox0;
+        sx[j] = mul24(q0 + tcol, a.ostr_x) + a.ox0;
     }
 #pragma unroll
     for (int i = 0; i < FK; ++i) {
@@ -576,9 +576,9 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
             const int krow0 = k0 + (wave_k * FK + i) * 32 + vq * 8;  // + 4*h for this lane
             if (krow0 >= a.Kp) continue;                            // wave-uniform
             // fp32: 8 rows = blocks 2*q (h=0) and 2*q+1 (h=1); bf16: one block, halves by h
-            // Shuffle mode: the lane's channel block is a position of the ostr x ostr cell.
+            // Shuffle mode: the lane's channel block is a position of the ostr x ostr_x cell.
             const int blk = krow0 / V + (V == 4 ? h : 0);
-            const int cy = blk / a.ostr, cx = blk - cy * a.ostr;
+            const int cy = blk / a.ostr_x, cx = blk - cy * a.ostr_x;
             const unsigned skip = a.shuffle ? 0u : (unsigned)(krow0 / V) * (unsigned)oplane;
             const unsigned lane_off =
                 a.shuffle ? (unsigned)(cy * a.OW + cx) * 16u + (V == 4 ? 0u : (unsigned)h * 8u)
@@ -593,7 +593,7 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
                            acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]);
                 if (a.zero_fill) {
                     for (int dy = 0; dy < a.ostr; ++dy)
-                        for (int dx = 0; dx < a.ostr; ++dx) {
+                        for (int dx = 0; dx < a.ostr_x; ++dx) {
                             if ((dy | dx) == 0) continue;
                             const bool in = live && sy[j] + dy < a.OH && sx[j] + dx < a.OW;
                             E_::store4(ro, in ? off + (unsigned)(dy * a.OW + dx) * 16u : kOutOfRange,

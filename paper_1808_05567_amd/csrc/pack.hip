@@ -111,16 +111,18 @@ __global__ __launch_bounds__(256) void wt_merge_kernel(const WtMergeArgs a, int 
     if (idx >= total) return;
     const T *src = static_cast<const T *>(a.src);
     T *dst = static_cast<T *>(a.dst);
-    const int rows = a.st * a.st * V;
+    const int rows = a.cells * a.st * a.st * V;
     const int row = idx % rows;
     int t = idx / rows;
     const int v = t % a.S2;
     t /= a.S2;
     const int u = t % a.R2;
     const int kb = t / a.R2;
-    const int cls = row / V, c = row % V;
-    const int py = cls / a.st, px = cls % a.st;
-    const int r2 = u - a.rsh[py], s2 = v - a.ssh[px];
+    // row block (py, e, px): the position (py, e*st + px) of a cell pair's st x (cells*st) pixels
+    const int blk = row / V, c = row % V;
+    const int py = blk / (a.cells * a.st);
+    const int e = (blk / a.st) % a.cells, px = blk % a.st;
+    const int r2 = u - a.rsh[py], s2 = v - e - a.ssh[px];
     const bool tap_ok = r2 >= 0 && r2 < a.rsub[py] && s2 >= 0 && s2 < a.ssub[px];
     const int r = a.st * (a.rsub[py] - 1 - r2) + a.roff[py];
     const int s = a.st * (a.ssub[px] - 1 - s2) + a.soff[px];
@@ -218,7 +220,7 @@ hipError_t launch_wt_xform(int dtype, const WtXformArgs &a, hipStream_t stream)
 hipError_t launch_wt_merge(int dtype, const WtMergeArgs &a, hipStream_t stream)
 {
     const int V = vlen_of(dtype);
-    const int total = a.Kb * a.R2 * a.S2 * a.st * a.st * V;
+    const int total = a.Kb * a.R2 * a.S2 * a.cells * a.st * a.st * V;
     if (dtype == CONV_BF16)
         hipLaunchKernelGGL((wt_merge_kernel<uint16_t, 8>), dim3(blocks_for(total)), dim3(256), 0, stream,
                            a, total);

@@ -55,6 +55,8 @@ SMALL = [
 FEW_CHANNELS = [
     (2, 3, 64, 32, 32, 7, 7, 2, 3),       # conv1 geometry: 7x7, stride 2, pad 3
     (3, 3, 40, 21, 19, 7, 7, 2, 3),       # odd extents, ragged channel tile
+    (2, 3, 32, 19, 21, 7, 7, 2, 3),       # an odd number of stride cells per row (backward pairs them)
+    (1, 4, 16, 8, 6, 7, 7, 2, 3),         # ... three cells per row, fewer rows than the filter
     (2, 3, 16, 12, 12, 3, 3, 1, 1),
     (2, 4, 72, 9, 9, 3, 3, 1, 1),
 ]
