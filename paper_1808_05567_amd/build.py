@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libconv_mi355x.so")
-SOURCES = ("api.hip", "igemm.hip", "igemm_rect.hip", "upd.hip", "upd_f32.hip", "upd_f32_1x1.hip", "upd_f32_c4.hip", "upd_bf16.hip", "upd_bf16_1x1.hip", "upd_bf16_c4.hip", "direct.hip", "pack.hip", "ceilings.hip")
+SOURCES = ("api.hip", "igemm.hip", "igemm_rect.hip", "igemm_stem.hip", "upd.hip", "upd_f32.hip", "upd_f32_1x1.hip", "upd_f32_c4.hip", "upd_bf16.hip", "upd_bf16_1x1.hip", "upd_bf16_c4.hip", "direct.hip", "pack.hip", "ceilings.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

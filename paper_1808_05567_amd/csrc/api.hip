@@ -55,6 +55,7 @@ struct conv_plan {
     conv_info_t info;
     IgemmPlan fwd;
     size_t fwd_ws = 0;  // bytes of fp32 partial results if the forward reduction is split
+    size_t fwd_stem_lds = 0;  // > 0: the plain forward pass runs on the resident-filter kernel (its LDS)
     // backward by data
     int bwd_mode = 0;  // 0 unsupported, 1 one launch (duality), 2 parity classes
     int n_bwd = 0;
@@ -1239,6 +1240,18 @@ conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
                 p->fwd_ws = (size_t)a.ksplit * d.N * f.Kp * f.P * f.Q * sizeof(float);
             }
         }
+        // A first layer (one channel block in, one reduction step, one channel tile): resident
+        // workgroups that keep the filter in LDS and prefetch the next input tile.
+        // (CONVMI_STEM=0 keeps one workgroup per tile: a tuning aid.)
+        p->fwd_stem_lds = 0;
+        if (p->fwd.ok) {
+            const char *env = getenv("CONVMI_STEM");
+            const size_t need = igemm_stem_lds(p->fwd.v, p->fwd.a);
+            if (need > 0 && need <= (size_t)kMaxLds && !(env && atoi(env) == 0)) p->fwd_stem_lds = need;
+            // (CONVMI_STEM_WG=n: at most n workgroups per XCD, so that small inputs too give a
+            // workgroup several tiles to walk: for tests of that path)
+            if (const char *cap = getenv("CONVMI_STEM_WG"); cap && atoi(cap) > 0) p->fwd.a.jstep = atoi(cap);
+        }
         plan_bwd(p);
         plan_upd(p);
     }
@@ -1385,7 +1398,11 @@ conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *w
     a.bias = split ? nullptr : bias;
     a.resid = split ? nullptr : residual;
     a.relu = split ? 0 : (relu != 0);
-    hipError_t e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
+    hipError_t e;
+    if (h->fwd_stem_lds && !scale && !bias && !residual && !relu)
+        e = launch_igemm_stem(h->fwd.v, a, h->fwd_stem_lds, (hipStream_t)stream);
+    else
+        e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
     if (e == hipSuccess && split)
         e = launch_split_reduce(h->d.dtype, static_cast<const float *>(ws), out,
                                 (size_t)h->d.N * h->info.Kp * h->info.P * h->info.Q, a.ksplit, scale,
@@ -1713,6 +1730,10 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
                  p->v.dtype, p->v.wk, p->v.wm, p->v.fk, p->v.fm, p->v.npl, p->v.nt, p->v.r, p->v.s, p->v.ppt,
                  p->a.TR, p->a.TQ, p->a.total, p->a.n_mt, p->a.n_qt, p->a.n_kt, p->a.gk, p->grid, p->lds,
                  p->a.n_stage, p->a.ksplit, pass == 0 ? 1 : h->n_bwd);
+        if (pass == 0 && h->fwd_stem_lds) {
+            const size_t n = strlen(buf);
+            snprintf(buf + n, buflen - n, " resident_filter_lds=%zu", h->fwd_stem_lds);
+        }
         return CONV_OK;
     }
     if (pass == 2) {

@@ -55,6 +55,8 @@ struct IgemmArgs {
     float inv_P, inv_Hs, inv_LW, inv_TQ;
     int total;     // workgroups doing work
     int per_xcd;   // workgroups per XCD (the grid is 8 * per_xcd)
+    int jstep;     // resident-filter kernel only: workgroups per XCD of its launch; a workgroup
+                   // takes pixel tiles j, j + jstep, ... of its XCD (set at launch)
     // Tiles over the 8 XCDs: gk channel groups of kt_per channel tiles x 8/gk pixel groups
     // of mq_per pixel tiles (per_xcd = kt_per * mq_per); unused when the reduction is split
     int gk, kt_per, mq_per;
@@ -99,6 +101,11 @@ hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
 hipError_t launch_igemm(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes,
                         int grid, hipStream_t stream);
 bool igemm_variant_exists(const IgemmVariant &v);
+// The resident-filter kernel for first layers (one channel block in, one reduction step, one
+// channel tile): LDS it needs for the plan, 0 if it does not serve it; and its launch (plain
+// store only: no fused operators).
+size_t igemm_stem_lds(const IgemmVariant &v, const IgemmArgs &a);
+hipError_t launch_igemm_stem(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes, hipStream_t stream);
 // out[e] = sum over copies j (ascending) of partial[j][e], converted to the tensor's type
 // Fused operators (null / 0: none): scale[channel], bias[channel], residual (output
 // layout), ReLU; pq = pixels per image, kb = channel blocks, for the channel of an element.

@@ -109,8 +109,10 @@ struct Elem<CONV_BF16> {
 // are not kept in the last-level cache, instead of pushing out the weights and the output
 // lines on their way to memory (measured at N = 256, bf16, backward pass of the 1x1 layers
 // that widen the channel count: 25 - 35 % faster).
+// (Register budget: two workgroups per CU for the four-wave tiles of at most 128 accumulator
+// registers; a 7x7 filter alone fills most of a CU's LDS, so those run one per CU anyway.)
 template <int DT, int WK, int WM, int FK, int FM, int NPL, int R, int S, int PPT, int NB = 2, int NTI = 0>
-__global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128) ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128 && R * S < 49) ? 2 : 1)) void igemm_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
     constexpr int V = E_::V;
@@ -352,6 +354,16 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128)
                 for (int i = 0; i < FK; ++i)
 #pragma unroll
                     for (int j = 0; j < FM; ++j) E_::mma(ac[i], bc[j], acc[i][j]);
+                // Issue order of the round: one MFMA, then one LDS read of the next pair's
+                // operands, and so on (left to itself the compiler reads each operand right
+                // before the MFMA that takes it, into one register set, and waits there).
+                constexpr int NMFMA1 = FK * FM * (DT == CONV_F32 ? 4 : 1);
+#pragma unroll
+                for (int k = 0; k < NMFMA1; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 if (q + 1 < NENT / 2) {
 #pragma unroll
                     for (int i = 0; i < FK; ++i) ac[i] = an[i];

@@ -247,6 +247,39 @@ def test_few_channel_layers_match_oracle(shape, dtype):
         L.close()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("wgs", [1, 2])
+def test_first_layer_forward_resident_filter(dtype, wgs, monkeypatch):
+    """Forward pass of a first layer on the kernel that keeps the filter in LDS and walks
+    several tiles per workgroup, the next tile's input prefetched: with at most `wgs`
+    workgroups per XCD a workgroup here walks up to five tiles (ragged last tile, an XCD
+    with fewer tiles than the others).  Against the oracle, and bit for bit against the general
+    kernel (same tiles, same order of the sum)."""
+    shape = (5, 3, 64, 60, 220, 7, 7, 2, 3)
+    N, C, K, H, W, R, S, stride, pad = shape
+    I, Wt, _ = make_inputs(shape, dtype, layer_id=1)
+    ref = oracle.fwd(I, Wt, stride, pad)
+    monkeypatch.setenv("CONVMI_STEM_WG", str(wgs))
+    L = _layer(shape, dtype)
+    try:
+        desc = conv.conv_describe(L.h, 0)
+        assert "resident_filter_lds" in desc, desc
+        tiles = int(desc.split("tiles=")[1].split()[0])
+        assert tiles > 8 * wgs, desc  # (several tiles per workgroup)
+        got = run_pass(L, "fwd", I=I, Wt=Wt)
+    finally:
+        L.close()
+    assert_close(got, ref, dtype, "fwd (resident filter)")
+    monkeypatch.setenv("CONVMI_STEM", "0")
+    L = _layer(shape, dtype)
+    try:
+        assert "resident_filter_lds" not in conv.conv_describe(L.h, 0)
+        plain = run_pass(L, "fwd", I=I, Wt=Wt)
+    finally:
+        L.close()
+    assert np.array_equal(got, plain)
+
+
 @pytest.mark.parametrize("shape", [FEW_CHANNELS[0], (3, 3, 48, 21, 19, 7, 7, 2, 3)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_first_layer_backward_bf16(shape):
