@@ -302,7 +302,8 @@ def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
                           "per_pass_tflops": {w: round(tf[w], 2) for w in PASSES},
                           "per_pass_pct_of_mfma_peak": {w: round(100 * tf[w] / peak, 1) for w in PASSES},
                           "tflops": round(allp, 2), "pct_of_mfma_peak": round(100 * allp / peak, 1)}
-    # Dominant kernel: the implicit-GEMM kernel.  A forward launch is exactly one launch of it,
+    # Dominant kernel: the implicit-GEMM kernel (for a first layer its resident-filter form:
+    # the same tiles and MFMA layout).  A forward launch is exactly one launch of it,
     # so the forward events are its launch durations: achieved = algorithmic flops of the
     # forward launches / their summed duration.
     all_l = [l for l, _ in layers]
@@ -315,7 +316,7 @@ def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
         try:
             ks = json.load(open(traffic_file))["kernels"]
             ig = [(v["calls"], v["fetch_bytes"] + v["write_bytes"]) for k, v in ks.items()
-                  if "igemm_kernel" in k]
+                  if "igemm_kernel" in k or "igemm_stem_kernel" in k]
             traffic = round(sum(c * b for c, b in ig) / sum(c for c, _ in ig))
         except Exception:
             traffic = None
@@ -384,12 +385,21 @@ def measure_ceilings():
         s = timed(lambda: conv.conv_ceiling_l2_to_lds(src, 2048 * win, nb, it, sink, regs))
         out["beyond_l2_to_lds_tbps_4wg_per_cu_%s" % ("via_registers" if regs else "lds_direct")] = round(
             nb * it * 16384 / s / 1e12, 2)
+    # LDS operand reads (bytes per clock and CU at the 2.4 GHz the peaks are quoted at): lanes on
+    # consecutive chunks, and over a staged tile of 14-pixel rows 16 chunks apart (the 14x14
+    # 3x3 layers), where lanes of one 16-lane pass share banks
+    for key, row_len, pitch in (("lds_read_bytes_per_clk_cu_contiguous", 0, 0),
+                                ("lds_read_bytes_per_clk_cu_rows_of_14_pitch_16", 14, 16)):
+        it, nb = 20000, 256
+        s = timed(lambda: conv.conv_ceiling_lds_read(nb, it, sink, row_len, pitch))
+        out[key] = round(nb * 512 * it * 8 * 16 / s / 256 / 2.4e9, 1)
     del src, sink
     out["note"] = ("MFMA: 512 workgroups x 4 waves (two waves per SIMD), eight independent 32x32 "
                    "accumulator tiles per wave; copy: 1 GiB, read + write bytes counted; L2->LDS: "
                    "workgroups of 4 waves streaming 96 KiB windows that hit the L2 but not the "
                    "32 KiB L1, with loads that write into LDS or through registers; beyond L2: "
-                   "the same with more windows per XCD than its L2 holds")
+                   "the same with more windows per XCD than its L2 holds; LDS reads: one workgroup "
+                   "of 8 waves per CU, eight 16-byte reads per lane in flight")
     return out
 
 

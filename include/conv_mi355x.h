@@ -265,6 +265,12 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
  *   the forward kernel); != 0: 16-byte loads into registers followed by LDS writes.
  *   Bytes moved = blocks * iters * 16 KiB.  src: device, 16-byte aligned,
  *   96 KiB <= src_bytes < 4 GiB; sink as above.
+ * conv_ceiling_lds_read: `blocks` workgroups of 8 waves, each wave keeping eight 16-byte LDS
+ *   reads per lane in flight, `iters` times.  row_len == 0: lane i reads chunk i (no two
+ *   lanes of a 16-lane pass on the same banks); row_len > 0: lane i reads the chunk of pixel
+ *   i of a tile whose rows of row_len pixels lie row_pitch chunks apart (the operand read
+ *   over a staged tile with a halo: pitch = row_len + S - 1), at most 2 KiB per wave.
+ *   Bytes read = blocks * 512 * iters * 8 * 16.  sink: device, blocks * 512 floats.
  * Errors: CONV_EINVAL for a NULL or misaligned pointer or a count < 1, CONV_EUNSUPPORTED
  * beyond the stated sizes, CONV_ELAUNCH if the runtime refuses the launch. */
 conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink,
@@ -275,6 +281,8 @@ conv_status_t conv_ceiling_write(void *dst, size_t bytes, void *stream);
 conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t blocks,
                                      int32_t iters, int32_t through_registers, float *sink,
                                      void *stream);
+conv_status_t conv_ceiling_lds_read(int32_t blocks, int32_t iters, int32_t row_len,
+                                    int32_t row_pitch, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

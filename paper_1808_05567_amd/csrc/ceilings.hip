@@ -138,6 +138,34 @@ __global__ __launch_bounds__(256) void l2_to_lds_kernel(const void *src, size_t 
         reinterpret_cast<const float *>(lds)[(threadIdx.x * 4 + blockIdx.x) % (2 * kStep / 4)];
 }
 
+// 16-byte LDS reads, eight independent ones in flight per wave, `iters` times.  Lane i reads
+// chunk i of its wave's 4 KiB (row_len = 0), or the chunk of pixel i of a tile of rows of
+// `row_len` pixels that lie `row_pitch` chunks apart: the operand read of the implicit-GEMM
+// kernel over a staged tile whose rows are wider than the result's (a 3x3 filter: pitch =
+// row_len + 2).  The LDS serves 16 lanes per pass from 64 banks of 4 bytes: lanes of one pass
+// whose chunks are equal modulo 16 take turns.
+__global__ __launch_bounds__(512) void lds_read_kernel(float *sink, int iters, int row_len, int row_pitch)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    for (int i = threadIdx.x; i < 16384; i += blockDim.x) reinterpret_cast<unsigned *>(lds)[i] = (unsigned)i;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = row_len > 0 ? (lane / row_len) * row_pitch + lane % row_len : lane;
+    const unsigned base = (unsigned)((wave & 7) * 4096 + chunk * 16);
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    unsigned acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v[u]) : "v"(base), "n"((u & 1) * 2048));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][3];
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = (float)(acc & 0xFFFF);
+}
+
 }  // namespace
 }  // namespace convmi
 
@@ -201,6 +229,18 @@ conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t 
     else
         hipLaunchKernelGGL(l2_to_lds_kernel<true>, dim3(blocks), dim3(256), lds_bytes, (hipStream_t)stream,
                            src, src_bytes, sink, iters);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_lds_read(int32_t blocks, int32_t iters, int32_t row_len, int32_t row_pitch,
+                                    float *sink, void *stream)
+{
+    if (!sink || blocks < 1 || iters < 1 || row_len < 0) return CONV_EINVAL;
+    // (a wave's 64 lanes stay inside its 4 KiB, the second read of a pair 2 KiB further on)
+    if (row_len > 0 && (row_pitch < row_len || ((63 / row_len) * row_pitch + row_len) * 16 > 2048))
+        return CONV_EINVAL;
+    hipLaunchKernelGGL(lds_read_kernel, dim3(blocks), dim3(512), 65536, (hipStream_t)stream, sink, iters,
+                       row_len, row_pitch);
     return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }
 
