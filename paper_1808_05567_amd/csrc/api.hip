@@ -392,6 +392,18 @@ IgemmPlan plan_igemm_tile(int dtype, int N, int Cb, int H, int W, int Kp, int P,
                                 oy0, ox0, zero_fill, geo, best.v.wk, best.v.wm, best.v.fk, best.v.fm, cap, 3);
         if (c.ok && c.a.total <= best.a.total) best = c;
     }
+    // ... and where the tiles number no more than the CUs (a narrow result behind a deep
+    // reduction: the 7x7 layers that narrow the channel count) a workgroup has its CU to itself
+    // anyway: eight channel blocks per step then, four MFMA rounds between two barriers instead
+    // of two and twice the bytes in flight (measured at N = 256: layer 20 forward 76 -> 55 us,
+    // layer 19 backward 83 -> 60, layer 17 forward 64 -> 54; deeper rings change nothing).
+    if (dtype == CONV_BF16 && R * S == 1 && best.ok && best.v.wk * best.v.wm == 4 && best.v.fk == 1 &&
+        best.a.total <= 256 && Cb % 8 == 0 && Cb >= 32) {
+        IgemmPlan c = try_igemm(dtype, N, Cb, H, W, Kp, P, Q, R, S, stride, pad_h, pad_w, OH, OW, ostr,
+                                oy0, ox0, zero_fill, geo, best.v.wk, best.v.wm, best.v.fk, best.v.fm,
+                                (size_t)kMaxLds, 2, 8);
+        if (c.ok && c.a.total <= best.a.total) best = c;
+    }
     return best;
 }
 
@@ -725,9 +737,14 @@ bool plan_upd_flat_bf16(conv_plan *p)
     if (bf16 && sampled && (double)d.N * f.P * f.Q < 4.0e6 &&
         (double)(d.N + 1) * std::max(f.Cb, f.Kb) < 8.0e6 && (double)d.H * d.W < 8.0e6 &&
         (double)d.N * f.Cp * d.H * d.W * 2 < 4.0e9 && (double)d.N * f.Kp * f.P * f.Q * 2 < 4.0e9) {
-        // bf16 1x1: the channel block that re-reads the least (the input is read once per
-        // output-channel block, dO once per input-channel block), then the smaller block;
-        // the pixel list is split so that one round of workgroups fills the chip
+        // bf16 1x1: the dW block that moves the fewest bytes.  The input is staged once per
+        // output-channel block and dO once per input-channel block (re-reads that the L2
+        // mostly serves: weight 1/2; with stride 2 only every other pixel of a fetched line
+        // is used), and the pixel list is split so that one round of workgroups fills the
+        // chip, each split writing a partial dW that the reduce kernel reads back (HBM both
+        // ways).  Fitted to the update times of the 14x14 and 7x7 layers at N = 256 under every
+        // block shape: a 128 x 256 block there beats 256 x 256 by 5 - 12 % (half the partial
+        // copies), except where dW itself is the largest tensor (1024 -> 2048).
         static const UpdRowsVariant kFlat[9] = {
             {1, 1, 4, 2, 1, 2, 4}, {1, 1, 2, 2, 2, 2, 4}, {1, 1, 1, 2, 4, 2, 4},
             {1, 1, 4, 1, 2, 2, 4}, {1, 1, 2, 1, 4, 2, 4}, {1, 1, 2, 2, 2, 1, 2},
@@ -738,10 +755,20 @@ bool plan_upd_flat_bf16(conv_plan *p)
         for (const UpdRowsVariant &c : kFlat) {
             if (!upd_bf16_1x1_variant_exists(c)) continue;
             const int TC = c.wc * c.fc * 32, TK = c.wk * c.fk * 32;
-            const double bytes = (double)f.in_bytes / (d.stride * d.stride) * ceil_div(f.Kp, TK) +
-                                 (double)f.out_bytes * ceil_div(f.Cp, TC);
-            const double cost = bytes * (1.0 + 1e-4 * (TC + TK));
+            const int n_ct = ceil_div(f.Cp, TC), n_kt = ceil_div(f.Kp, TK);
+            const double staged = (double)f.in_bytes / d.stride * n_kt + (double)f.out_bytes * n_ct;
+            const double copies = 2.0 * std::max(1, 256 / (n_ct * n_kt)) * (double)f.dwt_bytes;
+            const double cost = (0.5 * staged + copies) * (1.0 + 1e-4 * (TC + TK));
             if (!have || cost < best) { rv = c; best = cost; have = true; }
+        }
+        // (a tuning aid: CONVMI_UPD_FLAT="wc,wk,wp,fc,fk" asks for one variant)
+        if (const char *env = getenv("CONVMI_UPD_FLAT")) {
+            UpdRowsVariant c{1, 1, 0, 0, 0, 0, 0};
+            if (sscanf(env, "%d,%d,%d,%d,%d", &c.wc, &c.wk, &c.wp, &c.fc, &c.fk) == 5 &&
+                upd_bf16_1x1_variant_exists(c)) {
+                rv = c;
+                have = true;
+            }
         }
         if (have) {
             const int TC = rv.wc * rv.fc * 32, TK = rv.wk * rv.fk * 32, BP = 64;

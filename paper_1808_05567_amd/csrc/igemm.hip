@@ -93,6 +93,8 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 4, 1, 1, 2, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 8, 1, 1, 2, 2),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 2, 4, 4, 1, 1, 1, 2),
+    // (eight planes per step: for plans of at most one workgroup per CU, see plan_igemm_tile)
+    IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 8, 1, 1, 1, 2),
     // 3x3: 128 x 512 tiles
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 3),
     IGEMM_ENTRY(CONV_BF16, 2, 4, 2, 4, 2, 3, 3, 4),
