@@ -41,6 +41,8 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY(CONV_F32, 2, 2, 1, 7, 2, 4, 4, 4),
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 2, 4, 4, 6),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 2, 4, 4, 6),
+    // (eight pixel waves, 32 x 1792)
+    IGEMM_ENTRY(CONV_BF16, 1, 8, 1, 7, 2, 4, 4, 9),
     // (an odd number of channel blocks of dO: one block per step)
     IGEMM_ENTRY(CONV_F32, 1, 4, 1, 7, 1, 4, 4, 6),
     IGEMM_ENTRY(CONV_BF16, 1, 4, 1, 7, 1, 4, 4, 6),
@@ -83,15 +85,11 @@ static IgemmEntry g_igemm[] = {
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 4, 1, 1, 1, 3),
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 1, 7, 4, 1, 1, 2, 3),
     // bf16, eight waves (two per SIMD inside one workgroup, 128 accumulator registers each)
-    // 1x1: 256 x 256 and 128 x 512 tiles, two or four MFMA rounds per step
-    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 3),
-    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 4, 2, 4, 1, 1, 1, 3),
-    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 4),
-    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 4, 1, 1, 1, 5),
+    // 1x1: 256 x 256 tiles, four MFMA rounds per step.  (Measured and dropped: two rounds per
+    // step with rings of three to five buffers, 128 x 512 tiles, a 256 x 256 tile on four waves,
+    // and eight-wave fp32 tiles: none faster on any Table I layer.)
     IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 2),
-    IGEMM_ENTRY_NB(CONV_BF16, 4, 2, 2, 4, 8, 1, 1, 1, 3),
-    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 4, 1, 1, 2, 3),
-    IGEMM_ENTRY_NB(CONV_BF16, 2, 4, 2, 4, 8, 1, 1, 2, 2),
+    // 1x1, four waves, 128 x 256: two workgroups per CU where the reduction is short
     IGEMM_ENTRY_NB(CONV_BF16, 2, 2, 2, 4, 4, 1, 1, 1, 2),
     // (eight planes per step: for plans of at most one workgroup per CU, see plan_igemm_tile)
     IGEMM_ENTRY_NB(CONV_BF16, 4, 1, 1, 7, 8, 1, 1, 1, 2),
