@@ -207,8 +207,53 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128 
     const int wave_chunk = wave * 64;
     const int grp = wave >> 2;               // staging group of this wave
     const int grp_chunk = (wave & 3) * 64;   // its first chunk within the group's share
-    // ---- per-thread source byte offsets of the staged input pixels (plane 0)
-    unsigned g_off[PPT];
+    const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
+    const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
+    const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
+    const rsrc_t rsrc_wt = make_rsrc(a.wt, 0, wt_bytes);
+    unsigned g_off[PPT];  // per-thread source byte offsets of the staged input pixels (plane 0)
+    unsigned w_off[WPT];  // ... and of the staged weights (channel block 0)
+    // Load number l of a step: the input loads (plane-major) come first, then the weights.
+    constexpr int NLOADS = NPLG * PPT + WPT;
+    auto fetch_one = [&](int st, int l) {
+        // (the workgroup's reduction starts at step rot and wraps round: see IgemmArgs::rot_k)
+        int sr = st + rot;
+        if (sr >= nst) sr -= nst;
+        const int cb0 = (sbeg + sr) * NPL;
+        unsigned char *wb = lds + (st % NB) * bufbytes;
+        unsigned char *ib = wb + WBYTES;
+        if (l < NPLG * PPT) {
+            const int j = l / PPT, i = l - j * PPT;
+            const int pl = grp * NPLG + j;
+            load_to_lds_16<NTI ? 2 : 0>(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
+                           ib + (pl * a.PLS + min(i * 256 + grp_chunk, a.PLS - 64)) * 16);
+        } else {
+            const int i = l - NPLG * PPT;
+            load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
+                           wb + min(i * NT + wave_chunk, WCH - 64) * 16);
+        }
+    };
+    auto fetch = [&](int st) {
+#pragma unroll
+        for (int l = 0; l < NLOADS; ++l) fetch_one(st, l);
+    };
+    // The offsets are formed once per tile, and each load of the tile's FIRST step goes out as
+    // soon as its offset is known: the weights first (their offsets are the cheaper ones), so
+    // that the first bytes are on their way while the rest of the address arithmetic runs (a
+    // tall filter's tile has nine to twelve input positions per thread, 2 - 3 us of it).
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        const int w = min(i * NT + wave_chunk, WCH - 64) + lane;
+        unsigned off = kOutOfRange;
+        const int e = w / TK;
+        const int k = w - e * TK;
+        const int tap = e / NPL;
+        const int pl = e - tap * NPL;
+        if (tap < NTAPS && k0 + k < a.Kp)
+            off = (unsigned)(mul24(pl * NTAPS + tap, a.Kp) + k0 + k) * 16u;
+        w_off[i] = off;
+        fetch_one(0, NPLG * PPT + i);
+    }
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
         const int p = min(i * 256 + grp_chunk, a.PLS - 64) + lane;
@@ -234,50 +279,9 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128 
             if (ok) off = (unsigned)(mul24(mul24(mul24(n, a.Cb), a.H) + ih, a.W) + iw) * 16u;
         }
         g_off[i] = off;
-    }
-    // ---- per-thread source byte offsets of the staged weights (channel block 0)
-    unsigned w_off[WPT];
 #pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-        const int w = min(i * NT + wave_chunk, WCH - 64) + lane;
-        unsigned off = kOutOfRange;
-        const int e = w / TK;
-        const int k = w - e * TK;
-        const int tap = e / NPL;
-        const int pl = e - tap * NPL;
-        if (tap < NTAPS && k0 + k < a.Kp)
-            off = (unsigned)(mul24(pl * NTAPS + tap, a.Kp) + k0 + k) * 16u;
-        w_off[i] = off;
+        for (int j = 0; j < NPLG; ++j) fetch_one(0, j * PPT + i);
     }
-
-    const size_t in_bytes = (size_t)a.N * a.Cb * HW * 16;
-    const size_t wt_bytes = (size_t)a.Cb * NTAPS * a.Kp * 16;
-    const rsrc_t rsrc_in = make_rsrc(a.in, 0, in_bytes);
-    const rsrc_t rsrc_wt = make_rsrc(a.wt, 0, wt_bytes);
-    // Load number l of a step: the input loads (plane-major) come first, then the weights.
-    constexpr int NLOADS = NPLG * PPT + WPT;
-    auto fetch_one = [&](int st, int l) {
-        // (the workgroup's reduction starts at step rot and wraps round: see IgemmArgs::rot_k)
-        int sr = st + rot;
-        if (sr >= nst) sr -= nst;
-        const int cb0 = (sbeg + sr) * NPL;
-        unsigned char *wb = lds + (st % NB) * bufbytes;
-        unsigned char *ib = wb + WBYTES;
-        if (l < NPLG * PPT) {
-            const int j = l / PPT, i = l - j * PPT;
-            const int pl = grp * NPLG + j;
-            load_to_lds_16<NTI ? 2 : 0>(rsrc_in, g_off[i], (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
-                           ib + (pl * a.PLS + min(i * 256 + grp_chunk, a.PLS - 64)) * 16);
-        } else {
-            const int i = l - NPLG * PPT;
-            load_to_lds_16(rsrc_wt, w_off[i], (unsigned)cb0 * (unsigned)(NTAPS * a.Kp) * 16u,
-                           wb + min(i * NT + wave_chunk, WCH - 64) * 16);
-        }
-    };
-    auto fetch = [&](int st) {
-#pragma unroll
-        for (int l = 0; l < NLOADS; ++l) fetch_one(st, l);
-    };
     // All of this wave's staging loads have landed in LDS and all of its LDS reads are done.
     auto staged = [&]() { wait_all_memory(); };
 
@@ -315,8 +319,8 @@ __global__ __launch_bounds__(WK *WM * 64, ((WK * WM == 4 && FK * FM * 16 <= 128 
 #pragma unroll
             for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
 
-    // the first NB-1 steps' loads; step 0 must have landed before anyone reads it
-    fetch(0);
+    // (step 0's loads went out above) the other steps of the first NB-1; step 0 must have
+    // landed before anyone reads it
 #pragma unroll
     for (int d = 1; d < NB - 1; ++d)
         if (d < nst) fetch(d);
