@@ -29,6 +29,10 @@ import os
 import sys
 import time
 
+# (kernel arguments in device memory: see paper_1808_05567_amd/__init__.py; set before the HIP
+# runtime initialises, unless the environment says otherwise)
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -523,7 +527,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": head, "data": "synthetic",
         "config": {"workload": "%s, layers %s (%d layers), N=%d, %s, fwd+bwd_data+upd per layer, "
                                "blocked tensors resident in HBM" % (wname, args.layers, len(ids), N, head),
-                   "pct_of_mfma_peak": h["pct_of_mfma_peak"], "per_class": h["per_class"]},
+                   "pct_of_mfma_peak": h["pct_of_mfma_peak"], "per_class": h["per_class"],
+                   "runtime_env": {"HIP_FORCE_DEV_KERNARG": os.environ.get("HIP_FORCE_DEV_KERNARG")}},
         "roofline": h["roofline"],
     }
     for d in dtypes[1:]:
