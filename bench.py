@@ -12,7 +12,9 @@ ResNet-50 layers of Table I at N = 256 (the four 3x3 layers, the fifteen 1x1
 layers and the 7x7 first layer), seeded synthetic inputs.  With no --dtype the
 run times that workload twice: in fp32 (the headline: value, ms_per_step,
 roofline, cpu_baseline) and in bf16 (the "bf16" object of the same line); both
-carry per-class (3x3 / 1x1 / conv1) rates per pass.  "measured_ceilings" holds
+carry per-class (3x3 / 1x1 / conv1) rates per pass (timed in a separate pass after
+the clock has stopped: events around all 60 calls of a step cost 0.45 ms of stream
+time, so the timed steps bracket the forward launches only).  "measured_ceilings" holds
 what this device sustains on an MFMA issue loop, a 1 GiB copy and an L2 -> LDS
 streaming loop.  Prints ONE JSON line.
 
@@ -248,53 +250,75 @@ def bound_calls(layers):
     return calls
 
 
+DETAIL_STEPS = 10
+
+
 def time_workload(layers, N, steps, warmup):
-    """W untimed steps, then exactly K timed steps between two synchronisations; every launch
-    sits between two events on the stream the kernels run on (torch's current stream is the
-    one handed to the library).  Returns wall seconds and the mean duration (ms) per
-    (layer id, pass)."""
+    """W untimed steps, then exactly K timed steps between two synchronisations.  In the timed
+    steps only the launches of the dominant kernel (the forward launches) sit between two events
+    on the stream the kernels run on (torch's current stream is the one handed to the library):
+    an event record costs about 4 us of stream time, and a pair around each of the 60 calls of
+    a step is 0.45 ms, a tenth of a bf16 step.  The durations of the other passes come from a
+    separate pass of DETAIL_STEPS steps after the clock has stopped, with a pair around every
+    launch.  Returns wall seconds, the mean forward durations (ms) of the timed steps per layer
+    id, and the mean durations per (layer id, pass) of the detail pass."""
     import torch
 
     calls = bound_calls(layers)
-    # events are created (and recorded once, which is what allocates them) before the clock starts
-    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
-           for _ in range(steps)]
-    for row in evs:
-        for a, b in row:
-            a.record()
-            b.record()
+
+    def new_events(n_steps, which):
+        evs = [{i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                for i, c in enumerate(calls) if c[1] in which} for _ in range(n_steps)]
+        # (recorded once, which is what allocates them, before any clock starts)
+        for row in evs:
+            for a, b in row.values():
+                a.record()
+                b.record()
+        return evs
+
+    def run(evs):
+        for row in evs:
+            for i, (_, _, fn, args) in enumerate(calls):
+                pair = row.get(i)
+                if pair:
+                    pair[0].record()
+                rc = fn(*args)
+                if pair:
+                    pair[1].record()
+                if rc != 0:
+                    raise RuntimeError("conv call failed with status %d" % rc)
+
+    def means(evs):
+        return {(calls[i][0], calls[i][1]): sum(row[i][0].elapsed_time(row[i][1]) for row in evs) / len(evs)
+                for i in evs[0]}
+
+    evs = new_events(steps, ("fwd",))
     for _ in range(warmup):
         for _, _, fn, args in calls:
             assert fn(*args) == 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(steps):
-        row = evs[k]
-        for i, (_, _, fn, args) in enumerate(calls):
-            a, b = row[i]
-            a.record()
-            rc = fn(*args)
-            b.record()
-            if rc != 0:
-                raise RuntimeError("conv call failed with status %d" % rc)
+    run(evs)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per = {}
-    for i, (lid, which, _, _) in enumerate(calls):
-        per[(lid, which)] = sum(evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(steps)) / steps
-    return wall, per
+    fwd = means(evs)
+    evs = new_events(DETAIL_STEPS, PASSES)
+    torch.cuda.synchronize()
+    run(evs)
+    torch.cuda.synchronize()
+    return wall, fwd, means(evs)
 
 
-def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
+def summarize(layers, N, dtype_name, wall, fwd, per, steps, traffic_file):
     """Whole-workload rate, per-class rates and the roofline block of the dominant kernel."""
     peak = MFMA_PEAK[dtype_name]
     flops_step = sum(3 * l.flops(N) for l, _ in layers)
     ms_per_step = wall * 1e3 / steps
     value = flops_step / (wall / steps) / 1e12
 
-    def rate(ls, which):
+    def rate(ls, which, src=None):
         fl = sum(l.flops(N) for l in ls)
-        ms = sum(per[(l.id, which)] for l in ls)
+        ms = sum((src or per)[(l.id, which)] for l in ls)
         return fl / (ms * 1e-3) / 1e12
 
     per_class = {}
@@ -308,10 +332,10 @@ def summarize(layers, N, dtype_name, wall, per, steps, traffic_file):
                           "tflops": round(allp, 2), "pct_of_mfma_peak": round(100 * allp / peak, 1)}
     # Dominant kernel: the implicit-GEMM kernel (for a first layer its resident-filter form:
     # the same tiles and MFMA layout).  A forward launch is exactly one launch of it,
-    # so the forward events are its launch durations: achieved = algorithmic flops of the
-    # forward launches / their summed duration.
+    # so the forward events of the timed steps are its launch durations: achieved =
+    # algorithmic flops of the forward launches / their summed duration.
     all_l = [l for l, _ in layers]
-    achieved = rate(all_l, "fwd")
+    achieved = rate(all_l, "fwd", fwd)
     # HBM bytes per implicit-GEMM launch (forward and backward launches together: the counter
     # run cannot tell them apart), from the committed rocprofv3 counter summary of this same
     # workload; null when there is none.
@@ -511,11 +535,11 @@ def main():
     wname = "ResNet-50 Table I" if args.workload == "resnet50" else "Inception-v3 (distinct shapes)"
     summ, pers = {}, {}
     for d in dtypes:
-        wall, per = time_workload(sets[d], N, args.steps, args.warmup)
+        wall, fwd, per = time_workload(sets[d], N, args.steps, args.warmup)
         tf = None
         if args.workload == "resnet50" and N == N_BATCH and (args.layers, d) in TRAFFIC_FILE:
             tf = os.path.join(ROOT, "profiles", TRAFFIC_FILE[(args.layers, d)])
-        summ[d] = summarize(sets[d], N, d, wall, per, args.steps, tf)
+        summ[d] = summarize(sets[d], N, d, wall, fwd, per, args.steps, tf)
         pers[d] = per
 
     h = summ[head]
@@ -528,6 +552,10 @@ def main():
         "config": {"workload": "%s, layers %s (%d layers), N=%d, %s, fwd+bwd_data+upd per layer, "
                                "blocked tensors resident in HBM" % (wname, args.layers, len(ids), N, head),
                    "pct_of_mfma_peak": h["pct_of_mfma_peak"], "per_class": h["per_class"],
+                   "timing": "value and ms_per_step: the K timed steps, with an event pair around the "
+                             "forward launches only (roofline.achieved); per_class and per_pass figures: a "
+                             "separate pass of %d steps with an event pair around every launch (an event "
+                             "record costs about 4 us of stream time)" % DETAIL_STEPS,
                    "runtime_env": {"HIP_FORCE_DEV_KERNARG": os.environ.get("HIP_FORCE_DEV_KERNARG")}},
         "roofline": h["roofline"],
     }
