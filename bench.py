@@ -261,7 +261,8 @@ def time_workload(layers, N, steps, warmup):
     a step is 0.45 ms, a tenth of a bf16 step.  The durations of the other passes come from a
     separate pass of DETAIL_STEPS steps after the clock has stopped, with a pair around every
     launch.  Returns wall seconds, the mean forward durations (ms) of the timed steps per layer
-    id, and the mean durations per (layer id, pass) of the detail pass."""
+    id, the mean durations per (layer id, pass) of the detail pass, and the shader clock the
+    compute units ran at during a step (sampled afterwards, next to three more steps)."""
     import torch
 
     calls = bound_calls(layers)
@@ -306,7 +307,55 @@ def time_workload(layers, N, steps, warmup):
     torch.cuda.synchronize()
     run(evs)
     torch.cuda.synchronize()
-    return wall, fwd, means(evs)
+
+    def one_step():
+        for _, _, fn, args in calls:
+            fn(*args)
+    clock = shader_clock_under(one_step, wall * 1e3 / steps)
+    return wall, fwd, means(evs), clock
+
+
+_SIDE_STREAM = None
+
+
+def shader_clock_under(work, work_ms):
+    """Shader clock (MHz; median, lowest and highest of the 8 XCDs) while `work` keeps the
+    device busy: one sleeping wave per XCD on a second stream counts shader cycles against the
+    constant 100 MHz clock (conv_ceiling_shader_clock).  `work` (work_ms of device time) is
+    queued n times back to back, n - 2 of them at least a millisecond; the window is 0.8 of
+    those n - 2, begins while the first is under way and ends before the last does (short
+    kernels: the gaps between launches are inside the window, a few per cent of it).  Not part
+    of any timed region: the eight waves take a register-file share on eight CUs.  None if no
+    second stream could be made to run next to the work."""
+    import math
+    import torch
+    from paper_1808_05567_amd import conv
+    global _SIDE_STREAM
+    ticks = torch.zeros(16, dtype=torch.int64, device="cuda")
+    n = max(1, int(math.ceil(1.0 / max(work_ms, 1e-3))))
+    # The runtime maps streams onto a few hardware queues; a second stream that shares the main
+    # stream's queue runs behind the work instead of next to it.  Keep the first stream whose
+    # sampler demonstrably ended before the work did.
+    for attempt in range(8):
+        side = _SIDE_STREAM or torch.cuda.Stream()
+        e_side, e_main = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        work()
+        conv.conv_ceiling_shader_clock(8, min(1000000, max(50, int(n * work_ms * 800))), ticks, stream=side)
+        e_side.record(side)
+        for _ in range(n + 1):
+            work()
+        e_main.record()
+        torch.cuda.synchronize()
+        if e_side.elapsed_time(e_main) > 0:
+            _SIDE_STREAM = side
+            break
+        _SIDE_STREAM = None
+    else:
+        return None
+    t = ticks.cpu().view(8, 2).double()
+    mhz = sorted((t[:, 0] / (t[:, 1] / 100.0)).tolist())
+    return {"median": round(0.5 * (mhz[3] + mhz[4])), "min": round(mhz[0]), "max": round(mhz[-1])}
 
 
 def summarize(layers, N, dtype_name, wall, fwd, per, steps, traffic_file):
@@ -389,6 +438,17 @@ def measure_ceilings():
         it = iters if dt == conv.CONV_BF16 else iters // 2
         s = timed(lambda: conv.conv_ceiling_mfma(dt, blocks, it, sink))
         out[name] = round(blocks * 4 * it * 8 * 2 * 32 * 32 * k / s / 1e12, 1)
+        # the same loop kept up for a tenth of a second (the short run above ends before power
+        # management has settled), and the shader clock meanwhile
+        reps = max(1, int(0.03 / s))
+
+        def burst():
+            for _ in range(reps):
+                conv.conv_ceiling_mfma(dt, blocks, it, sink)
+        s = timed(burst, reps=3) / reps
+        out[name.replace("_tflops", "_sustained_tflops")] = round(
+            blocks * 4 * it * 8 * 2 * 32 * 32 * k / s / 1e12, 1)
+        out[name.replace("_tflops", "_sustained_shader_clock_mhz")] = shader_clock_under(burst, s * reps * 1e3)
     src = torch.empty(CALIB_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty_like(src)
     s = timed(lambda: conv.conv_ceiling_copy(dst, src, CALIB_BYTES))
@@ -427,7 +487,9 @@ def measure_ceilings():
                    "workgroups of 4 waves streaming 96 KiB windows that hit the L2 but not the "
                    "32 KiB L1, with loads that write into LDS or through registers; beyond L2: "
                    "the same with more windows per XCD than its L2 holds; LDS reads: one workgroup "
-                   "of 8 waves per CU, eight 16-byte reads per lane in flight")
+                   "of 8 waves per CU, eight 16-byte reads per lane in flight; shader clock: one "
+                   "sleeping wave per XCD on a second stream counting shader cycles against the "
+                   "100 MHz clock while the loop runs (the published peaks assume 2400 MHz)")
     return out
 
 
@@ -535,11 +597,12 @@ def main():
     wname = "ResNet-50 Table I" if args.workload == "resnet50" else "Inception-v3 (distinct shapes)"
     summ, pers = {}, {}
     for d in dtypes:
-        wall, fwd, per = time_workload(sets[d], N, args.steps, args.warmup)
+        wall, fwd, per, clock = time_workload(sets[d], N, args.steps, args.warmup)
         tf = None
         if args.workload == "resnet50" and N == N_BATCH and (args.layers, d) in TRAFFIC_FILE:
             tf = os.path.join(ROOT, "profiles", TRAFFIC_FILE[(args.layers, d)])
         summ[d] = summarize(sets[d], N, d, wall, fwd, per, args.steps, tf)
+        summ[d]["shader_clock_mhz_during_step"] = clock
         pers[d] = per
 
     h = summ[head]
@@ -552,6 +615,7 @@ def main():
         "config": {"workload": "%s, layers %s (%d layers), N=%d, %s, fwd+bwd_data+upd per layer, "
                                "blocked tensors resident in HBM" % (wname, args.layers, len(ids), N, head),
                    "pct_of_mfma_peak": h["pct_of_mfma_peak"], "per_class": h["per_class"],
+                   "shader_clock_mhz_during_step": h["shader_clock_mhz_during_step"],
                    "timing": "value and ms_per_step: the K timed steps, with an event pair around the "
                              "forward launches only (roofline.achieved); per_class and per_pass figures: a "
                              "separate pass of %d steps with an event pair around every launch (an event "
@@ -565,6 +629,7 @@ def main():
                      "value": summ[d]["value"], "unit": "TFLOP/s", "ms_per_step": summ[d]["ms_per_step"],
                      "steps": args.steps, "warmup": args.warmup,
                      "pct_of_mfma_peak": summ[d]["pct_of_mfma_peak"], "per_class": summ[d]["per_class"],
+                     "shader_clock_mhz_during_step": summ[d]["shader_clock_mhz_during_step"],
                      "roofline": summ[d]["roofline"]}
     if ceilings:
         result["measured_ceilings"] = ceilings
@@ -586,7 +651,8 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
     """Per layer and pass: the cycling loop's duration (operands evicted from the 256 MB
     last-level cache between launches: cold), the same launch repeated back to back (warm),
     % of the published MFMA peak, % of the layer's own ceiling min(MFMA peak, AI x HBM rate)
-    at the published figures and at the measured ones."""
+    at the published figures and at the measured ones, and the shader clock the compute units
+    ran at while the launch was repeated (the peaks assume 2400 MHz)."""
     import torch
     from paper_1808_05567_amd import conv as _conv
     es = 2 if dtype_name == "bf16" else 4
@@ -594,7 +660,7 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
     m_peak = (ceilings or {}).get("mfma_%s_tflops" % dtype_name)
     m_rd = (ceilings or {}).get("hbm_read_tbps")
     m_wr = (ceilings or {}).get("hbm_write_tbps")
-    warm = {}
+    warm, clk = {}, {}
     for l, L in layers:
         for which in PASSES:
             launch(L, which)
@@ -608,6 +674,9 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
                 evs.append((a0, a1))
             torch.cuda.synchronize()
             warm[(l.id, which)] = sum(x.elapsed_time(y) for x, y in evs) / len(evs)
+            # the shader clock while this kernel runs (back to back, a window inside the middle launch)
+            c = shader_clock_under(lambda: launch(L, which), warm[(l.id, which)])
+            clk[(l.id, which)] = c["median"] if c else 0
 
     def row(l, which, ms, by, extra=None, wr=None):
         tf = l.flops(N) / (ms * 1e-3) / 1e12
@@ -632,7 +701,7 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
     for l, L in layers:
         for which in PASSES:
             rows.append(row(l, which, per[(l.id, which)], algorithmic_bytes(l, N, es, which),
-                            {"ms_warm": round(warm[(l.id, which)], 4)}))
+                            {"ms_warm": round(warm[(l.id, which)], 4), "shader_clock_mhz": clk[(l.id, which)]}))
     # forward pass with bias + residual + ReLU fused into its store, timed on its own
     # (dy_blk, a tensor of the output's shape, stands in for the residual)
     for l, L in layers:
@@ -681,7 +750,7 @@ def layer_table(args, layers, N, dtype_name, per, ceilings):
         print("# %-4s L%-2d %-10s %8.3f ms %8.2f TF/s %5.1f%% peak %5.1f%% of ceiling%s %7.1f GB/s%s" % (
             dtype_name, r["layer"], r["pass"], r["ms"], r["tflops"], r["pct_mfma_peak"], r["pct_ceiling"],
             " (%5.1f%% of measured)" % r["pct_measured_ceiling"] if "pct_measured_ceiling" in r else "",
-            r["alg_GBps"], "  warm %8.3f ms" % r["ms_warm"] if "ms_warm" in r else ""),
+            r["alg_GBps"], "  warm %8.3f ms  %4d MHz" % (r["ms_warm"], r["shader_clock_mhz"]) if "ms_warm" in r else ""),
             file=sys.stderr)
 
 

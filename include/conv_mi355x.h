@@ -271,6 +271,14 @@ conv_status_t conv_describe(conv_handle_t h, int32_t pass, char *buf, size_t buf
  *   i of a tile whose rows of row_len pixels lie row_pitch chunks apart (the operand read
  *   over a staged tile with a halo: pitch = row_len + S - 1), at most 2 KiB per wave.
  *   Bytes read = blocks * 512 * iters * 8 * 16.  sink: device, blocks * 512 floats.
+ * conv_ceiling_shader_clock: `blocks` (1..256) workgroups of one wave each wait for
+ *   duration_us (1..1000000) microseconds of the constant 100 MHz clock, asleep most of the
+ *   time, and report the shader-clock cycles that went by: ticks[2*b] = cycles, ticks[2*b+1] =
+ *   100 MHz ticks, for workgroup b (consecutive workgroups go to consecutive XCDs).  Launched
+ *   on a second stream next to other work, it says at which clock the compute units ran under
+ *   that load (the published peaks assume 2.4 GHz).  ticks: device, 2 * blocks int64, written
+ *   once; the wave holds no LDS and a handful of registers, and ends after a bounded number of
+ *   iterations whatever the clocks do.
  * Errors: CONV_EINVAL for a NULL or misaligned pointer or a count < 1, CONV_EUNSUPPORTED
  * beyond the stated sizes, CONV_ELAUNCH if the runtime refuses the launch. */
 conv_status_t conv_ceiling_mfma(int32_t dtype, int32_t blocks, int32_t iters, float *sink,
@@ -283,6 +291,8 @@ conv_status_t conv_ceiling_l2_to_lds(const void *src, size_t src_bytes, int32_t 
                                      void *stream);
 conv_status_t conv_ceiling_lds_read(int32_t blocks, int32_t iters, int32_t row_len,
                                     int32_t row_pitch, float *sink, void *stream);
+conv_status_t conv_ceiling_shader_clock(int32_t blocks, int32_t duration_us, int64_t *ticks,
+                                        void *stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ EXPORTS = (
     "conv_unpack_in", "conv_unpack_out", "conv_unpack_wt", "conv_unpack_dwt",
     "conv_describe",
     "conv_ceiling_mfma", "conv_ceiling_copy", "conv_ceiling_read", "conv_ceiling_write",
-    "conv_ceiling_l2_to_lds", "conv_ceiling_lds_read",
+    "conv_ceiling_l2_to_lds", "conv_ceiling_lds_read", "conv_ceiling_shader_clock",
 )
 
 
@@ -97,6 +97,7 @@ def load():
     lib.conv_ceiling_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            vp, vp]
     lib.conv_ceiling_lds_read.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.conv_ceiling_shader_clock.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.conv_bwd_data_noalloc.argtypes = [vp, vp, vp, vp, vp]
     lib.conv_noalloc_scratch_bytes.argtypes = []
     lib.conv_noalloc_scratch_bytes.restype = ctypes.c_size_t
@@ -248,6 +249,12 @@ def conv_ceiling_write(dst, nbytes, stream=None):
 def conv_ceiling_lds_read(blocks, iters, sink, row_len=0, row_pitch=0, stream=None):
     _check(load().conv_ceiling_lds_read(blocks, iters, row_len, row_pitch, _ptr(sink), _stream(stream)),
            "conv_ceiling_lds_read")
+
+
+def conv_ceiling_shader_clock(blocks, duration_us, ticks, stream=None):
+    """ticks: int64 device tensor of 2 * blocks elements (cycles, 100 MHz ticks per workgroup)."""
+    _check(load().conv_ceiling_shader_clock(blocks, duration_us, _ptr(ticks), _stream(stream)),
+           "conv_ceiling_shader_clock")
 
 
 def conv_ceiling_l2_to_lds(src, src_bytes, blocks, iters, sink, through_registers=False, stream=None):

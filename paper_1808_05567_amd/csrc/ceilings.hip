@@ -166,6 +166,27 @@ __global__ __launch_bounds__(512) void lds_read_kernel(float *sink, int iters, i
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = (float)(acc & 0xFFFF);
 }
 
+// One wave per workgroup sits out `ticks_100mhz` ticks of the constant 100 MHz clock, asleep
+// most of the time, and reports how many shader-clock cycles went by meanwhile: the clock the
+// compute units really ran at while other work (on another stream) kept the device busy.  The
+// published peaks assume 2.4 GHz; power management lowers the clock under load.  The loop is
+// bounded by an iteration count as well, so the wave ends whatever the clocks do.
+__global__ __launch_bounds__(64) void shader_clock_kernel(long long *out, long long ticks_100mhz, int max_iters)
+{
+    const long long w0 = wall_clock64();
+    const long long c0 = clock64();
+    long long w = w0;
+    for (int it = 0; it < max_iters && w - w0 < ticks_100mhz; ++it) {
+        __builtin_amdgcn_s_sleep(32);
+        w = wall_clock64();
+    }
+    const long long c1 = clock64();
+    if (threadIdx.x == 0) {
+        out[2 * blockIdx.x] = c1 - c0;
+        out[2 * blockIdx.x + 1] = w - w0;
+    }
+}
+
 }  // namespace
 }  // namespace convmi
 
@@ -241,6 +262,17 @@ conv_status_t conv_ceiling_lds_read(int32_t blocks, int32_t iters, int32_t row_l
         return CONV_EINVAL;
     hipLaunchKernelGGL(lds_read_kernel, dim3(blocks), dim3(512), 65536, (hipStream_t)stream, sink, iters,
                        row_len, row_pitch);
+    return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
+}
+
+conv_status_t conv_ceiling_shader_clock(int32_t blocks, int32_t duration_us, int64_t *ticks, void *stream)
+{
+    if (!ticks || blocks < 1 || blocks > 256 || duration_us < 1 || duration_us > 1000000) return CONV_EINVAL;
+    // (a sleep of 32 x 64 cycles is about 1 us at any clock the device runs at: four times the
+    // duration in iterations is never the binding limit, and ends the loop if the clock stood still)
+    const int max_iters = 4 * duration_us + 1024;
+    hipLaunchKernelGGL(shader_clock_kernel, dim3(blocks), dim3(64), 0, (hipStream_t)stream,
+                       reinterpret_cast<long long *>(ticks), (long long)duration_us * 100, max_iters);
     return hipGetLastError() == hipSuccess ? CONV_OK : CONV_ELAUNCH;
 }
 

@@ -69,6 +69,12 @@ def test_null_and_misaligned_pointers_are_rejected_without_launch():
     buf = ctypes.create_string_buffer(256)
     assert lib.conv_describe(h, 9, buf, 256) == conv.CONV_EINVAL
     conv.conv_destroy(h)
+    # the shader-clock sampler: bounded workgroup count and duration, checked before any launch
+    assert lib.conv_ceiling_shader_clock(8, 100, None, None) == conv.CONV_EINVAL
+    assert lib.conv_ceiling_shader_clock(0, 100, 16, None) == conv.CONV_EINVAL
+    assert lib.conv_ceiling_shader_clock(257, 100, 16, None) == conv.CONV_EINVAL
+    assert lib.conv_ceiling_shader_clock(8, 0, 16, None) == conv.CONV_EINVAL
+    assert lib.conv_ceiling_shader_clock(8, 1000001, 16, None) == conv.CONV_EINVAL
 
 
 def test_every_table1_layer_is_planned():

@@ -453,3 +453,18 @@ def test_fused_forward_matches_oracle(shape, dtype):
         assert_close(got, ref, dtype, "fused in place")
     finally:
         L.close()
+
+
+@pytest.mark.gpu
+def test_shader_clock_sampler_waits_out_its_window_and_reports_a_plausible_clock():
+    """One sleeping wave per XCD counts shader cycles against the 100 MHz clock: the window it
+    reports is the one asked for (within a sleep quantum), and the clock lies between the
+    idle floor and the 2.4 GHz the peaks are quoted at (plus measurement slack)."""
+    import torch
+    ticks = torch.zeros(16, dtype=torch.int64, device="cuda")
+    conv.conv_ceiling_shader_clock(8, 2000, ticks)
+    torch.cuda.synchronize()
+    t = ticks.cpu().view(8, 2)
+    assert (t[:, 1] >= 2000 * 100).all() and (t[:, 1] < 2100 * 100).all()
+    mhz = t[:, 0].double() / (t[:, 1].double() / 100.0)
+    assert (mhz > 50).all() and (mhz < 2600).all()
