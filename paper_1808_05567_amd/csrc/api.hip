@@ -281,9 +281,19 @@ IgemmPlan plan_igemm(int dtype, int N, int Cb, int H, int W, int Kp, int P, int 
                                   oy0, ox0, zero_fill, geo);
     // One channel tile: every line of the input is staged by exactly one workgroup.  Loaded
     // non-temporally it does not displace the weights in the L2 nor settle in the last-level
-    // cache on its way past (CONVMI_IGEMM_NT=0 keeps the default policy: a tuning aid).
+    // cache on its way past.  The same with two channel tiles side by side on an XCD, as long as
+    // every XCD walks all channel tiles (one channel group): the second reader still finds the
+    // line (measured at N = 256: bf16 layer 6 forward -15 %, layer 11 backward -8 %, fp32 layers
+    // 6 and 14 backward -3 %).  With several channel groups the XCDs of the other groups fetch
+    // the same lines later, from the last-level cache: there the hint costs 8 - 17 % (layer 16).
+    // (CONVMI_IGEMM_NT: 0 never, 1 wherever the variant exists, 2 one channel tile only -- tuning aids.)
     const char *env = getenv("CONVMI_IGEMM_NT");
-    if (p.ok && p.a.n_kt == 1 && !(env && atoi(env) == 0)) {
+    const int mode = env ? atoi(env) : -1;
+    const bool want = mode == 0 ? false
+                      : mode == 1 ? true
+                      : mode == 2 ? p.a.n_kt == 1
+                                  : (p.a.n_kt == 1 || (p.a.gk == 1 && p.a.kt_per <= 2));
+    if (p.ok && want) {
         IgemmVariant v = p.v;
         v.nt = 1;
         if (igemm_variant_exists(v)) p.v = v;
