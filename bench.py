@@ -2,7 +2,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16]
                     [--workload resnet50|inception_v3] [--layers all|4,8,13,18]
-                    [--table] [--table-dir DIR] [--no-cpu] [--no-ceilings]
+                    [--table] [--table-dir DIR] [--no-cpu] [--no-ceilings] [--no-detail]
 
 A "step" is one pass of the whole hot path over one minibatch: forward,
 backward-by-data and weight update (partial + reduce) of every layer in the
@@ -61,6 +61,9 @@ def parse():
     ap.add_argument("--table-dir", default=os.path.join(ROOT, "gpurun_out"),
                     help="where --table writes layers_<workload>_<dtype>.json")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-detail", action="store_true",
+                    help="timed steps only: no separate per-pass pass, no shader-clock sampling "
+                         "(profiler runs, where every launch is counted)")
     ap.add_argument("--no-ceilings", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=0,
                     help="minibatch of the oracle's timed sample (default: sized to the workload)")
@@ -253,7 +256,7 @@ def bound_calls(layers):
 DETAIL_STEPS = 10
 
 
-def time_workload(layers, N, steps, warmup):
+def time_workload(layers, N, steps, warmup, detail=True):
     """W untimed steps, then exactly K timed steps between two synchronisations.  In the timed
     steps only the launches of the dominant kernel (the forward launches) sit between two events
     on the stream the kernels run on (torch's current stream is the one handed to the library):
@@ -303,6 +306,8 @@ def time_workload(layers, N, steps, warmup):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     fwd = means(evs)
+    if not detail:
+        return wall, fwd, None, None
     evs = new_events(DETAIL_STEPS, PASSES)
     torch.cuda.synchronize()
     run(evs)
@@ -371,7 +376,7 @@ def summarize(layers, N, dtype_name, wall, fwd, per, steps, traffic_file):
         return fl / (ms * 1e-3) / 1e12
 
     per_class = {}
-    for cls in sorted({layer_class(l) for l, _ in layers}):
+    for cls in sorted({layer_class(l) for l, _ in layers} if per else ()):
         ls = [l for l, _ in layers if layer_class(l) == cls]
         tf = {w: rate(ls, w) for w in PASSES}
         allp = sum(3 * l.flops(N) for l in ls) / (sum(per[(l.id, w)] for l in ls for w in PASSES) * 1e-3) / 1e12
@@ -400,7 +405,7 @@ def summarize(layers, N, dtype_name, wall, fwd, per, steps, traffic_file):
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "traffic": traffic,
                 "kernel": "igemm_kernel (the forward launches of the workload's layers)",
-                "per_pass_tflops": {w: round(rate(all_l, w), 2) for w in PASSES}}
+                "per_pass_tflops": {w: round(rate(all_l, w), 2) for w in PASSES} if per else None}
     es = 2 if dtype_name == "bf16" else 4
     alg = {w: sum(algorithmic_bytes(l, N, es, w) for l in all_l) for w in PASSES}
     roofline["algorithmic_bytes_per_step"] = alg
@@ -597,7 +602,7 @@ def main():
     wname = "ResNet-50 Table I" if args.workload == "resnet50" else "Inception-v3 (distinct shapes)"
     summ, pers = {}, {}
     for d in dtypes:
-        wall, fwd, per, clock = time_workload(sets[d], N, args.steps, args.warmup)
+        wall, fwd, per, clock = time_workload(sets[d], N, args.steps, args.warmup, detail=not args.no_detail)
         tf = None
         if args.workload == "resnet50" and N == N_BATCH and (args.layers, d) in TRAFFIC_FILE:
             tf = os.path.join(ROOT, "profiles", TRAFFIC_FILE[(args.layers, d)])
@@ -634,7 +639,7 @@ def main():
     if ceilings:
         result["measured_ceilings"] = ceilings
 
-    if args.table:
+    if args.table and not args.no_detail:
         for d in dtypes:
             layer_table(args, sets[d], N, d, pers[d], ceilings)
 
