@@ -646,6 +646,7 @@ bool plan_upd_c4(conv_plan *p)
             a.N = d.N; a.Cb = 1; a.H = d.H; a.W = d.W; a.Kb = f.Kb; a.Kp = f.Kp; a.P = f.P; a.Q = f.Q;
             a.R = d.R; a.S = d.S; a.stride = d.stride; a.pad = pad_h; a.pad_w = pad_w;
             a.tap0 = 0; a.ntaps_all = d.R * d.S;
+            a.live_ch = d.C;
             int TR = std::min(NP, std::max(1, 256 / Qp));
             for (;; --TR) {
                 if (TR < 1) return false;
@@ -1289,6 +1290,7 @@ conv_status_t create_plan(const conv_desc_t *desc, int32_t pad_h, int32_t pad_w,
         // A first layer (one channel block in, one reduction step, one channel tile): resident
         // workgroups that keep the filter in LDS and prefetch the next input tile.
         // (CONVMI_STEM=0 keeps one workgroup per tile: a tuning aid.)
+        p->fwd.a.live_ch = f.Cb == 1 ? std::min(d.C, vlen_of(d.dtype)) : vlen_of(d.dtype);
         p->fwd_stem_lds = 0;
         if (p->fwd.ok) {
             const char *env = getenv("CONVMI_STEM");

@@ -51,6 +51,8 @@ struct IgemmArgs {
     int LRW;       // staged tile size   (pixels) = rows * LW
     int PLS;       // LDS plane pitch    (16-byte units)
     int sampled;   // R=S=1, pad=0: stage only the pixels that are read
+    int live_ch;   // channel slots of an input block that can be non-zero: min(C, slots per block)
+                   // with one channel block, else all of them (the rest is zero padding on both sides)
     // 1.0f / P, Hs, LW, TQ for the kernel's exact small divisions (see fast_div)
     float inv_P, inv_Hs, inv_LW, inv_TQ;
     int total;     // workgroups doing work
@@ -166,6 +168,7 @@ struct UpdArgs {
     int Hs, LW, LRW, PLS_in, PLS_out;
     int sampled;
     int total, per_xcd;
+    int live_ch;     // few-channel fp32 kernel: input channels that exist (1..4)
     int runs;        // bf16 row kernel: 8-pixel runs per output row
     int Qp;          // fp32 kernel: row pitch of the staged dO band (pixels)
 };

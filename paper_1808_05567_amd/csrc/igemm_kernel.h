@@ -34,13 +34,18 @@ struct Elem<CONV_F32> {
     static constexpr int ES = 4;
     // One 16-byte operand per lane carries 4 reduction indices; lanes 0-31 and
     // 32-63 hold different channel blocks, so four 32x32x2 MFMAs consume it.
+    // NCH: channel slots of the operand's block that can be non-zero (a first layer with
+    // three channels pads the fourth slot with zeros on both sides: its MFMA adds nothing).
+    template <int NCH = 4>
     static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
     {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < NCH; ++t)
             c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[t]), __uint_as_float(b[t]),
                                                      c, 0, 0, 0);
     }
+    template <int NCH>
+    static constexpr int mfmas_per_operand = NCH;
     // Load 4 consecutive channels of one pixel (zeros if byte_off is out of range).
     static __device__ __forceinline__ void load4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
                                                  float (&x)[4])
@@ -80,11 +85,15 @@ template <>
 struct Elem<CONV_BF16> {
     static constexpr int V = 8;
     static constexpr int ES = 2;
+    // (one MFMA takes all eight channel slots of the block, live or not)
+    template <int NCH = 8>
     static __device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &c)
     {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                     __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
+    template <int NCH>
+    static constexpr int mfmas_per_operand = 1;
     static __device__ __forceinline__ void load4(rsrc_t r, unsigned byte_off, unsigned uniform_off,
                                                  float (&x)[4])
     {

@@ -33,7 +33,7 @@
 
 namespace convmi {
 
-template <int DT, int WK, int WM, int FK, int FM, int R, int S, int PPT>
+template <int DT, int WK, int WM, int FK, int FM, int R, int S, int PPT, int NCH>
 __global__ __launch_bounds__(512, 1) void igemm_stem_kernel(const IgemmArgs a)
 {
     using E_ = Elem<DT>;
@@ -193,11 +193,11 @@ __global__ __launch_bounds__(512, 1) void igemm_stem_kernel(const IgemmArgs a)
 #pragma unroll
                     for (int i = 0; i < FK; ++i)
 #pragma unroll
-                        for (int f = 0; f < FM; ++f) E_::mma(ac[i], bc[f], acc[i][f]);
+                        for (int f = 0; f < FM; ++f) E_::template mma<NCH>(ac[i], bc[f], acc[i][f]);
                     // Issue order of the round: one MFMA, then one LDS read of the next pair's
                     // operands, and so on (left to itself the compiler reads each operand
                     // right before the MFMA that takes it, and waits for it there).
-                    constexpr int NMFMA = FK * FM * (DT == CONV_F32 ? 4 : 1);
+                    constexpr int NMFMA = FK * FM * E_::template mfmas_per_operand<NCH>;
 #pragma unroll
                     for (int k = 0; k < NMFMA; ++k) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
@@ -265,25 +265,30 @@ __global__ __launch_bounds__(512, 1) void igemm_stem_kernel(const IgemmArgs a)
 namespace {
 
 struct StemEntry {
-    int dtype, wk, wm, fk, fm, r, s, ppt;
+    int dtype, wk, wm, fk, fm, r, s, ppt, nch;
     igemm_fn_t fn;
 };
-#define STEM_ENTRY(DT, WK, WM, FK, FM, R, S, PPT) \
-    {DT, WK, WM, FK, FM, R, S, PPT, igemm_stem_kernel<DT, WK, WM, FK, FM, R, S, PPT>}
+#define STEM_ENTRY(DT, WK, WM, FK, FM, R, S, PPT, NCH) \
+    {DT, WK, WM, FK, FM, R, S, PPT, NCH, igemm_stem_kernel<DT, WK, WM, FK, FM, R, S, PPT, NCH>}
 StemEntry g_stem[] = {
-    // 7x7, stride 2 over 224 x 224 (112 result columns, four result rows per tile)
-    STEM_ENTRY(CONV_F32, 2, 2, 1, 7, 7, 7, 12),
-    STEM_ENTRY(CONV_BF16, 2, 2, 1, 7, 7, 7, 12),
+    // 7x7, stride 2 over 224 x 224 (112 result columns, four result rows per tile); nch: the
+    // channel slots that get an MFMA of their own (fp32; three for an RGB input)
+    STEM_ENTRY(CONV_F32, 2, 2, 1, 7, 7, 7, 12, 3),
+    STEM_ENTRY(CONV_F32, 2, 2, 1, 7, 7, 7, 12, 4),
+    STEM_ENTRY(CONV_BF16, 2, 2, 1, 7, 7, 7, 12, 8),
 };
 
-const StemEntry *find_stem(const IgemmVariant &v)
+// The instantiation for variant v whose MFMAs cover `live_ch` channel slots with the fewest.
+const StemEntry *find_stem(const IgemmVariant &v, int live_ch)
 {
     if (v.npl != 1 || v.nb != 2) return nullptr;
+    if (live_ch <= 0) live_ch = vlen_of(v.dtype);  // (not stated: all of them)
+    const StemEntry *best = nullptr;
     for (const StemEntry &e : g_stem)
         if (e.dtype == v.dtype && e.wk == v.wk && e.wm == v.wm && e.fk == v.fk && e.fm == v.fm &&
-            e.r == v.r && e.s == v.s && e.ppt == v.ppt)
-            return &e;
-    return nullptr;
+            e.r == v.r && e.s == v.s && e.ppt == v.ppt && e.nch >= live_ch && (!best || e.nch < best->nch))
+            best = &e;
+    return best;
 }
 
 // Workgroups of `kernel` (threads, dynamic LDS) that one XCD holds at a time on the current
@@ -334,7 +339,7 @@ static IgemmArgs stem_geometry(const IgemmArgs &a)
 // plain result geometry) or no instantiation exists.
 size_t igemm_stem_lds(const IgemmVariant &v, const IgemmArgs &a)
 {
-    const StemEntry *e = find_stem(v);
+    const StemEntry *e = find_stem(v, a.live_ch);
     if (!e) return 0;
     if (a.Cb != 1 || a.n_stage != 1 || a.n_kt != 1 || a.ksplit != 1 || a.sampled || a.shuffle || a.zero_fill ||
         a.ostr != 1 || a.ostr_x != 1 || a.cstride != a.stride || a.oy0 != 0 || a.ox0 != 0 || a.gk != 1 ||
@@ -350,7 +355,7 @@ size_t igemm_stem_lds(const IgemmVariant &v, const IgemmArgs &a)
 // The launch: as many workgroups as stay resident, each walking every jstep-th tile of its XCD.
 hipError_t launch_igemm_stem(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes, hipStream_t stream)
 {
-    const StemEntry *e = find_stem(v);
+    const StemEntry *e = find_stem(v, a.live_ch);
     if (!e || a.scale || a.bias || a.resid || a.relu) return hipErrorInvalidDeviceFunction;
     const void *fn = reinterpret_cast<const void *>(e->fn);
     if (hipError_t err = ensure_dynamic_lds(fn, lds_bytes); err != hipSuccess) return err;

@@ -6,9 +6,12 @@
 //   dW[k,c,r,s] = sum over (n,oj,oi) of I[n,c,oj*stride-pad+r,oi*stride-pad+s] * dO[n,k,oj,oi]
 //
 // With so few channels the roles of Algorithm 9's small GEMM are swapped: M = output
-// channels (dO is the A operand), N = (s, c) -- the S taps of one filter row times
-// the 4 channel slots, which are S*4 consecutive floats of the staged input row --
-// and one accumulator tile per filter row r, all R rows resident in the wave.
+// channels (dO is the A operand), N = (tap, c) -- all R*S taps times the channels that
+// exist, numbered through and cut into accumulator tiles of 32 columns (7x7 and three
+// channels: 147 columns in 5 tiles; one tile per filter row with the padded fourth slot
+// in it would be 7).  A lane's column is a fixed offset from the pair's first input
+// pixel in the staged band, (r * row pitch + s) pixels and c floats on; all tiles are
+// resident in the wave.
 // Eight waves = 2 x 32 output channels x FOUR pixel groups that take alternate pixel
 // pairs of a band into private accumulators, summed through LDS after the last band
 // (the "T copies + reduction" of Section II-J inside the workgroup).  The band of the
@@ -26,14 +29,15 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // BF16IN: the tensors are bf16 in blocks of 8 channels (the input's first 4 slots are
 // used); LDS holds the same fp32 bands either way.
-template <int R, int S, bool BF16IN>
+// NTL: accumulator tiles = ceil(R * S * live channels / 32).
+template <int R, int S, bool BF16IN, int NTL>
 __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
 {
     constexpr int V = 4;
     constexpr int NTAPS = R * S;
     constexpr int NW = 8;
     constexpr int NPO = 16;  // staged dO planes: 64 output channels per workgroup
-    static_assert(S * V <= 32, "one filter row must fit the 32 columns of a fragment");
+    static_assert(NTL * 32 >= NTAPS && NTL * 32 < NTAPS * V + 32, "tiles for one to four channels");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int ibytes = a.PLS_in * 16;
@@ -181,17 +185,28 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
         }
     };
 
-    f32x16 acc[R];
+    f32x16 acc[NTL];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int t = 0; t < NTL; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[r][e] = 0.0f;
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
     // A operand: output channel wave_k*32 + l32 of the staged dO pixel
     const int k_lane = wave_k * 32 + l32;
     const int a_lane = (k_lane / V) * a.PLS_out * V + (k_lane % V);
-    // column (s, c) of the B operand = float l32 of the S*4 floats starting at the pixel
-    const int b_lane = l32 < S * V ? l32 : 0;
+    // column 32*t + l32 of the B operand = (tap, c), c < live_ch: that float of the staged band,
+    // counted from the pair's first input pixel (columns past the last tap read float 0 and
+    // are never stored)
+    const int live = a.live_ch;
+    int b_lane[NTL], b_tap[NTL];
+#pragma unroll
+    for (int t = 0; t < NTL; ++t) {
+        const int j = 32 * t + l32;
+        const int tap = j / live, c = j - tap * live;
+        const int r = tap / S, sx = tap - r * S;
+        b_tap[t] = tap < NTAPS ? tap : -1;
+        b_lane[t] = tap < NTAPS ? (r * a.LW + sx) * V + c : 0;
+    }
 
     if (rho_begin < rho_end) {
         if constexpr (BF16IN) {
@@ -228,13 +243,13 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
 #pragma unroll 2
             for (int col = 2 * wave_p + h; col < Qp; col += 8) {
                 const float av = ldsO[a_lane + (orow + col) * V];
-                float bv[R];
+                float bv[NTL];
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    bv[r] = ldsI[(irow + r * a.LW + col * a.stride) * V + b_lane];
+                for (int t = 0; t < NTL; ++t)
+                    bv[t] = ldsI[(irow + col * a.stride) * V + b_lane[t]];
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[r], acc[r], 0, 0, 0);
+                for (int t = 0; t < NTL; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[t], acc[t], 0, 0, 0);
             }
         }
         wait_all_memory();
@@ -250,10 +265,10 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
 #pragma unroll
     for (int g = 1; g < 4; ++g) {
 #pragma unroll
-        for (int r0 = 0; r0 < R; r0 += 2) {
+        for (int r0 = 0; r0 < NTL; r0 += 2) {
             if (wave_p == g) {
 #pragma unroll
-                for (int rr = 0; rr < 2 && r0 + rr < R; ++rr)
+                for (int rr = 0; rr < 2 && r0 + rr < NTL; ++rr)
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         const f32x4 v = {acc[r0 + rr][4 * vq + 0], acc[r0 + rr][4 * vq + 1],
@@ -264,7 +279,7 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
             __syncthreads();
             if (wave_p == 0) {
 #pragma unroll
-                for (int rr = 0; rr < 2 && r0 + rr < R; ++rr)
+                for (int rr = 0; rr < 2 && r0 + rr < NTL; ++rr)
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         const f32x4 v = xch[(rr * 4 + vq) * 64];
@@ -284,19 +299,23 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
     constexpr int VB = BF16IN ? 8 : 4;
     const size_t copy = (size_t)NTAPS * a.Kp * VB;
     float *dst = a.partial + (size_t)split * copy;
-    const int s = l32 / V, c = l32 % V;
     const int kbase = (BF16IN ? kbb0 * 8 : kb0 * V) + wave_k * 32;
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int t = 0; t < NTL; ++t) {
+        const int tap = b_tap[t];
+        const int c = 32 * t + l32 - tap * live;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int k = kbase + (e / 4) * 8 + h * 4 + (e % 4);
-            if (s < S && k < a.Kp) {
-                float *d = dst + ((size_t)(r * S + s) * a.Kp + k) * VB;
-                d[c] = acc[r][e];
-                if (BF16IN) d[4 + c] = 0.0f;
+            if (tap >= 0 && k < a.Kp) {
+                float *d = dst + ((size_t)tap * a.Kp + k) * VB;
+                d[c] = acc[t][e];
+                // (the lane of a tap's last channel also clears the slots behind it)
+                if (c == live - 1)
+                    for (int cc = live; cc < VB; ++cc) d[cc] = 0.0f;
             }
         }
+    }
 }
 
 hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_bytes, int grid,
@@ -305,8 +324,14 @@ hipError_t launch_upd_c4(int dtype, int r, int s, const UpdArgs &a, size_t lds_b
     typedef void (*fn_t)(const UpdArgs);
     fn_t fn = nullptr;
     const bool bf = dtype == CONV_BF16;
-    if (r == 7 && s == 7) fn = bf ? upd_c4_f32_kernel<7, 7, true> : upd_c4_f32_kernel<7, 7, false>;
-    if (r == 3 && s == 3) fn = bf ? upd_c4_f32_kernel<3, 3, true> : upd_c4_f32_kernel<3, 3, false>;
+    if (a.live_ch < 1 || a.live_ch > 4) return hipErrorInvalidValue;
+    const int ntl = (r * s * a.live_ch + 31) / 32;
+#define C4_PICK(R_, S_, NTL_) \
+    if (r == R_ && s == S_ && ntl == NTL_) \
+        fn = bf ? upd_c4_f32_kernel<R_, S_, true, NTL_> : upd_c4_f32_kernel<R_, S_, false, NTL_>;
+    C4_PICK(7, 7, 2) C4_PICK(7, 7, 4) C4_PICK(7, 7, 5) C4_PICK(7, 7, 7)
+    C4_PICK(3, 3, 1) C4_PICK(3, 3, 2)
+#undef C4_PICK
     if (!fn) return hipErrorInvalidDeviceFunction;
     if (hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void *>(fn), lds_bytes);
         err != hipSuccess)
