@@ -239,17 +239,37 @@ __global__ __launch_bounds__(512) void upd_c4_f32_kernel(const UpdArgs a)
             const int oj = rho - n * a.P;
             const int irow = (n * a.Hs + oj * a.stride - lam0) * a.LW;
             const int orow = trow * Qp;
-            // the lane halves take the two pixels of a pair, the pixel groups alternate pairs
-#pragma unroll 2
-            for (int col = 2 * wave_p + h; col < Qp; col += 8) {
-                const float av = ldsO[a_lane + (orow + col) * V];
-                float bv[NTL];
+            // The lane halves take the two pixels of a pair, the pixel groups alternate pairs.
+            // The operands of a wave's next pair are read before the MFMAs of this pair issue,
+            // one LDS read behind each MFMA (left to itself the compiler reads, waits, and only
+            // then issues the MFMAs: the matrix core idles through every LDS latency).
+            // (Qp is even: both lane halves make the same number of rounds.)
+            auto read_pair = [&](int col, float &av, float (&bv)[NTL]) {
+                av = ldsO[a_lane + (orow + col) * V];
+#pragma unroll
+                for (int t = 0; t < NTL; ++t) bv[t] = ldsI[(irow + col * a.stride) * V + b_lane[t]];
+            };
+            int col = 2 * wave_p + h;
+            float ac = 0.0f, bc[NTL];
+            if (col < Qp) read_pair(col, ac, bc);
+            for (; col < Qp; col += 8) {
+                float an = 0.0f, bn[NTL];
+#pragma unroll
+                for (int t = 0; t < NTL; ++t) bn[t] = 0.0f;
+                if (col + 8 < Qp) read_pair(col + 8, an, bn);
 #pragma unroll
                 for (int t = 0; t < NTL; ++t)
-                    bv[t] = ldsI[(irow + col * a.stride) * V + b_lane[t]];
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac, bc[t], acc[t], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
 #pragma unroll
-                for (int t = 0; t < NTL; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[t], acc[t], 0, 0, 0);
+                for (int t = 0; t < NTL; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                ac = an;
+#pragma unroll
+                for (int t = 0; t < NTL; ++t) bc[t] = bn[t];
             }
         }
         wait_all_memory();
