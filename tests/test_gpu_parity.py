@@ -59,6 +59,9 @@ FEW_CHANNELS = [
     (1, 4, 16, 8, 6, 7, 7, 2, 3),         # ... three cells per row, fewer rows than the filter
     (2, 3, 16, 12, 12, 3, 3, 1, 1),
     (2, 4, 72, 9, 9, 3, 3, 1, 1),
+    (2, 1, 32, 20, 18, 7, 7, 2, 3),       # one and two channels: the update's (tap, channel)
+    (2, 2, 48, 18, 20, 7, 7, 2, 3),       # columns fill two and four accumulator tiles
+    (3, 1, 24, 10, 10, 3, 3, 2, 1),
 ]
 
 # rectangular filters and padding given per axis (pad_h, pad_w): the factorised 7x7 and 3x3
@@ -233,7 +236,7 @@ def test_seeded_descriptor_sweep_matches_oracle(shape, dtype):
 @pytest.mark.parametrize("shape", FEW_CHANNELS, ids=lambda s: "x".join(map(str, s)))
 def test_few_channel_layers_match_oracle(shape, dtype):
     """C below the channel block: padded slots, tap pairing in the forward kernel,
-    residue-class decomposition of the strided backward pass, filter-row update
+    residue-class decomposition of the strided backward pass, (tap, channel) columns of the update
     (bf16 tensors are widened on their way into LDS there)."""
     N, C, K, H, W, R, S, stride, pad = shape
     I, Wt, dO = make_inputs(shape, dtype, layer_id=1)
