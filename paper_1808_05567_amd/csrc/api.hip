@@ -1447,7 +1447,7 @@ conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *w
     a.resid = split ? nullptr : residual;
     a.relu = split ? 0 : (relu != 0);
     hipError_t e;
-    if (h->fwd_stem_lds && !scale && !bias && !residual && !relu)
+    if (h->fwd_stem_lds)
         e = launch_igemm_stem(h->fwd.v, a, h->fwd_stem_lds, (hipStream_t)stream);
     else
         e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);

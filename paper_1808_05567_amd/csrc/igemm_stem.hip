@@ -239,6 +239,11 @@ __global__ __launch_bounds__(512, 1) void igemm_stem_kernel(const IgemmArgs a)
                                        lane_off
                                  : kOutOfRange;
                 }
+                // L() of Algorithm 4 on the finished accumulators, as in the general kernel: scale,
+                // bias, residual, ReLU.  The residual values of a row group are all requested
+                // before the first store of the group (the residual may be the output itself).
+                const bool fused = a.scale != nullptr || a.bias != nullptr || a.resid != nullptr || a.relu != 0;
+                const rsrc_t rres = make_rsrc(a.resid ? a.resid : a.out, 0, out_bytes);
 #pragma unroll
                 for (int i = 0; i < FK; ++i) {
 #pragma unroll
@@ -248,11 +253,45 @@ __global__ __launch_bounds__(512, 1) void igemm_stem_kernel(const IgemmArgs a)
                         const unsigned skip = (unsigned)(krow0 / V) * (unsigned)oplane;
                         // (fp32: the upper lane half's block may lie beyond the last channel block)
                         const bool upper_dead = (V == 4) && krow0 + 4 >= a.Kp;  // wave-uniform
+                        if (!fused) {
+#pragma unroll
+                            for (int f = 0; f < FM; ++f)
+                                E_::template store4<CONVMI_OUT_POLICY>(
+                                    ro, (upper_dead && h) ? kOutOfRange : ooff[f], skip, acc[i][f][4 * vq + 0],
+                                    acc[i][f][4 * vq + 1], acc[i][f][4 * vq + 2], acc[i][f][4 * vq + 3]);
+                            continue;
+                        }
+                        const bool rows_live = krow0 + 4 * h < a.Kp;
+                        float b4[4] = {0.f, 0.f, 0.f, 0.f}, s4[4] = {1.f, 1.f, 1.f, 1.f};
+                        if (a.bias && rows_live) {
+                            const f32x4 b = *reinterpret_cast<const f32x4 *>(a.bias + krow0 + 4 * h);
+                            b4[0] = b[0]; b4[1] = b[1]; b4[2] = b[2]; b4[3] = b[3];
+                        }
+                        if (a.scale && rows_live) {
+                            const f32x4 g = *reinterpret_cast<const f32x4 *>(a.scale + krow0 + 4 * h);
+                            s4[0] = g[0]; s4[1] = g[1]; s4[2] = g[2]; s4[3] = g[3];
+                        }
+                        float r4[FM][4];
 #pragma unroll
                         for (int f = 0; f < FM; ++f)
-                            E_::template store4<CONVMI_OUT_POLICY>(
-                                ro, (upper_dead && h) ? kOutOfRange : ooff[f], skip, acc[i][f][4 * vq + 0],
-                                acc[i][f][4 * vq + 1], acc[i][f][4 * vq + 2], acc[i][f][4 * vq + 3]);
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) r4[f][t] = 0.0f;
+                        if (a.resid) {
+#pragma unroll
+                            for (int f = 0; f < FM; ++f)
+                                E_::load4(rres, rows_live ? ooff[f] : kOutOfRange, skip, r4[f]);
+                        }
+#pragma unroll
+                        for (int f = 0; f < FM; ++f) {
+                            float o4[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                o4[t] = acc[i][f][4 * vq + t] * s4[t] + r4[f][t] + b4[t];
+                                if (a.relu) o4[t] = fmaxf(o4[t], 0.0f);
+                            }
+                            E_::template store4<CONVMI_OUT_POLICY>(ro, rows_live ? ooff[f] : kOutOfRange, skip,
+                                                                   o4[0], o4[1], o4[2], o4[3]);
+                        }
                     }
                 }
             }
@@ -356,7 +395,7 @@ size_t igemm_stem_lds(const IgemmVariant &v, const IgemmArgs &a)
 hipError_t launch_igemm_stem(const IgemmVariant &v, const IgemmArgs &a, size_t lds_bytes, hipStream_t stream)
 {
     const StemEntry *e = find_stem(v, a.live_ch);
-    if (!e || a.scale || a.bias || a.resid || a.relu) return hipErrorInvalidDeviceFunction;
+    if (!e) return hipErrorInvalidDeviceFunction;
     const void *fn = reinterpret_cast<const void *>(e->fn);
     if (hipError_t err = ensure_dynamic_lds(fn, lds_bytes); err != hipSuccess) return err;
     int resident = 0;

@@ -405,6 +405,8 @@ FUSED = [
     (2, 48, 72, 17, 17, 1, 7, 1, (0, 3)),  # rectangular filter, padding along one axis
     (2, 32, 40, 13, 13, 3, 3, 2, 0),       # unpadded stride 2
     (2, 20, 24, 9, 11, 1, 5, 1, (0, 2)),   # a filter only the direct kernel serves
+    (3, 3, 64, 40, 44, 7, 7, 2, 3),        # a first layer: operators in the resident-filter kernel's store
+    (2, 3, 40, 21, 19, 7, 7, 2, 3),        # ... with a ragged channel tile
 ]
 
 
@@ -425,6 +427,9 @@ def test_fused_forward_matches_oracle(shape, dtype):
     L = _layer(shape, dtype)
     try:
         info = conv.conv_query(L.h)
+        if C <= 4 and R == 7 and S == 7:
+            # (the first-layer cases are there for the resident-filter kernel's fused store)
+            assert "resident_filter_lds" in conv.conv_describe(L.h, 0)
         bias_dev = torch.zeros(info.Kp, dtype=torch.float32, device="cuda")
         bias_dev[:K] = torch.from_numpy(bias)
         scale = rng.uniform(0.5, 1.5, size=K).astype(np.float32) * rng.choice([-1.0, 1.0], size=K).astype(np.float32)
