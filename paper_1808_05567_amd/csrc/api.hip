@@ -1447,7 +1447,11 @@ conv_status_t conv_fwd_fused_norm(conv_handle_t h, const void *in, const void *w
     a.resid = split ? nullptr : residual;
     a.relu = split ? 0 : (relu != 0);
     hipError_t e;
-    if (h->fwd_stem_lds)
+    // (bf16 with fused operators: the resident-filter kernel's phases are a few microseconds
+    // long there, and the residual's round trips do not fit into them -- 0.49 ms against 0.38
+    // on the general kernel for layer 1 of Table I; in fp32 it is 0.64 against 0.89)
+    const bool fused_ops = scale || bias || residual || relu;
+    if (h->fwd_stem_lds && !(fused_ops && h->d.dtype == CONV_BF16))
         e = launch_igemm_stem(h->fwd.v, a, h->fwd_stem_lds, (hipStream_t)stream);
     else
         e = launch_igemm(h->fwd.v, a, h->fwd.lds, h->fwd.grid, (hipStream_t)stream);
