@@ -156,7 +156,13 @@ __global__ __launch_bounds__(512) void upd_f32_1x1_kernel(const UpdArgs a)
     __syncthreads();
     for (int band = 0; band < nbands; ++band) {
         const bool more = band + 1 < nbands;
-        if (more) fetch(band + 1);
+        // All eight waves forming addresses and issuing loads at the top of a band leaves the
+        // matrix cores idle for the 0.7 us it takes.  Half of the waves (the even ones) do it
+        // there, the others halfway through their pixel pairs, while the first half has MFMAs
+        // to issue (measured at N = 256: 256-channel tiles -4 to -5 %, the rest -1 to -2 %;
+        // odd waves first or waves 0-3 first do the same, waves 4-7 first loses 7 %).
+        const bool early = (wave & 1) == 0;
+        if (more && early) fetch(band + 1);
         const unsigned char *buf = lds + (band & 1) * BUF;
         // pixel pairs wave_p, wave_p + WP, ... of the band; the operands of the next pair are
         // read before this pair's MFMAs issue
@@ -165,6 +171,7 @@ __global__ __launch_bounds__(512) void upd_f32_1x1_kernel(const UpdArgs a)
         f32x2 bn = *reinterpret_cast<const f32x2 *>(pb);
 #pragma unroll
         for (int i = 0; i < BP / 2 / WP; ++i) {
+            if (i == BP / 4 / WP && more && !early) fetch(band + 1);
             const f32x4 av = an;
             const f32x2 bv = bn;
             if (i + 1 < BP / 2 / WP) {
