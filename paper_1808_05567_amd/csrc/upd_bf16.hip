@@ -220,7 +220,13 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 
     int step = 0;
     for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, ++step) {
-        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, (step + 1) & 1);
+        // (the even waves issue the next band's loads at the top of the band, the odd ones halfway
+        // through their run pairs)
+        bool pending = rho0 + a.TR < rho_end;
+        if (pending && (wave & 1) == 0) {
+            fetch(rho0 + a.TR, (step + 1) & 1);
+            pending = false;
+        }
         const unsigned char *ib = lds + (step & 1) * bufbytes;
         const unsigned char *ob = ib + ibytes;
 
@@ -309,9 +315,14 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         unsigned w0[R][FC][WN];
         u32x4 b0[FK];
         for (int t = wave_p; 2 * t < nruns; t += WP) {
+            if (pending && 4 * t >= nruns) {
+                fetch(rho0 + a.TR, (step + 1) & 1);
+                pending = false;
+            }
             load_pair(t, w0, b0);
             mma_pair(w0, b0);
         }
+        if (pending) fetch(rho0 + a.TR, (step + 1) & 1);
         wait_all_memory();
         __syncthreads();
     }
