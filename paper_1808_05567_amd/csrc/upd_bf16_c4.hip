@@ -166,7 +166,13 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
     __syncthreads();
     int buf = 0;
     for (int rho0 = rho_begin; rho0 < rho_end; rho0 += a.TR, buf ^= 1) {
-        if (rho0 + a.TR < rho_end) fetch(rho0 + a.TR, buf ^ 1);
+        // (the even waves issue the next band's loads at the top of the band, the odd ones halfway
+        // through their run pairs)
+        bool pending = rho0 + a.TR < rho_end;
+        if (pending && (wave & 1) == 0) {
+            fetch(rho0 + a.TR, buf ^ 1);
+            pending = false;
+        }
         const unsigned char *ib = lds + buf * bufbytes;
         const unsigned char *ob = ib + ibytes;
         const int lam0 = band_lam0(rho0);
@@ -174,6 +180,10 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
         const int nruns = rows * a.runs;
         // Pairs of 8-pixel runs: lane half h takes run 2*t + h, the pixel groups alternate t.
         for (int t = wave_p; 2 * t < nruns; t += 4) {
+            if (pending && 4 * t >= nruns) {
+                fetch(rho0 + a.TR, buf ^ 1);
+                pending = false;
+            }
             const int q = 2 * t + h;
             const bool live = q < nruns;
             const int trow = fast_div(q, inv_runs);
@@ -201,6 +211,7 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
                                                                  __builtin_bit_cast(bf16x8, bf), acc[r],
                                                                  0, 0, 0);
         }
+        if (pending) fetch(rho0 + a.TR, buf ^ 1);
         wait_all_memory();
         __syncthreads();
     }
