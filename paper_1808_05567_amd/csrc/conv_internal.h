@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "conv_mi355x.h"
 
@@ -295,6 +296,45 @@ static __device__ __forceinline__ void load_to_lds_16(rsrc_t r, unsigned byte_of
     typedef __attribute__((address_space(3))) void *lds_vptr_t;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_vptr_t)lds_wave_base, 16, byte_off, uniform_off,
                                              0, POLICY);
+}
+// Transposing 64-bit LDS reads the compiler does not track.  Before a transposing read issued
+// through its builtin the compiler waits for EVERY outstanding load of the wave, loads that
+// write straight into LDS included (it cannot tell that they fill the other buffer; before
+// ordinary LDS reads it places no such wait) -- a band's prefetch would be awaited in the
+// instruction after it was issued.  These reads are plain instructions to the compiler
+// instead: the caller waits for them with lds_reads_pending<N>() (LDS operations of a wave
+// complete in order: "at most N still pending") and then passes every register they wrote
+// through lds_read_landed(), which pins each use of the value behind that wait.
+// Within a group of 16 lanes, lane i slot j receives 16-bit element (i % 4) of the 8 bytes
+// addressed by lane 4*j + i/4.  `addr` is the LDS byte address, OFF a constant added to it.
+typedef unsigned int lds_u32x2 __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ unsigned lds_address(const unsigned char *p)
+{
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char *)p;
+}
+template <int OFF>
+static __device__ __forceinline__ lds_u32x2 lds_read_tr16_b64_untracked(unsigned addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+    lds_u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+static __device__ __forceinline__ void lds_reads_pending()
+{
+    // (the counter has four bits: a count it cannot hold waits for everything)
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N <= 15 ? N : 0));
+}
+static __device__ __forceinline__ void lds_read_landed(lds_u32x2 &v) { asm volatile("" : "+v"(v)); }
+// Compile-time loop: f(std::integral_constant<int, I>) for I in [I0, I1).
+template <int I0, int I1, class F>
+static __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
 }
 // Cache policy of the loads of the update kernels, which read both tensors exactly once:
 // non-temporal (the lines are not kept in the last-level cache and leave the L2 first).

@@ -38,15 +38,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// Transposing 64-bit LDS read: within a group of 16 lanes, lane i slot j
-// receives 16-bit element (i % 4) of the 8 bytes addressed by lane 4*j + i/4.
-static __device__ __forceinline__ u32x2 lds_read_tr16_b64(const unsigned char *p)
-{
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-    return __builtin_bit_cast(u32x2, v);
-}
-
 // STRIDED: filters larger than 1x1 with stride > 1.  Consecutive output pixels are then
 // `stride` input pixels apart, so a tap's operand is not a shifted window any more; the
 // transposing read takes a per-lane address, and the lanes of a group simply address
@@ -62,7 +53,6 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
     constexpr int NPI = TC / V;
     constexpr int NPO = TK / V;
     constexpr int WIN = (8 + S - 1 + 3) / 4;  // 4-pixel reads covering a run plus S-1 shifts
-    constexpr int WN = STRIDED ? 4 * S : 2 * WIN;  // operand dwords a lane holds per filter row
     static_assert(NT == 256 || NT == 512, "four or eight waves");
     // Two waves per SIMD need the accumulators to fit the 256 AGPRs outright:
     // above that the compiler shuttles tiles between register files every step.
@@ -236,7 +226,11 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         const int oj0 = rho0 - n0 * a.P;
         // Run pairs: lane half h takes run 2*t + h; waves along pixels interleave t.
         // (Two waves per SIMD: one wave's LDS latency hides behind the other's MFMAs.)
-        auto load_pair = [&](int t, unsigned (&w)[R][FC][WN], u32x4 (&bf)[FK]) {
+        // (The transposing reads are issued untracked -- see lds_read_tr16_b64_untracked -- so that
+        // the next band's loads, which write into the other buffer, stay in flight behind them.)
+        constexpr int PER_ROW = STRIDED ? 2 * S : WIN;  // reads per filter row and fragment
+        const unsigned ib_a = lds_address(ib), ob_a = lds_address(ob);
+        auto load_pair = [&](int t, u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2]) {
             const int q = 2 * t + h;
             const bool live = q < nruns;
             const int trow = fast_div(q, inv_runs);
@@ -254,42 +248,49 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
             const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
 #pragma unroll
             for (int j = 0; j < FK; ++j) {
-                const u32x2 lo = lds_read_tr16_b64(ob + b_lane[j] + opix);
-                const u32x2 hi = lds_read_tr16_b64(ob + b_lane[j] + opix + 4 * 16);
-                bf[j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                const unsigned p = ob_a + b_lane[j] + opix;
+                bf[j][0] = lds_read_tr16_b64_untracked<0>(p);
+                bf[j][1] = lds_read_tr16_b64_untracked<4 * 16>(p);
             }
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int i = 0; i < FC; ++i) {
+                    const unsigned p = ib_a + a_lane[i] + ipix + r * a.LW * 16;
                     if constexpr (STRIDED) {
-#pragma unroll
-                        for (int sx = 0; sx < S; ++sx) {
-                            // the 8 output pixels of the run under tap (r, sx): input pixels
-                            // stride*j + sx of the window, four per read
-                            const unsigned char *p = ib + a_lane[i] + ipix + (r * a.LW + sx) * 16;
-                            const u32x2 lo = lds_read_tr16_b64(p);
-                            const u32x2 hi = lds_read_tr16_b64(p + lst * 4 * 16);
-                            w[r][i][4 * sx + 0] = lo[0];
-                            w[r][i][4 * sx + 1] = lo[1];
-                            w[r][i][4 * sx + 2] = hi[0];
-                            w[r][i][4 * sx + 3] = hi[1];
-                        }
+                        // the 8 output pixels of the run under tap (r, sx): input pixels
+                        // stride*j + sx of the window, four per read
+                        const unsigned p2 = p + lst * 4 * 16;
+                        static_for<0, S>([&](auto sx) {
+                            constexpr int SX = decltype(sx)::value;
+                            w[r][i][2 * SX] = lds_read_tr16_b64_untracked<SX * 16>(p);
+                            w[r][i][2 * SX + 1] = lds_read_tr16_b64_untracked<SX * 16>(p2);
+                        });
                     } else {
-#pragma unroll
-                        for (int g = 0; g < WIN; ++g) {
-                            // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
-                            const u32x2 v =
-                                lds_read_tr16_b64(ib + a_lane[i] + ipix + (r * a.LW + 4 * g) * 16);
-                            w[r][i][2 * g] = v[0];
-                            w[r][i][2 * g + 1] = v[1];
-                        }
+                        // window of 4*WIN consecutive pixels of this lane's channel, 2 per dword
+                        static_for<0, WIN>([&](auto g) {
+                            constexpr int G = decltype(g)::value;
+                            w[r][i][G] = lds_read_tr16_b64_untracked<4 * G * 16>(p);
+                        });
                     }
                 }
         };
-        auto mma_pair = [&](const unsigned (&w)[R][FC][WN], const u32x4 (&bf)[FK]) {
+        auto mma_pair = [&](u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2]) {
+            static_for<0, R>([&](auto rr) {
+                constexpr int r = decltype(rr)::value;
+                // the reads of the filter rows behind this one may still be on their way
+                lds_reads_pending<(R - 1 - r) * FC * PER_ROW>();
+                if constexpr (r == 0) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+                    for (int j = 0; j < FK; ++j) {
+                        lds_read_landed(bf[j][0]);
+                        lds_read_landed(bf[j][1]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < FC; ++i)
+#pragma unroll
+                    for (int g = 0; g < PER_ROW; ++g) lds_read_landed(w[r][i][g]);
 #pragma unroll
                 for (int i = 0; i < FC; ++i)
 #pragma unroll
@@ -298,22 +299,27 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
                             if constexpr (STRIDED) {
-                                af[d] = w[r][i][4 * s + d];
+                                af[d] = w[r][i][2 * s + d / 2][d & 1];
                             } else {
                                 const int lo = d + s / 2;
-                                af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][lo + 1], w[r][i][lo], 16)
-                                                : w[r][i][lo];
+                                const unsigned w_lo = w[r][i][lo / 2][lo & 1];
+                                af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][(lo + 1) / 2][(lo + 1) & 1],
+                                                                            w_lo, 16)
+                                                : w_lo;
                             }
                         }
 #pragma unroll
-                        for (int j = 0; j < FK; ++j)
+                        for (int j = 0; j < FK; ++j) {
+                            const u32x4 bq = {bf[j][0][0], bf[j][0][1], bf[j][1][0], bf[j][1][1]};
                             acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf[j]),
+                                __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bq),
                                 acc[r * S + s][i][j], 0, 0, 0);
+                        }
                     }
+            });
         };
-        unsigned w0[R][FC][WN];
-        u32x4 b0[FK];
+        u32x2 w0[R][FC][PER_ROW];
+        u32x2 b0[FK][2];
         for (int t = wave_p; 2 * t < nruns; t += WP) {
             if (pending && 4 * t >= nruns) {
                 fetch(rho0 + a.TR, (step + 1) & 1);

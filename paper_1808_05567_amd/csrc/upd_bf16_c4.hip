@@ -33,15 +33,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// Transposing 64-bit LDS read: within a group of 16 lanes, lane i slot j receives
-// 16-bit element (i % 4) of the 8 bytes addressed by lane 4*j + i/4.
-static __device__ __forceinline__ u32x2 c4_read_tr16_b64(const unsigned char *p)
-{
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-    return __builtin_bit_cast(u32x2, v);
-}
-
 template <int R, int S>
 __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
 {
@@ -175,6 +166,7 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
         }
         const unsigned char *ib = lds + buf * bufbytes;
         const unsigned char *ob = ib + ibytes;
+        const unsigned ib_a = lds_address(ib), ob_a = lds_address(ob);
         const int lam0 = band_lam0(rho0);
         const int rows = min(a.TR, rho_end - rho0);
         const int nruns = rows * a.runs;
@@ -194,22 +186,34 @@ __global__ __launch_bounds__(512) void upd_c4_bf16_kernel(const UpdArgs a)
             const int lrow = n * a.Hs + oj * a.stride - lam0;  // staged row of tap row 0
             const int ipix = live ? (lrow * a.LW + a.stride * 8 * ri) * 16 : 0;
             const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
-            const u32x2 blo = c4_read_tr16_b64(ob + b_lane + opix);
-            const u32x2 bhi = c4_read_tr16_b64(ob + b_lane + opix + 4 * 16);
-            const u32x4 bf = {blo[0], blo[1], bhi[0], bhi[1]};
-            u32x4 af[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const unsigned char *p = ib + a_lane + ipix + r * row_bytes;
-                const u32x2 lo = c4_read_tr16_b64(p);
-                const u32x2 hi = c4_read_tr16_b64(p + a_step);
-                af[r] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            // (untracked reads: the next band's loads stay in flight behind them)
+            u32x2 bq[2], aq[R][2];
+            {
+                const unsigned p = ob_a + b_lane + opix;
+                bq[0] = lds_read_tr16_b64_untracked<0>(p);
+                bq[1] = lds_read_tr16_b64_untracked<4 * 16>(p);
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r]),
+            for (int r = 0; r < R; ++r) {
+                const unsigned p = ib_a + a_lane + ipix + r * row_bytes;
+                aq[r][0] = lds_read_tr16_b64_untracked<0>(p);
+                aq[r][1] = lds_read_tr16_b64_untracked<0>(p + a_step);
+            }
+            static_for<0, R>([&](auto rr) {
+                constexpr int r = decltype(rr)::value;
+                lds_reads_pending<2 * (R - 1 - r)>();
+                if constexpr (r == 0) {
+                    lds_read_landed(bq[0]);
+                    lds_read_landed(bq[1]);
+                }
+                lds_read_landed(aq[r][0]);
+                lds_read_landed(aq[r][1]);
+                const u32x4 af = {aq[r][0][0], aq[r][0][1], aq[r][1][0], aq[r][1][1]};
+                const u32x4 bf = {bq[0][0], bq[0][1], bq[1][0], bq[1][1]};
+                acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af),
                                                                  __builtin_bit_cast(bf16x8, bf), acc[r],
                                                                  0, 0, 0);
+            });
         }
         if (pending) fetch(rho0 + a.TR, buf ^ 1);
         wait_all_memory();
