@@ -230,7 +230,10 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
         // the next band's loads, which write into the other buffer, stay in flight behind them.)
         constexpr int PER_ROW = STRIDED ? 2 * S : WIN;  // reads per filter row and fragment
         const unsigned ib_a = lds_address(ib), ob_a = lds_address(ob);
-        auto load_pair = [&](int t, u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2]) {
+        struct PairAddr {
+            int ipix, opix;
+        };
+        auto pair_addr = [&](int t) -> PairAddr {
             const int q = 2 * t + h;
             const bool live = q < nruns;
             const int trow = fast_div(q, inv_runs);
@@ -244,19 +247,26 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                 const int dn = fast_div(oj0 + trow, inv_P);
                 lrow = trow + dn * gap;
             }
-            const int ipix = live ? (lrow * a.LW + ri * 8 * lst) * 16 : 0;
-            const int opix = live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16;  // else: the zero run
+            // (a pair beyond the band's runs reads position 0 and the zero run: valid addresses)
+            return PairAddr{live ? (lrow * a.LW + ri * 8 * lst) * 16 : 0,
+                            live ? (trow * RP + ri * 8) * 16 : a.TR * RP * 16};
+        };
+        auto read_out = [&](const PairAddr &pa, u32x2 (&bf)[FK][2]) {
 #pragma unroll
             for (int j = 0; j < FK; ++j) {
-                const unsigned p = ob_a + b_lane[j] + opix;
+                const unsigned p = ob_a + b_lane[j] + pa.opix;
                 bf[j][0] = lds_read_tr16_b64_untracked<0>(p);
                 bf[j][1] = lds_read_tr16_b64_untracked<4 * 16>(p);
             }
+        };
+        // filter rows [r0, r1) of the input operand
+        auto read_in = [&](const PairAddr &pa, int r0, int r1, u32x2 (&w)[R][FC][PER_ROW]) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r) {
+                if (r < r0 || r >= r1) continue;
 #pragma unroll
                 for (int i = 0; i < FC; ++i) {
-                    const unsigned p = ib_a + a_lane[i] + ipix + r * a.LW * 16;
+                    const unsigned p = ib_a + a_lane[i] + pa.ipix + r * a.LW * 16;
                     if constexpr (STRIDED) {
                         // the 8 output pixels of the run under tap (r, sx): input pixels
                         // stride*j + sx of the window, four per read
@@ -274,59 +284,119 @@ __global__ __launch_bounds__(WC *WK *WP * 64) void upd_rows_bf16_kernel(const Up
                         });
                     }
                 }
+            }
         };
-        auto mma_pair = [&](u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2]) {
-            static_for<0, R>([&](auto rr) {
-                constexpr int r = decltype(rr)::value;
-                // the reads of the filter rows behind this one may still be on their way
-                lds_reads_pending<(R - 1 - r) * FC * PER_ROW>();
-                if constexpr (r == 0) {
+        // The MFMAs of one filter row, once its reads (and, with the first row, dO's) have landed.
+        auto mma_row = [&](auto rr, u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2]) {
+            constexpr int r = decltype(rr)::value;
+            if constexpr (r == 0) {
+#pragma unroll
+                for (int j = 0; j < FK; ++j) {
+                    lds_read_landed(bf[j][0]);
+                    lds_read_landed(bf[j][1]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < FC; ++i)
+#pragma unroll
+                for (int g = 0; g < PER_ROW; ++g) lds_read_landed(w[r][i][g]);
+#pragma unroll
+            for (int i = 0; i < FC; ++i)
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    u32x4 af;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        if constexpr (STRIDED) {
+                            af[d] = w[r][i][2 * s + d / 2][d & 1];
+                        } else {
+                            const int lo = d + s / 2;
+                            const unsigned w_lo = w[r][i][lo / 2][lo & 1];
+                            af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][(lo + 1) / 2][(lo + 1) & 1],
+                                                                        w_lo, 16)
+                                            : w_lo;
+                        }
+                    }
 #pragma unroll
                     for (int j = 0; j < FK; ++j) {
-                        lds_read_landed(bf[j][0]);
-                        lds_read_landed(bf[j][1]);
+                        const u32x4 bq = {bf[j][0][0], bf[j][0][1], bf[j][1][0], bf[j][1][1]};
+                        acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bq),
+                            acc[r * S + s][i][j], 0, 0, 0);
                     }
                 }
-#pragma unroll
-                for (int i = 0; i < FC; ++i)
-#pragma unroll
-                    for (int g = 0; g < PER_ROW; ++g) lds_read_landed(w[r][i][g]);
-#pragma unroll
-                for (int i = 0; i < FC; ++i)
-#pragma unroll
-                    for (int s = 0; s < S; ++s) {
-                        u32x4 af;
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            if constexpr (STRIDED) {
-                                af[d] = w[r][i][2 * s + d / 2][d & 1];
-                            } else {
-                                const int lo = d + s / 2;
-                                const unsigned w_lo = w[r][i][lo / 2][lo & 1];
-                                af[d] = (s & 1) ? __builtin_amdgcn_alignbit(w[r][i][(lo + 1) / 2][(lo + 1) & 1],
-                                                                            w_lo, 16)
-                                                : w_lo;
-                            }
-                        }
-#pragma unroll
-                        for (int j = 0; j < FK; ++j) {
-                            const u32x4 bq = {bf[j][0][0], bf[j][0][1], bf[j][1][0], bf[j][1][1]};
-                            acc[r * S + s][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bq),
-                                acc[r * S + s][i][j], 0, 0, 0);
-                        }
-                    }
-            });
         };
-        u32x2 w0[R][FC][PER_ROW];
-        u32x2 b0[FK][2];
-        for (int t = wave_p; 2 * t < nruns; t += WP) {
-            if (pending && 4 * t >= nruns) {
-                fetch(rho0 + a.TR, (step + 1) & 1);
-                pending = false;
+        constexpr int ROW_READS = FC * PER_ROW;           // reads of one filter row
+        constexpr int HEAD_READS = 2 * FK + ROW_READS;    // dO's and the first filter row's
+        constexpr int PAIR_READS = 2 * FK + R * ROW_READS;
+        // The reads of the next pair go out while this pair's MFMAs issue, if the wave's counter of
+        // pending LDS operations (four bits) can hold a pair's reads.
+        constexpr bool AHEAD = !STRIDED && PAIR_READS <= 15;
+        if constexpr (AHEAD) {
+            // One pair: `w`, `bf` hold (or are about to receive) this pair's operands, all of its
+            // reads pending at most; the next pair's reads are issued into `wn`, `bn` in two parts --
+            // dO and the first filter row as soon as this pair's have landed, the other rows before
+            // the last row's MFMAs -- so that PAIR_READS are pending again when it returns.
+            auto pair_step = [&](int tn, u32x2 (&w)[R][FC][PER_ROW], u32x2 (&bf)[FK][2],
+                                 u32x2 (&wn)[R][FC][PER_ROW], u32x2 (&bn)[FK][2]) {
+                const PairAddr pn = pair_addr(tn);
+                static_for<0, R>([&](auto rr) {
+                    constexpr int r = decltype(rr)::value;
+                    lds_reads_pending<(R - 1 - r) * ROW_READS + (r > 0 ? HEAD_READS : 0)>();
+                    if constexpr (r == 0) {
+                        mma_row(rr, w, bf);  // (registers pinned first, then the MFMAs)
+                        read_out(pn, bn);
+                        read_in(pn, 0, 1, wn);
+                    } else {
+                        if constexpr (r == R - 1) read_in(pn, 1, R, wn);
+                        mma_row(rr, w, bf);
+                    }
+                });
+            };
+            int t = wave_p;
+            if (2 * t < nruns) {
+                u32x2 wa[R][FC][PER_ROW], wb[R][FC][PER_ROW];
+                u32x2 ba[FK][2], bb[FK][2];
+                {
+                    const PairAddr p0 = pair_addr(t);
+                    read_out(p0, ba);
+                    read_in(p0, 0, R, wa);
+                }
+                for (;;) {
+                    if (pending && 4 * t >= nruns) {
+                        fetch(rho0 + a.TR, (step + 1) & 1);
+                        pending = false;
+                    }
+                    pair_step(t + WP, wa, ba, wb, bb);
+                    t += WP;
+                    if (2 * t >= nruns) break;
+                    if (pending && 4 * t >= nruns) {
+                        fetch(rho0 + a.TR, (step + 1) & 1);
+                        pending = false;
+                    }
+                    pair_step(t + WP, wb, bb, wa, ba);
+                    t += WP;
+                    if (2 * t >= nruns) break;
+                }
             }
-            load_pair(t, w0, b0);
-            mma_pair(w0, b0);
+        } else {
+            u32x2 w0[R][FC][PER_ROW];
+            u32x2 b0[FK][2];
+            for (int t = wave_p; 2 * t < nruns; t += WP) {
+                if (pending && 4 * t >= nruns) {
+                    fetch(rho0 + a.TR, (step + 1) & 1);
+                    pending = false;
+                }
+                const PairAddr p0 = pair_addr(t);
+                read_out(p0, b0);
+                read_in(p0, 0, R, w0);
+                static_for<0, R>([&](auto rr) {
+                    constexpr int r = decltype(rr)::value;
+                    // the reads of the filter rows behind this one may still be on their way
+                    lds_reads_pending<(R - 1 - r) * ROW_READS>();
+                    mma_row(rr, w0, b0);
+                });
+            }
         }
         if (pending) fetch(rho0 + a.TR, (step + 1) & 1);
         wait_all_memory();

@@ -121,8 +121,10 @@ __global__ __launch_bounds__(512) void upd_f32_bands_kernel(const UpdArgs a)
                 cur = key;
                 off = is_in ? in_off(ch * 64 + lane) : out_off(ch * 64 + lane);
             }
+            // (default cache policy for the input: consecutive bands share R-1 staged rows, which
+            // the second band then finds in the L2 -- 1-2 % on the 3x3 layers; dO streams past once)
             if (is_in)
-                load_to_lds_16<CONVMI_UPD_POLICY>(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
+                load_to_lds_16<0>(rsrc_in, cb0 + pl < a.Cb ? off : kOutOfRange,
                                (unsigned)(cb0 + pl) * (unsigned)HW * 16u,
                                ib + (pl * a.PLS_in + ch * 64) * 16);
             else
